@@ -1,0 +1,332 @@
+"""Pins for the fp64 oracle: things the mathematics fixes, independent of the oracle's own code.
+
+Each test names the fact it rests on.  The paper (Background, "LLM serving systems"; Section 4,
+first paragraph) only states that partial outputs and normalizers of independent segments
+combine into the final output, so the pins are closed forms, hand-expanded tiny cases, brute
+force with a differently structured evaluator, and library routines (scipy logsumexp/softmax).
+"""
+import itertools
+import math
+
+import numpy as np
+import pytest
+from scipy.special import logsumexp, softmax
+
+from oracle import tokenlake_oracle as orc
+
+
+# ---------------------------------------------------------------------------------------
+def f64_to_bf16_bits(x):
+    """Test helper: values exactly representable in bf16 -> their bit patterns (asserts exactness)."""
+    x32 = np.asarray(x, np.float32)
+    bits = (x32.view(np.uint32) >> 16).astype(np.uint16)
+    assert np.array_equal(orc.bf16_bits_to_f64(bits), np.asarray(x, np.float64)), "value not bf16-exact"
+    return bits
+
+
+def rand_bf16_bits(rng, shape, scale=1.0):
+    x = (rng.standard_normal(shape) * scale).astype(np.float32)
+    u = x.view(np.uint32)
+    u = ((u + 0x7FFF + ((u >> 16) & 1)) >> 16).astype(np.uint16)     # round to nearest even
+    return u
+
+
+# ---------------------------------------------------------------------------------------
+def test_bf16_bit_patterns_known_values():
+    # IEEE: bf16 = sign(1) exp(8) frac(7); 0x3F80 = 1, 0xC000 = -2, 0x3FC0 = 1.5, 0x0080 = 2^-126,
+    # 0x0001 = 2^-133 (subnormal), 0x7F80 = +inf, 0x4049 = 3.140625
+    bits = np.array([0x3F80, 0xC000, 0x3FC0, 0x0080, 0x0001, 0x7F80, 0x4049, 0x0000, 0x8000], np.uint16)
+    want = [1.0, -2.0, 1.5, 2.0 ** -126, 2.0 ** -133, math.inf, 3.140625, 0.0, -0.0]
+    got = orc.bf16_bits_to_f64(bits)
+    assert got.dtype == np.float64
+    assert np.array_equal(got, np.array(want))
+    assert math.copysign(1.0, got[-1]) == -1.0
+
+
+def test_hand_expanded_three_keys():
+    """scale=1, q=(1,0), k_j=(ln a_j, .) with a=(1,2,3): softmax weights are exactly 1/6, 2/6, 3/6.
+    v_j = (6,0), (0,6), (12,-6)  ->  O = (1+0+6, 0+2-3) = (7,-1);  LSE = ln 6."""
+    q = np.array([[1.0, 0.0]])
+    k = np.array([[math.log(1.0), 5.0], [math.log(2.0), -7.0], [math.log(3.0), 11.0]])
+    v = np.array([[6.0, 0.0], [0.0, 6.0], [12.0, -6.0]])
+    o, lse = orc.attention_rows(q, k, v, 1.0)
+    assert np.allclose(o, [[7.0, -1.0]], rtol=0, atol=1e-12)
+    assert abs(lse[0] - math.log(6.0)) < 1e-12
+
+
+def test_hand_expanded_causal_eight_tokens():
+    """8 tokens, every score equal to ln 2 * 0 = 0 except key j has score ln(j+1) for every row:
+    row i sees keys 0..i, so Z_i = 1+2+..+(i+1) = (i+1)(i+2)/2 and O_i = sum_j (j+1) v_j / Z_i.
+    With v_j = j (one channel): O_i = sum_{j<=i} (j+1) j / Z_i = (i(i+1)(i+2)/3) / Z_i = 2i/3."""
+    n = 8
+    q = np.ones((n, 1))
+    k = np.log(np.arange(1, n + 1, dtype=np.float64))[:, None]
+    v = np.arange(n, dtype=np.float64)[:, None]
+    o, lse = orc.attention_rows(q, k, v, 1.0, n_visible=np.arange(1, n + 1))
+    for i in range(n):
+        assert abs(o[i, 0] - 2.0 * i / 3.0) < 1e-12
+        assert abs(lse[i] - math.log((i + 1) * (i + 2) / 2.0)) < 1e-12
+
+
+def test_hand_expanded_bf16_integer_case():
+    """Through the bf16 entry point, GQA 2 q-heads on 1 kv-head, d=2, scale=0.5.
+    q0=(2,0): scores (0, 1*... ) -- keys (0,0),(2,0),(4,2): s = 0.5*(0,4,8) = (0,2,4)
+    q1=(0,2): s = 0.5*(0,0,4) = (0,0,2).  Expected weights typed from e^0, e^2, e^4."""
+    qb = f64_to_bf16_bits(np.array([[[2.0, 0.0], [0.0, 2.0]]]))           # [1 tok, 2 heads, 2]
+    kb = f64_to_bf16_bits(np.array([[[0.0, 0.0]], [[2.0, 0.0]], [[4.0, 2.0]]]))
+    vb = f64_to_bf16_bits(np.array([[[1.0, -1.0]], [[3.0, 0.5]], [[-2.0, 8.0]]]))
+    o, lse = orc.partial_attention(qb, kb, vb, 0.5)
+    e2, e4 = 7.38905609893065, 54.598150033144236            # e^2, e^4 to 15 digits (tables)
+    z0 = 1.0 + e2 + e4
+    z1 = 1.0 + 1.0 + e2
+    want0 = [(1.0 + 3.0 * e2 - 2.0 * e4) / z0, (-1.0 + 0.5 * e2 + 8.0 * e4) / z0]
+    want1 = [(1.0 + 3.0 - 2.0 * e2) / z1, (-1.0 + 0.5 + 8.0 * e2) / z1]
+    assert np.allclose(o[0, 0], want0, rtol=0, atol=1e-12)
+    assert np.allclose(o[0, 1], want1, rtol=0, atol=1e-12)
+    assert abs(lse[0, 0] - math.log(z0)) < 1e-12 and abs(lse[0, 1] - math.log(z1)) < 1e-12
+
+
+# ---------------------------------------------------------------------------------------
+def brute_attention(q, k, v, scale, n_vis=None):
+    """Differently structured evaluator: python loops, math.exp, no max subtraction."""
+    nq, nk, d = len(q), len(k), len(v[0])
+    out = [[0.0] * d for _ in range(nq)]
+    lse = [0.0] * nq
+    for i in range(nq):
+        vis = nk if n_vis is None else n_vis[i]
+        ws = []
+        for j in range(vis):
+            s = 0.0
+            for c in range(len(q[i])):
+                s += q[i][c] * k[j][c]
+            ws.append(math.exp(s * scale))
+        z = math.fsum(ws)
+        lse[i] = math.log(z)
+        for c in range(d):
+            out[i][c] = math.fsum(w * v[j][c] for j, w in enumerate(ws)) / z
+    return np.array(out), np.array(lse)
+
+
+def test_brute_force_small_random():
+    rng = np.random.default_rng(7)
+    for nq, nk, d in [(1, 1, 1), (3, 5, 4), (6, 8, 3), (8, 8, 2)]:
+        q, k, v = rng.standard_normal((nq, d)), rng.standard_normal((nk, d)), rng.standard_normal((nk, d))
+        o, l = orc.attention_rows(q, k, v, 0.37)
+        bo, bl = brute_attention(q.tolist(), k.tolist(), v.tolist(), 0.37)
+        assert np.allclose(o, bo, rtol=0, atol=1e-12) and np.allclose(l, bl, rtol=0, atol=1e-12)
+    q, k, v = rng.standard_normal((8, 4)), rng.standard_normal((8, 4)), rng.standard_normal((8, 4))
+    nv = list(range(1, 9))
+    o, l = orc.attention_rows(q, k, v, 0.5, n_visible=nv)
+    bo, bl = brute_attention(q.tolist(), k.tolist(), v.tolist(), 0.5, nv)
+    assert np.allclose(o, bo, rtol=0, atol=1e-12) and np.allclose(l, bl, rtol=0, atol=1e-12)
+
+
+def test_brute_force_request_with_pool_and_gqa():
+    """Whole-request definition against explicit loops over (slot, token, head): checks slot
+    indexing, fills, list order, GQA head map, causal visibility and scale in one go."""
+    rng = np.random.default_rng(11)
+    n_slots, C, hkv, hq, d, lq = 5, 3, 2, 4, 2, 4
+    pk = rand_bf16_bits(rng, (n_slots, C, hkv, d))
+    pv = rand_bf16_bits(rng, (n_slots, C, hkv, d))
+    qb = rand_bf16_bits(rng, (lq, hq, d))
+    kn = rand_bf16_bits(rng, (lq, hkv, d))
+    vn = rand_bf16_bits(rng, (lq, hkv, d))
+    slots, fills, scale = [3, 0, 4], [3, 2, 1], 0.8
+    o, lse = orc.request_attention(qb, pk, pv, slots, fills, kn, vn, scale)
+    P_k, P_v = orc.bf16_bits_to_f64(pk), orc.bf16_bits_to_f64(pv)
+    Q, KN, VN = orc.bf16_bits_to_f64(qb), orc.bf16_bits_to_f64(kn), orc.bf16_bits_to_f64(vn)
+    for i in range(lq):
+        for h in range(hq):
+            g = h // (hq // hkv)
+            keys, vals = [], []
+            for s, f in zip(slots, fills):
+                for t in range(f):
+                    keys.append(P_k[s, t, g].tolist())
+                    vals.append(P_v[s, t, g].tolist())
+            for j in range(i + 1):
+                keys.append(KN[j, g].tolist())
+                vals.append(VN[j, g].tolist())
+            bo, bl = brute_attention([Q[i, h].tolist()], keys, vals, scale)
+            assert np.allclose(o[i, h], bo[0], rtol=0, atol=1e-12)
+            assert abs(lse[i, h] - bl[0]) < 1e-12
+
+
+# ---------------------------------------------------------------------------------------
+def test_closed_forms():
+    rng = np.random.default_rng(3)
+    d, n = 5, 9
+    v = rng.standard_normal((n, d))
+    q = rng.standard_normal((4, d))
+    # identical keys: LSE = s + ln n, O = mean(V)
+    k1 = rng.standard_normal(d)
+    k = np.tile(k1, (n, 1))
+    o, l = orc.attention_rows(q, k, v, 0.3)
+    assert np.allclose(o, np.tile(v.mean(0), (4, 1)), atol=1e-12)
+    assert np.allclose(l, 0.3 * q @ k1 + math.log(n), atol=1e-12)
+    # q = 0: LSE = ln n, O = mean(V)
+    o, l = orc.attention_rows(np.zeros((2, d)), rng.standard_normal((n, d)), v, 1.7)
+    assert np.allclose(o, np.tile(v.mean(0), (2, 1)), atol=1e-12) and np.allclose(l, math.log(n), atol=1e-12)
+    # bounds and convexity
+    k = rng.standard_normal((n, d))
+    o, l = orc.attention_rows(q, k, v, 0.9)
+    s = 0.9 * q @ k.T
+    assert np.all(l >= s.max(1) - 1e-12) and np.all(l <= s.max(1) + math.log(n) + 1e-12)
+    assert np.all(o <= v.max(0) + 1e-12) and np.all(o >= v.min(0) - 1e-12)
+    # constant V
+    o, _ = orc.attention_rows(q, k, np.full((n, d), 2.5), 0.9)
+    assert np.allclose(o, 2.5, atol=1e-12)
+    # one dominating key (+40 over the rest): O -> its v
+    kd = np.zeros((n, 1)); kd[4, 0] = 40.0
+    o, l = orc.attention_rows(np.ones((1, 1)), kd, v, 1.0)
+    assert np.allclose(o[0], v[4], atol=1e-12 * 1e5) and abs(l[0] - 40.0) < 1e-12 * 1e5
+    # library routine: scipy softmax / logsumexp
+    o, l = orc.attention_rows(q, k, v, 0.9)
+    assert np.allclose(o, softmax(s, axis=1) @ v, atol=1e-12)
+    assert np.allclose(l, logsumexp(s, axis=1), atol=1e-12)
+
+
+def test_shift_and_duplication():
+    rng = np.random.default_rng(5)
+    d, n = 4, 7
+    q, k, v = rng.standard_normal((3, d)), rng.standard_normal((n, d)), rng.standard_normal((n, d))
+    o, l = orc.attention_rows(q, k, v, 0.6)
+    # extra channel: q gets 1, every key gets c/scale -> all scores + c
+    c = 2.25
+    q2 = np.concatenate([q, np.ones((3, 1))], 1)
+    k2 = np.concatenate([k, np.full((n, 1), c / 0.6)], 1)
+    o2, l2 = orc.attention_rows(q2, k2, v, 0.6)
+    assert np.allclose(o2, o, atol=1e-12) and np.allclose(l2, l + c, atol=1e-12)
+    # keys listed twice: same O, LSE + ln 2
+    o3, l3 = orc.attention_rows(q, np.concatenate([k, k]), np.concatenate([v, v]), 0.6)
+    assert np.allclose(o3, o, atol=1e-12) and np.allclose(l3, l + math.log(2.0), atol=1e-12)
+
+
+def test_empty_and_masked_rows():
+    o, l = orc.attention_rows(np.ones((2, 3)), np.zeros((0, 3)), np.zeros((0, 3)), 1.0)
+    assert o.shape == (2, 3) and np.all(o == 0) and np.all(np.isneginf(l))
+    o, l = orc.attention_rows(np.ones((2, 3)), np.ones((4, 3)), np.ones((4, 3)), 1.0, n_visible=[0, 2])
+    assert np.all(o[0] == 0) and np.isneginf(l[0]) and np.allclose(o[1], 1.0)
+    assert abs(l[1] - (3.0 + math.log(2.0))) < 1e-12
+    # merge: -inf partials carry weight 0; all -inf stays (0, -inf); no NaN anywhere
+    outs = np.stack([np.zeros((2, 3)), np.full((2, 3), 4.0)])
+    lses = np.array([[-np.inf, -np.inf], [1.5, -np.inf]])
+    mo, ml = orc.merge_partials(outs, lses)
+    assert np.allclose(mo[0], 4.0) and ml[0] == 1.5
+    assert np.all(mo[1] == 0) and np.isneginf(ml[1]) and not np.isnan(mo).any()
+
+
+# ---------------------------------------------------------------------------------------
+def _request_case(rng, n_list=5, C=4, hkv=2, hq=4, d=8, lq=5, n_slots=9):
+    pk = rand_bf16_bits(rng, (n_slots, C, hkv, d))
+    pv = rand_bf16_bits(rng, (n_slots, C, hkv, d))
+    qb = rand_bf16_bits(rng, (lq, hq, d))
+    kn = rand_bf16_bits(rng, (lq, hkv, d))
+    vn = rand_bf16_bits(rng, (lq, hkv, d))
+    slots = rng.permutation(n_slots)[:n_list]
+    fills = rng.integers(1, C + 1, size=n_list)
+    return qb, pk, pv, slots, fills, kn, vn
+
+
+def test_merge_of_partials_equals_full_any_partition_any_order():
+    rng = np.random.default_rng(13)
+    qb, pk, pv, slots, fills, kn, vn = _request_case(rng)
+    scale = 1.0 / math.sqrt(8)
+    full_o, full_l = orc.request_attention(qb, pk, pv, slots, fills, kn, vn, scale)
+    n = len(slots)
+    for trial in range(12):
+        # random partition of the list into 1..n groups (not necessarily contiguous), random order
+        n_groups = int(rng.integers(1, n + 1))
+        labels = rng.integers(0, n_groups, size=n)
+        groups = [np.flatnonzero(labels == g).tolist() for g in range(n_groups)]
+        groups = [g for g in groups if g]
+        outs, lses = orc.request_partials_by_segment(qb, pk, pv, slots, fills, kn, vn, scale, groups)
+        perm = rng.permutation(len(outs))
+        mo, ml = orc.merge_partials(outs[perm], lses[perm])
+        assert np.allclose(mo, full_o, rtol=0, atol=1e-12)
+        assert np.allclose(ml, full_l, rtol=0, atol=1e-12)
+
+
+def test_merge_split_points_inside_segments_and_associativity():
+    rng = np.random.default_rng(17)
+    d, n = 6, 23
+    q, k, v = rng.standard_normal((4, d)), rng.standard_normal((n, d)), rng.standard_normal((n, d))
+    full_o, full_l = orc.attention_rows(q, k, v, 0.41)
+    for trial in range(10):
+        cuts = np.sort(rng.choice(np.arange(1, n), size=int(rng.integers(1, 6)), replace=False))
+        edges = [0] + cuts.tolist() + [n]
+        parts = [orc.attention_rows(q, k[a:b], v[a:b], 0.41) for a, b in zip(edges[:-1], edges[1:])]
+        outs = np.stack([p[0] for p in parts]); lses = np.stack([p[1] for p in parts])
+        mo, ml = orc.merge_partials(outs, lses)
+        assert np.allclose(mo, full_o, atol=1e-12) and np.allclose(ml, full_l, atol=1e-12)
+        # pairwise tree == flat
+        acc_o, acc_l = outs[0], lses[0]
+        for j in range(1, len(outs)):
+            acc_o, acc_l = orc.merge_partials(np.stack([acc_o, outs[j]]), np.stack([acc_l, lses[j]]))
+        assert np.allclose(acc_o, full_o, atol=1e-12) and np.allclose(acc_l, full_l, atol=1e-12)
+
+
+def test_single_segment_reduces_to_plain_attention():
+    rng = np.random.default_rng(19)
+    C, hkv, hq, d, lq = 6, 1, 1, 8, 3
+    pk = rand_bf16_bits(rng, (2, C, hkv, d)); pv = rand_bf16_bits(rng, (2, C, hkv, d))
+    qb = rand_bf16_bits(rng, (lq, hq, d))
+    o, l = orc.request_attention(qb, pk, pv, [1], [C], None, None, 0.25)
+    Q = orc.bf16_bits_to_f64(qb)[:, 0]; K = orc.bf16_bits_to_f64(pk)[1, :, 0]; V = orc.bf16_bits_to_f64(pv)[1, :, 0]
+    s = 0.25 * Q @ K.T
+    assert np.allclose(o[:, 0], softmax(s, axis=1) @ V, atol=1e-12)
+    assert np.allclose(l[:, 0], logsumexp(s, axis=1), atol=1e-12)
+
+
+def test_slot_placement_does_not_change_any_bit():
+    rng = np.random.default_rng(23)
+    qb, pk, pv, slots, fills, kn, vn = _request_case(rng)
+    o1, l1 = orc.request_attention(qb, pk, pv, slots, fills, kn, vn, 0.3)
+    perm = rng.permutation(pk.shape[0])                 # slot s moves to perm[s]
+    pk2 = np.empty_like(pk); pv2 = np.empty_like(pv)
+    pk2[perm] = pk; pv2[perm] = pv
+    o2, l2 = orc.request_attention(qb, pk2, pv2, perm[slots], fills, kn, vn, 0.3)
+    assert np.array_equal(o1, o2) and np.array_equal(l1, l2)
+
+
+def test_gqa_equals_mha_with_replicated_kv_heads():
+    rng = np.random.default_rng(29)
+    qb, pk, pv, slots, fills, kn, vn = _request_case(rng, hkv=2, hq=6)
+    o1, l1 = orc.request_attention(qb, pk, pv, slots, fills, kn, vn, 0.3)
+    rep = lambda x: np.repeat(x, 3, axis=-2)
+    o2, l2 = orc.request_attention(qb, rep(pk), rep(pv), slots, fills, rep(kn), rep(vn), 0.3)
+    assert np.array_equal(o1, o2) and np.array_equal(l1, l2)
+
+
+def test_gather_brute_force_and_slot_table():
+    rng = np.random.default_rng(31)
+    n_slots, C, hkv, d = 6, 3, 2, 4
+    pk = rng.integers(0, 65536, size=(n_slots, C, hkv, d)).astype(np.uint16)
+    pv = rng.integers(0, 65536, size=(n_slots, C, hkv, d)).astype(np.uint16)
+    slots, fills = [5, 2, 2, 0], [3, 1, 1, 2]
+    gk, gv = orc.gather_segments(pk, pv, slots, fills)
+    row = 0
+    for s, f in zip(slots, fills):
+        for t in range(f):
+            for h in range(hkv):
+                for c in range(d):
+                    assert gk[row, h, c] == pk[s, t, h, c] and gv[row, h, c] == pv[s, t, h, c]
+            row += 1
+    assert row == gk.shape[0] == 7
+    tab = orc.SlotTable(4, 8)
+    assert tab.put(100, 8, want_slot=2) == 2
+    assert tab.put(7, 3) == 0            # lowest free
+    assert tab.put(100, 5) == 2          # dedup: existing id keeps slot and fill
+    assert tab.put(9, 8) == 1
+    assert list(tab.lookup([7, 100, 55, 9])) == [0, 2, -1, 1]
+    assert list(tab.fill([0, 2, 1])) == [3, 8, 8]
+    tab.put(1, 1)
+    with pytest.raises(MemoryError):
+        tab.put(2, 1)
+
+
+def test_duplicate_slot_counts_twice():
+    rng = np.random.default_rng(37)
+    qb, pk, pv, slots, fills, kn, vn = _request_case(rng, n_list=1)
+    o1, l1 = orc.request_attention(qb, pk, pv, slots, fills, None, None, 0.3)
+    o2, l2 = orc.request_attention(qb, pk, pv, list(slots) * 2, list(fills) * 2, None, None, 0.3)
+    assert np.allclose(o1, o2, atol=1e-12) and np.allclose(l2, l1 + math.log(2.0), atol=1e-12)
