@@ -1,0 +1,208 @@
+#!/usr/bin/env python3
+"""Benchmark of the segment-attention hot path on one MI355X.
+
+A "step" is one pass of the whole path over one batch: tl_segment_attn (partial attention of
+every work item over its pool slots) + tl_causal_block (self block of the new tokens) +
+tl_merge (LSE recombination), with all inputs already resident in HBM.
+
+Default workload: "prefill" (Llama-3-8B layer shape, 16 requests x 512 new tokens, prefixes
+8k-32k tokens, first 2k shared) -- the configuration the prefill MFMA target is quoted on.
+`--workload decode` times the 70B-shape decode batch (HBM-bound); by default a short decode
+measurement is appended to the same JSON line under "decode".
+
+Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+
+
+def _setup(batch, torch, B):
+    dev = "cuda"
+    shape = (batch.n_slots, batch.seg_len, batch.kv_heads, batch.head_dim)
+    pk = torch.zeros(shape, dtype=torch.bfloat16, device=dev)
+    pv = torch.zeros(shape, dtype=torch.bfloat16, device=dev)
+    batch.fill_pool(pk, pv)
+    pool = B.tl_pool_create(batch.n_slots, batch.seg_len, batch.kv_heads, batch.head_dim, pk, pv)
+    B.tl_pool_adopt(pool, batch.pool_ids, batch.pool_slots, batch.pool_fills)
+    return pk, pv, pool
+
+
+def run_workload(batch, steps, warmup, torch, B, split_segments=0):
+    """Times `steps` passes of the whole path; returns timings and the plan's work counters."""
+    pk, pv, pool = _setup(batch, torch, B)
+    plan = B.tl_plan_create(pool, batch.q_heads, batch.req_row_ptr, batch.req_seg_ptr, batch.seg_ids,
+                            B.TL_PLAN_SELF_BLOCK, split_segments)
+    info = B.tl_plan_get_info(plan)
+    dev = "cuda"
+    q, kn, vn = batch.q(dev), batch.k_new(dev), batch.v_new(dev)
+    H, D = batch.q_heads, batch.head_dim
+    outp = torch.empty((info.n_partial_rows, H, D), dtype=torch.float32, device=dev)
+    lsep = torch.empty((info.n_partial_rows, H), dtype=torch.float32, device=dev)
+    out = torch.empty((info.n_tokens, H, D), dtype=torch.bfloat16, device=dev)
+    lse = torch.empty((info.n_tokens, H), dtype=torch.float32, device=dev)
+    scale = batch.scale
+
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(steps)]
+
+    def step(marks=None):
+        if marks: marks[0].record()
+        B.tl_segment_attn(pool, plan, q, scale, outp, lsep)
+        if marks: marks[1].record()
+        B.tl_causal_block(plan, q, kn, vn, scale, outp, lsep)
+        if marks: marks[2].record()
+        B.tl_merge(plan, outp, lsep, out, True, lse)
+        if marks: marks[3].record()
+
+    for _ in range(max(warmup, 1)):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(ev[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    seg_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / steps
+    causal_ms = sum(e[1].elapsed_time(e[2]) for e in ev) / steps
+    merge_ms = sum(e[2].elapsed_time(e[3]) for e in ev) / steps
+    res = {
+        "ms_per_step": (t1 - t0) * 1e3 / steps,
+        "segment_attn_ms": seg_ms, "causal_block_ms": causal_ms, "merge_ms": merge_ms,
+        "info": {n: getattr(info, n) for n, _ in info._fields_},
+        "checksum": float(out.float().abs().mean().item()),
+    }
+    B.tl_plan_destroy(plan)
+    B.tl_pool_destroy(pool)
+    del pk, pv, outp, lsep, out, lse, q, kn, vn
+    torch.cuda.empty_cache()
+    return res
+
+
+def algorithmic_work(batch, info):
+    """Flops and minimum HBM bytes of one pass (what the method must do)."""
+    hq, hkv, d = batch.q_heads, batch.kv_heads, batch.head_dim
+    flops_prefix = 4.0 * hq * d * info["prefix_pairs"]
+    flops_self = 4.0 * hq * d * info["self_pairs"]
+    kv_bytes = 4.0 * hkv * d * info["unique_kv_tokens"]          # K and V, bf16, each unique slot once
+    q_bytes = 2.0 * hq * d * info["n_tokens"]
+    part_rows = info["n_partial_rows"] - (info["n_tokens"] if info["self_row_base"] >= 0 else 0)
+    part_bytes = part_rows * hq * (d + 1) * 4.0
+    return {"flops_prefix": flops_prefix, "flops_self": flops_self, "kv_bytes": kv_bytes, "q_bytes": q_bytes,
+            "partial_bytes": part_bytes}
+
+
+def cpu_baseline(batch, budget_s=15.0):
+    """The fp64 oracle, as it stands, timed on this host on a bounded sample of the workload:
+    whole new tokens (all heads, full prefix + self block) of the request with the median
+    prefix length, as many as fit the budget (at least 2)."""
+    import numpy as np
+    from threadpoolctl import threadpool_info
+    from tests import tl_harness as H      # test-side glue around oracle/ (generator -> oracle inputs)
+    from oracle import tokenlake_oracle as orc
+    L = batch.prefix_tokens()
+    r = int(np.argsort(L)[len(L) // 2])
+    qb, pk, pv, slots, fills, kn, vn = H.host_request_inputs(batch, r)
+    lq = qb.shape[0]
+    n_done, t_used = 0, 0.0
+    n = min(2, lq)
+    while n_done < lq and t_used < budget_s:
+        rows = np.arange(n_done, min(lq, n_done + n))
+        t0 = time.perf_counter()
+        gk, gv = orc.gather_segments(pk, pv, slots, fills)
+        k_all = np.concatenate([gk, kn], axis=0)
+        v_all = np.concatenate([gv, vn], axis=0)
+        orc.partial_attention(qb[rows], k_all, v_all, batch.scale, n_visible=gk.shape[0] + rows + 1)
+        dt = time.perf_counter() - t0
+        t_used += dt
+        n_done += len(rows)
+        n = max(1, min(lq - n_done, int(n * max(1.0, min(4.0, (budget_s - t_used) / max(dt, 1e-3) / 2)))))
+        if n_done >= 64:
+            break
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    return {"value": n_done / t_used, "unit": "tok/s", "cores": int(threads), "kind": "oracle",
+            "sample": "%d new tokens (all %d heads) of request %d (prefix %d tokens, median of the batch), "
+                      "full prefix + causal self block, numpy fp64, %.1f s" % (n_done, batch.q_heads, r, int(L[r]), t_used)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="prefill", choices=["prefill", "decode", "longctx", "multiturn", "tiny"])
+    ap.add_argument("--split-segments", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-decode", action="store_true", help="skip the appended decode measurement")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding or collectives); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2508_17219_amd import binding as B
+    from paper_2508_17219_amd import workloads as wl
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    B.load_library()
+
+    maker = {"prefill": wl.prefill, "decode": wl.decode, "longctx": wl.longctx, "tiny": wl.tiny,
+             "multiturn": lambda: wl.multiturn(turn=7)}[args.workload]
+    batch = maker()
+    res = run_workload(batch, args.steps, args.warmup, torch, B, args.split_segments)
+    work = algorithmic_work(batch, res["info"])
+    tok_s = batch.n_tokens / (res["ms_per_step"] * 1e-3)
+
+    def roofline_for(b, r, w):
+        seg_s = r["segment_attn_ms"] * 1e-3
+        if b.name.startswith("decode"):
+            by = w["kv_bytes"] + w["q_bytes"] + w["partial_bytes"]
+            ach = by / seg_s / 1e9
+            return {"kernel": "splitk_unit_attn_kernel", "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS,
+                    "unit": "GB/s", "frac": ach / PEAK_HBM_GBS, "traffic": None, "avg_kernel_ms": r["segment_attn_ms"]}
+        ach = w["flops_prefix"] / seg_s / 1e12
+        return {"kernel": "row_tile_attn_kernel", "bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS,
+                "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS, "traffic": None, "avg_kernel_ms": r["segment_attn_ms"]}
+
+    line = {
+        "metric": "merged tok/s (one layer: partial attention over the segment pool + causal self block + LSE merge)",
+        "value": tok_s, "unit": "tok/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": res["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": batch.name, "n_req": batch.n_req, "new_tokens": batch.n_tokens,
+                   "q_heads": batch.q_heads, "kv_heads": batch.kv_heads, "head_dim": batch.head_dim,
+                   "seg_len": batch.seg_len, "prefix_tokens_total": int(batch.prefix_tokens().sum()),
+                   "seed": batch.seed},
+        "roofline": roofline_for(batch, res, work),
+        "kernels_ms": {"segment_attn": res["segment_attn_ms"], "causal_block": res["causal_block_ms"],
+                       "merge": res["merge_ms"]},
+        "partial_attn_tflops": (work["flops_prefix"] + work["flops_self"]) /
+                               ((res["segment_attn_ms"] + res["causal_block_ms"]) * 1e-3) / 1e12,
+    }
+    if args.workload != "decode" and not args.no_decode:
+        db = wl.decode()
+        dres = run_workload(db, max(3, args.steps // 4), 1, torch, B, args.split_segments)
+        dwork = algorithmic_work(db, dres["info"])
+        line["decode"] = {"workload": db.name, "ms_per_step": dres["ms_per_step"],
+                          "merged_tok_s": db.n_tokens / (dres["ms_per_step"] * 1e-3),
+                          "roofline": roofline_for(db, dres, dwork),
+                          "kernels_ms": {"segment_attn": dres["segment_attn_ms"], "causal_block": dres["causal_block_ms"],
+                                         "merge": dres["merge_ms"]}}
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(batch)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

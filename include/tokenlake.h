@@ -1,0 +1,203 @@
+/*
+ * tokenlake.h -- C ABI of the MI355X (gfx950) segment-level prefix-attention library.
+ *
+ * The library implements the data-plane compute of TokenLake's cache-aware operation
+ * (paper Section 3.2 "Interfaces": `query` returns the attention output of the query
+ * tensor over the prefix-cache pool, `put` stores new KV; Section 4, first paragraph:
+ * segments are independent, each yields a partial output and a normalizer, and the
+ * final output is their combination; Section 2.1: prefix attention and the new tokens'
+ * self-attention are reduced together).
+ *
+ * Conventions
+ *  - Every call returns a tl_status (0 = TL_OK, negative = error).  Nothing throws or
+ *    aborts across this boundary; tl_last_error() gives a per-thread message.
+ *  - "host" pointers are ordinary CPU memory, read during the call only.
+ *    "device" pointers are HIP device memory owned by the caller unless stated otherwise;
+ *    they must stay valid until the stream work enqueued by the call has completed.
+ *  - Compute calls enqueue kernels on `stream` (a hipStream_t passed as void*, NULL = the
+ *    default stream) and return without synchronising.
+ *  - All tensors are dense, row-major, bf16 = 16-bit brain float bit patterns.
+ *  - head_dim must be 128; q_heads / kv_heads must be a power of two <= 32; seg_len must
+ *    be a multiple of 64.  Anything else is TL_EINVAL.
+ *  - The normalizer is the natural-log log-sum-exp of the scaled scores.  A row with no
+ *    keys has O = 0 and LSE = -inf.
+ */
+#ifndef TOKENLAKE_H_
+#define TOKENLAKE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t tl_status;
+enum {
+  TL_OK = 0,
+  TL_EINVAL = -1,    /* bad argument (null pointer, size, unsupported shape)          */
+  TL_ENOMEM = -2,    /* host or device allocation failed                              */
+  TL_EFULL = -3,     /* no free slot in the pool                                      */
+  TL_ENOTFOUND = -4, /* segment id not resident in the pool                           */
+  TL_EHIP = -5       /* a HIP runtime call failed (no device, launch error, ...)      */
+};
+
+/* Text for a status code (static storage). */
+const char* tl_status_str(tl_status s);
+/* Message of the last failing call on this thread (static thread-local storage). */
+const char* tl_last_error(void);
+
+/* ------------------------------------------------------------------------------------
+ * Segment pool (paper Section 3.1: prefix caches are split into fixed-size segments kept in
+ * per-GPU cache slots; Section 1 / 4: one copy per segment -- deduplication).
+ *
+ * Slot s holds K and V as [seg_len, kv_heads, head_dim] bf16 each, at
+ *   k_dev + s * seg_len * kv_heads * head_dim   (same for v_dev).
+ * A slot has `fill` valid tokens (1..seg_len); tokens at or beyond fill do not exist for
+ * attention.  The pool object lives on the host; it owns the id->slot table, the per-slot
+ * fill / reference count / last-use stamp, and a device mirror of fill[].
+ * ------------------------------------------------------------------------------------ */
+typedef struct tl_pool tl_pool;
+
+/* k_dev/v_dev: device, [n_slots, seg_len, kv_heads, head_dim] bf16 each, caller-owned; or
+ * both NULL, then the library allocates them (and frees them in tl_pool_destroy).
+ * Makes no HIP call when k_dev/v_dev are given (device state is set up on first use). */
+tl_status tl_pool_create(tl_pool** out, int32_t n_slots, int32_t seg_len, int32_t kv_heads,
+                         int32_t head_dim, void* k_dev, void* v_dev);
+tl_status tl_pool_destroy(tl_pool* pool);
+
+/* `put` (Section 3.2): store one segment.  k_src_dev/v_src_dev: device,
+ * [fill, kv_heads, head_dim] bf16.  If the id is already resident nothing is copied, its
+ * reference count goes up and *slot_out is the existing slot (deduplication).  Otherwise
+ * the segment goes to want_slot (must be free) or, with want_slot = -1, to the
+ * lowest-numbered free slot; tokens [fill, seg_len) of the slot are zeroed.
+ * Errors: TL_EFULL, TL_EINVAL (fill outside 1..seg_len, slot taken or out of range). */
+tl_status tl_pool_put(tl_pool* pool, uint64_t segment_id, const void* k_src_dev, const void* v_src_dev,
+                      int32_t fill, int32_t want_slot, int32_t* slot_out, void* stream);
+
+/* Register segments whose KV the caller has already written into the pool memory
+ * (no copy; the slots' tails are left as they are).  ids/slots/fills: host, [n].
+ * Same id twice or slot taken -> TL_EINVAL, nothing is registered. */
+tl_status tl_pool_adopt(tl_pool* pool, const uint64_t* ids, const int32_t* slots, const int32_t* fills,
+                        int32_t n, void* stream);
+
+/* Drop one reference.  A segment with zero references stays resident (it can still be
+ * looked up and attended to) until tl_pool_evict_lru removes it.  TL_ENOTFOUND for an
+ * unknown id, TL_EINVAL if the count is already zero. */
+tl_status tl_pool_release(tl_pool* pool, uint64_t segment_id);
+
+/* Free the slot of the least recently used segment among those with zero references
+ * (Section 4.3: eviction by last access time).  A segment is "used" when it is put,
+ * adopted, or named by a plan.  *evicted_id receives its id; TL_ENOTFOUND if no segment
+ * is evictable. */
+tl_status tl_pool_evict_lru(tl_pool* pool, uint64_t* evicted_id);
+
+/* segment_id -> slot for n ids (host arrays); -1 for an id that is not resident.
+ * Never fails on a miss.  Bit-exact integer work. */
+tl_status tl_pool_lookup(const tl_pool* pool, const uint64_t* ids, int32_t n, int32_t* slots_out);
+/* Valid tokens of n slots (host arrays); 0 for a free slot. */
+tl_status tl_pool_fills(const tl_pool* pool, const int32_t* slots, int32_t n, int32_t* fills_out);
+/* Counters: slots in use. */
+tl_status tl_pool_used(const tl_pool* pool, int32_t* n_used);
+
+/* Copy the listed slots, whole (seg_len tokens each), to contiguous device buffers
+ * k_out_dev/v_out_dev [n, seg_len, kv_heads, head_dim].  slots: host [n].  For
+ * verification of slot addressing; bit-exact. */
+tl_status tl_pool_gather(tl_pool* pool, const int32_t* slots, int32_t n, void* k_out_dev, void* v_out_dev,
+                         void* stream);
+
+/* ------------------------------------------------------------------------------------
+ * Plan: the per-iteration control flow (Section 3.2: plans are generated for each batch
+ * before the data plane runs).  Built on the host from each request's new-token range and
+ * ordered segment-id list.  It resolves ids to slots, groups requests that share a run of
+ * slots into one work item (a hot segment is then read once for all their query rows,
+ * Section 4.3), splits long lists of decode requests into chunks (split-K), and lays out
+ * the partial rows and the merge lists.
+ *
+ * Partial row p of out_partial/lse belongs to one (work item, token) pair; the causal self
+ * block, if requested, owns rows [self_row_base, self_row_base + n_tokens).
+ * ------------------------------------------------------------------------------------ */
+typedef struct tl_plan tl_plan;
+
+enum {
+  TL_PLAN_SELF_BLOCK = 1, /* reserve partial rows for tl_causal_block and merge them   */
+  TL_PLAN_NO_SHARING = 2  /* do not group requests: one item chain per request         */
+};
+
+typedef struct tl_plan_info {
+  int32_t n_req, n_tokens, q_heads, kv_heads;
+  int32_t n_items;         /* work items of tl_segment_attn                              */
+  int32_t n_partial_rows;  /* R: rows the caller must provide in out_partial / lse       */
+  int32_t self_row_base;   /* first row of the self block, -1 without TL_PLAN_SELF_BLOCK */
+  int32_t n_tiles;         /* MFMA row tiles (work items with many query rows)           */
+  int32_t n_units;         /* split-K units (work items with <= 16 rows per kv head)     */
+  int32_t n_causal_tiles;
+  int32_t n_list_entries;  /* sum of request list lengths                                */
+  int32_t n_merge_entries; /* sum over tokens of partials to merge                       */
+  int64_t prefix_pairs;    /* sum over list entries of new_tokens(req) * fill(slot)      */
+  int64_t self_pairs;      /* sum over requests of Lq (Lq + 1) / 2                       */
+  int64_t unique_kv_tokens;/* valid tokens in the distinct slots the plan touches        */
+} tl_plan_info;
+
+/* req_row_ptr: host [n_req+1], offsets of each request's new tokens in the batch's Q
+ * (req_row_ptr[0] = 0, non-decreasing).  req_seg_ptr: host [n_req+1], offsets into seg_ids.
+ * seg_ids: host, the ordered prefix of each request.  split_segments: list entries per
+ * split-K chunk for items with few rows (0 = library default).
+ * Errors: TL_ENOTFOUND if an id is not resident; TL_EINVAL on malformed arrays.
+ * Makes no HIP call: device copies of the plan are made on first use. */
+tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, int32_t n_req,
+                         const int32_t* req_row_ptr, const int32_t* req_seg_ptr, const uint64_t* seg_ids,
+                         int32_t flags, int32_t split_segments);
+tl_status tl_plan_destroy(tl_plan* plan);
+tl_status tl_plan_get_info(const tl_plan* plan, tl_plan_info* info);
+
+/* Host copies of the plan's integer structure, for checking it (each pointer may be NULL
+ * to skip; arrays must be large enough, sizes from tl_plan_info):
+ *   item_row_base [n_items]     first partial row of the item
+ *   item_tok_ptr  [n_items+1]   into item_tokens
+ *   item_tokens   [..]          batch token index of each of the item's rows, in row order
+ *   item_slot_ptr [n_items+1]   into item_slots
+ *   item_slots    [..]          the item's ordered slot list
+ *   merge_ptr     [n_tokens+1]  into merge_rows
+ *   merge_rows    [n_merge_entries] partial rows to combine for each token            */
+tl_status tl_plan_export(const tl_plan* plan, int32_t* item_row_base, int32_t* item_tok_ptr,
+                         int32_t* item_tokens, int32_t* item_slot_ptr, int32_t* item_slots,
+                         int32_t* merge_ptr, int32_t* merge_rows);
+/* Sizes of the two variable-length arrays of tl_plan_export. */
+tl_status tl_plan_export_sizes(const tl_plan* plan, int32_t* n_item_tokens, int32_t* n_item_slots);
+
+/* ------------------------------------------------------------------------------------
+ * Compute (Section 3.2 `query`; Section 4 first paragraph; Section 2.1).
+ * ------------------------------------------------------------------------------------ */
+
+/* Partial attention of every work item: for each of its query rows (token, q-head) the
+ * softmax attention over the valid tokens of the item's slots, in list order:
+ *   s_j = scale * <q, k_j>,  LSE = ln sum_j exp(s_j),  O = sum_j exp(s_j - LSE) v_j.
+ * q_dev: device [n_tokens, q_heads, 128] bf16.
+ * out_partial: device [n_partial_rows, q_heads, 128] fp32;  lse: device [n_partial_rows, q_heads] fp32.
+ * Rows of the self block are not written by this call. */
+tl_status tl_segment_attn(const tl_pool* pool, tl_plan* plan, const void* q_dev, float scale,
+                          float* out_partial, float* lse, void* stream);
+
+/* Causal self block of the new tokens: token i of a request attends to the request's new
+ * tokens 0..i (inclusive).  k_new_dev/v_new_dev: device [n_tokens, kv_heads, 128] bf16.
+ * Writes partial rows [self_row_base, self_row_base + n_tokens).  TL_EINVAL if the plan was
+ * built without TL_PLAN_SELF_BLOCK. */
+tl_status tl_causal_block(tl_plan* plan, const void* q_dev, const void* k_new_dev, const void* v_new_dev,
+                          float scale, float* out_partial, float* lse, void* stream);
+
+/* Exact recombination of each token's partials:
+ *   M = max_j LSE_j, w_j = exp(LSE_j - M), O = sum_j w_j O_j / sum_j w_j, LSE = M + ln sum_j w_j.
+ * out_dev: device [n_tokens, q_heads, 128], bf16 if out_is_bf16 else fp32.
+ * lse_out: device [n_tokens, q_heads] fp32, or NULL. */
+tl_status tl_merge(tl_plan* plan, const float* out_partial, const float* lse, void* out_dev,
+                   int32_t out_is_bf16, float* lse_out, void* stream);
+
+/* Kernel-variant switch for experiments and A/B tests (0 = default).  Returns TL_EINVAL
+ * for an unknown knob.  Knobs: "vread" (0 = transposing LDS reads, 1 = scalar LDS reads). */
+tl_status tl_set_option(const char* knob, int32_t value);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TOKENLAKE_H_ */

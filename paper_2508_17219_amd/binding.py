@@ -1,0 +1,230 @@
+"""Thin ctypes binding over libtokenlake.so: same names as the C ABI (include/tokenlake.h),
+argument marshalling only.  Every step of the path runs in the library's kernels; there is
+no Python or CPU fallback -- if the library is missing, loading raises.
+
+Device arguments are torch tensors (their data_ptr is passed) or raw integer addresses;
+host arrays are numpy arrays.  `stream=None` uses torch's current HIP stream.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libtokenlake.so")
+
+TL_OK, TL_EINVAL, TL_ENOMEM, TL_EFULL, TL_ENOTFOUND, TL_EHIP = 0, -1, -2, -3, -4, -5
+TL_PLAN_SELF_BLOCK, TL_PLAN_NO_SHARING = 1, 2
+
+
+class TokenLakeError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__("tokenlake status %d: %s" % (status, message))
+        self.status = status
+
+
+class tl_plan_info(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in (
+        "n_req", "n_tokens", "q_heads", "kv_heads", "n_items", "n_partial_rows", "self_row_base",
+        "n_tiles", "n_units", "n_causal_tiles", "n_list_entries", "n_merge_entries")] + [
+        (n, C.c_int64) for n in ("prefix_pairs", "self_pairs", "unique_kv_tokens")]
+
+
+_lib = None
+
+_P, _I32, _U64, _F32 = C.c_void_p, C.c_int32, C.c_uint64, C.c_float
+_SIGNATURES = {
+    "tl_status_str": (C.c_char_p, [_I32]),
+    "tl_last_error": (C.c_char_p, []),
+    "tl_set_option": (_I32, [C.c_char_p, _I32]),
+    "tl_pool_create": (_I32, [C.POINTER(_P), _I32, _I32, _I32, _I32, _P, _P]),
+    "tl_pool_destroy": (_I32, [_P]),
+    "tl_pool_put": (_I32, [_P, _U64, _P, _P, _I32, _I32, C.POINTER(_I32), _P]),
+    "tl_pool_adopt": (_I32, [_P, _P, _P, _P, _I32, _P]),
+    "tl_pool_release": (_I32, [_P, _U64]),
+    "tl_pool_evict_lru": (_I32, [_P, C.POINTER(_U64)]),
+    "tl_pool_lookup": (_I32, [_P, _P, _I32, _P]),
+    "tl_pool_fills": (_I32, [_P, _P, _I32, _P]),
+    "tl_pool_used": (_I32, [_P, C.POINTER(_I32)]),
+    "tl_pool_gather": (_I32, [_P, _P, _I32, _P, _P, _P]),
+    "tl_plan_create": (_I32, [C.POINTER(_P), _P, _I32, _I32, _P, _P, _P, _I32, _I32]),
+    "tl_plan_destroy": (_I32, [_P]),
+    "tl_plan_get_info": (_I32, [_P, C.POINTER(tl_plan_info)]),
+    "tl_plan_export_sizes": (_I32, [_P, C.POINTER(_I32), C.POINTER(_I32)]),
+    "tl_plan_export": (_I32, [_P, _P, _P, _P, _P, _P, _P, _P]),
+    "tl_segment_attn": (_I32, [_P, _P, _P, _F32, _P, _P, _P]),
+    "tl_causal_block": (_I32, [_P, _P, _P, _P, _F32, _P, _P, _P]),
+    "tl_merge": (_I32, [_P, _P, _P, _P, _I32, _P, _P]),
+}
+EXPORTED = tuple(_SIGNATURES)
+
+
+def load_library(path: Optional[str] = None):
+    """Load libtokenlake.so (built by paper_2508_17219_amd.build).  Raises if it is absent."""
+    global _lib
+    if _lib is None:
+        p = path or LIB_PATH
+        if not os.path.exists(p):
+            raise FileNotFoundError(
+                "%s not found: build it with `python -m paper_2508_17219_amd.build` "
+                "(there is no fallback path)" % p)
+        lib = C.CDLL(p)
+        for name, (res, args) in _SIGNATURES.items():
+            fn = getattr(lib, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = lib
+    return _lib
+
+
+def _check(status: int):
+    if status != TL_OK:
+        raise TokenLakeError(status, load_library().tl_last_error().decode())
+
+
+def _dev(x) -> Optional[int]:
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    if not x.is_contiguous():
+        raise ValueError("device tensor must be contiguous")
+    return x.data_ptr()
+
+
+def _host(a, dtype) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(a), dtype=dtype)
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        if torch.cuda.is_available():
+            return torch.cuda.current_stream().cuda_stream or None
+        return None
+    return int(stream) or None
+
+
+# ---- pool -------------------------------------------------------------------------------
+def tl_pool_create(n_slots: int, seg_len: int, kv_heads: int, head_dim: int, k_dev=None, v_dev=None) -> int:
+    h = _P()
+    _check(load_library().tl_pool_create(C.byref(h), n_slots, seg_len, kv_heads, head_dim, _dev(k_dev), _dev(v_dev)))
+    return h.value
+
+
+def tl_pool_destroy(pool: int):
+    _check(load_library().tl_pool_destroy(pool))
+
+
+def tl_pool_put(pool: int, segment_id: int, k_src, v_src, fill: int, want_slot: int = -1, stream=None) -> int:
+    slot = _I32(-1)
+    _check(load_library().tl_pool_put(pool, segment_id, _dev(k_src), _dev(v_src), fill, want_slot, C.byref(slot),
+                                      _stream(stream)))
+    return slot.value
+
+
+def tl_pool_adopt(pool: int, ids, slots, fills, stream=None):
+    ids, slots, fills = _host(ids, np.uint64), _host(slots, np.int32), _host(fills, np.int32)
+    if not (len(ids) == len(slots) == len(fills)):
+        raise ValueError("ids/slots/fills length mismatch")
+    _check(load_library().tl_pool_adopt(pool, ids.ctypes.data, slots.ctypes.data, fills.ctypes.data, len(ids),
+                                        _stream(stream)))
+
+
+def tl_pool_release(pool: int, segment_id: int):
+    _check(load_library().tl_pool_release(pool, segment_id))
+
+
+def tl_pool_evict_lru(pool: int) -> int:
+    out = _U64(0)
+    _check(load_library().tl_pool_evict_lru(pool, C.byref(out)))
+    return out.value
+
+
+def tl_pool_lookup(pool: int, ids) -> np.ndarray:
+    ids = _host(ids, np.uint64)
+    out = np.empty(len(ids), np.int32)
+    _check(load_library().tl_pool_lookup(pool, ids.ctypes.data, len(ids), out.ctypes.data))
+    return out
+
+
+def tl_pool_fills(pool: int, slots) -> np.ndarray:
+    slots = _host(slots, np.int32)
+    out = np.empty(len(slots), np.int32)
+    _check(load_library().tl_pool_fills(pool, slots.ctypes.data, len(slots), out.ctypes.data))
+    return out
+
+
+def tl_pool_used(pool: int) -> int:
+    n = _I32(0)
+    _check(load_library().tl_pool_used(pool, C.byref(n)))
+    return n.value
+
+
+def tl_pool_gather(pool: int, slots, k_out, v_out, stream=None):
+    slots = _host(slots, np.int32)
+    _check(load_library().tl_pool_gather(pool, slots.ctypes.data, len(slots), _dev(k_out), _dev(v_out), _stream(stream)))
+
+
+# ---- plan -------------------------------------------------------------------------------
+def tl_plan_create(pool: int, q_heads: int, req_row_ptr, req_seg_ptr, seg_ids, flags: int = TL_PLAN_SELF_BLOCK,
+                   split_segments: int = 0) -> int:
+    rp, sp, ids = _host(req_row_ptr, np.int32), _host(req_seg_ptr, np.int32), _host(seg_ids, np.uint64)
+    if len(rp) != len(sp) or len(rp) < 1:
+        raise ValueError("req_row_ptr/req_seg_ptr must both have n_req+1 entries")
+    if len(ids) < int(sp[-1]):
+        raise ValueError("seg_ids shorter than req_seg_ptr[-1]")
+    h = _P()
+    _check(load_library().tl_plan_create(C.byref(h), pool, q_heads, len(rp) - 1, rp.ctypes.data, sp.ctypes.data,
+                                         ids.ctypes.data if len(ids) else None, flags, split_segments))
+    return h.value
+
+
+def tl_plan_destroy(plan: int):
+    _check(load_library().tl_plan_destroy(plan))
+
+
+def tl_plan_get_info(plan: int) -> tl_plan_info:
+    info = tl_plan_info()
+    _check(load_library().tl_plan_get_info(plan, C.byref(info)))
+    return info
+
+
+def tl_plan_export(plan: int) -> dict:
+    lib = load_library()
+    info = tl_plan_get_info(plan)
+    nt, ns = _I32(0), _I32(0)
+    _check(lib.tl_plan_export_sizes(plan, C.byref(nt), C.byref(ns)))
+    out = {
+        "item_row_base": np.zeros(info.n_items, np.int32),
+        "item_tok_ptr": np.zeros(info.n_items + 1, np.int32),
+        "item_tokens": np.zeros(nt.value, np.int32),
+        "item_slot_ptr": np.zeros(info.n_items + 1, np.int32),
+        "item_slots": np.zeros(ns.value, np.int32),
+        "merge_ptr": np.zeros(info.n_tokens + 1, np.int32),
+        "merge_rows": np.zeros(info.n_merge_entries, np.int32),
+    }
+    _check(lib.tl_plan_export(plan, *[out[k].ctypes.data for k in (
+        "item_row_base", "item_tok_ptr", "item_tokens", "item_slot_ptr", "item_slots", "merge_ptr", "merge_rows")]))
+    return out
+
+
+# ---- compute ----------------------------------------------------------------------------
+def tl_segment_attn(pool: int, plan: int, q, scale: float, out_partial, lse, stream=None):
+    _check(load_library().tl_segment_attn(pool, plan, _dev(q), scale, _dev(out_partial), _dev(lse), _stream(stream)))
+
+
+def tl_causal_block(plan: int, q, k_new, v_new, scale: float, out_partial, lse, stream=None):
+    _check(load_library().tl_causal_block(plan, _dev(q), _dev(k_new), _dev(v_new), scale, _dev(out_partial), _dev(lse),
+                                          _stream(stream)))
+
+
+def tl_merge(plan: int, out_partial, lse, out, out_is_bf16: bool, lse_out=None, stream=None):
+    _check(load_library().tl_merge(plan, _dev(out_partial), _dev(lse), _dev(out), int(bool(out_is_bf16)), _dev(lse_out),
+                                   _stream(stream)))
+
+
+def tl_set_option(knob: str, value: int):
+    _check(load_library().tl_set_option(knob.encode(), value))

@@ -1,0 +1,61 @@
+// Device-side helpers shared by the attention kernels (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include "tl_internal.h"
+
+namespace tl {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+// LDS rows are padded from 128 to 136 bf16 (272 B) so that the 16 B reads of one MFMA
+// operand column fall in different banks.
+constexpr int kLdsStride = 136;
+
+struct AttnArgs {
+  const uint16_t* q;      // [n_tokens, q_heads, 128] bf16
+  const uint16_t* k;      // pool K base, or new-token K [n_tokens, kv_heads, 128]
+  const uint16_t* v;
+  const int32_t* fill;    // per-slot valid tokens (pool work)
+  const Work* work;
+  const int32_t* tok;     // token index lists
+  const int32_t* slots;   // slot lists (pool work)
+  float* out;             // [rows, q_heads, 128]
+  float* lse;             // [rows, q_heads]
+  int32_t q_heads, kv_heads, log2g, seg_len, n_work;
+  float scale;            // softmax scale
+  float scale_log2e;      // scale * log2(e)
+};
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+__device__ __forceinline__ bf16x8 pack_bf16x8(float a0, float a1, float a2, float a3, float a4, float a5, float a6,
+                                              float a7) {
+  f32x8 f = {a0, a1, a2, a3, a4, a5, a6, a7};
+  return __builtin_convertvector(f, bf16x8);
+}
+
+__device__ __forceinline__ bf16x8 as_bf16x8(uint4 u) { return __builtin_bit_cast(bf16x8, u); }
+
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+
+// Transposing LDS read: within each group of 16 lanes, lane j supplies the address of 4
+// consecutive bf16 (row j/4, columns 4*(j%4)..+3 of a 4 x 16 block); lane i receives column
+// i of that block, rows 0..3.
+__device__ __forceinline__ s16x4 lds_read_tr(const uint16_t* p) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)p);
+}
+
+__device__ __forceinline__ bf16x8 join_tr(s16x4 lo, s16x4 hi) {
+  s16x8 r = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+  return __builtin_bit_cast(bf16x8, r);
+}
+
+}  // namespace tl

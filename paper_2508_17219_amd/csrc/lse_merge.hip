@@ -1,0 +1,141 @@
+// Exact recombination of partial outputs by their log-sum-exp (paper Section 2.1: partial
+// outputs and normalizers are reduced into the final output; Section 4, first paragraph),
+// and the three compute entry points of the ABI.
+#include <cmath>
+
+#include "attn_common.h"
+
+namespace tl {
+
+tl_status launch_pool_row_tiles(const AttnArgs& a, int n_work, hipStream_t st);
+tl_status launch_causal_row_tiles(const AttnArgs& a, int n_work, hipStream_t st);
+tl_status launch_splitk_units(const AttnArgs& a, int n_work, hipStream_t st);
+
+namespace {
+
+// One workgroup per token; a thread owns 4 consecutive channels of one head.
+//   M = max_j LSE_j;  w_j = exp(LSE_j - M);  O = sum w_j O_j / sum w_j;  LSE = M + ln sum w_j
+template <bool OUT_BF16>
+__global__ __launch_bounds__(256) void lse_merge_kernel(const float* __restrict__ part, const float* __restrict__ lse,
+                                                        const int32_t* __restrict__ mptr,
+                                                        const int32_t* __restrict__ mrows, void* __restrict__ out,
+                                                        float* __restrict__ lse_out, int q_heads) {
+  const int t = blockIdx.x;
+  const int b = mptr[t], e = mptr[t + 1];
+  for (int idx = threadIdx.x; idx < q_heads * 32; idx += blockDim.x) {
+    const int hd = idx >> 5, c4 = idx & 31;
+    float M = -INFINITY;
+    for (int jj = b; jj < e; ++jj) M = fmaxf(M, lse[(size_t)mrows[jj] * q_heads + hd]);
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    float wsum = 0.f;
+    if (M > -INFINITY) {
+      for (int jj = b; jj < e; ++jj) {
+        const size_t row = (size_t)mrows[jj] * q_heads + hd;
+        const float w = expf(lse[row] - M);
+        const float4 v = ((const float4*)part)[row * 32 + c4];
+        acc.x += w * v.x; acc.y += w * v.y; acc.z += w * v.z; acc.w += w * v.w;
+        wsum += w;
+      }
+      const float inv = 1.f / wsum;
+      acc.x *= inv; acc.y *= inv; acc.z *= inv; acc.w *= inv;
+    }
+    const size_t orow = (size_t)t * q_heads + hd;
+    if (OUT_BF16) {
+      typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
+      f32x4 f = {acc.x, acc.y, acc.z, acc.w};
+      ((bf16x4_t*)out)[orow * 32 + c4] = __builtin_convertvector(f, bf16x4_t);
+    } else {
+      ((float4*)out)[orow * 32 + c4] = acc;
+    }
+    if (lse_out && c4 == 0) lse_out[orow] = M > -INFINITY ? M + logf(wsum) : -INFINITY;
+  }
+}
+
+int ilog2(int x) {
+  int l = 0;
+  while ((1 << l) < x) ++l;
+  return l;
+}
+
+void fill_args(AttnArgs& a, const tl_plan* plan, const void* q, float scale, float* out, float* lse) {
+  a.q = (const uint16_t*)q;
+  a.tok = plan->d_tok;
+  a.slots = plan->d_slots;
+  a.out = out;
+  a.lse = lse;
+  a.q_heads = plan->q_heads;
+  a.kv_heads = plan->kv_heads;
+  a.log2g = ilog2(plan->group);
+  a.scale = scale;
+  a.scale_log2e = scale * 1.4426950408889634f;
+}
+
+}  // namespace
+}  // namespace tl
+
+using namespace tl;
+
+extern "C" {
+
+tl_status tl_segment_attn(const tl_pool* pool, tl_plan* plan, const void* q_dev, float scale, float* out_partial,
+                          float* lse, void* stream) {
+  if (!pool || !plan || !q_dev || !out_partial || !lse) TL_FAIL(TL_EINVAL, "tl_segment_attn: null argument");
+  if (plan->pool != pool) TL_FAIL(TL_EINVAL, "tl_segment_attn: plan was built for another pool");
+  if (!(scale > 0.f) || !std::isfinite(scale)) TL_FAIL(TL_EINVAL, "tl_segment_attn: scale must be positive and finite");
+  hipStream_t st = (hipStream_t)stream;
+  tl_status rc = pool_device_ready(pool, st);
+  if (rc != TL_OK) return rc;
+  rc = plan_device_ready(plan);
+  if (rc != TL_OK) return rc;
+  AttnArgs a;
+  fill_args(a, plan, q_dev, scale, out_partial, lse);
+  a.k = (const uint16_t*)pool->k_dev;
+  a.v = (const uint16_t*)pool->v_dev;
+  a.fill = pool->fill_dev;
+  a.seg_len = pool->seg_len;
+  a.work = plan->d_tiles;
+  a.n_work = (int)plan->tiles.size();
+  rc = launch_pool_row_tiles(a, a.n_work, st);
+  if (rc != TL_OK) return rc;
+  a.work = plan->d_units;
+  a.n_work = (int)plan->units.size();
+  return launch_splitk_units(a, a.n_work, st);
+}
+
+tl_status tl_causal_block(tl_plan* plan, const void* q_dev, const void* k_new_dev, const void* v_new_dev, float scale,
+                          float* out_partial, float* lse, void* stream) {
+  if (!plan || !q_dev || !k_new_dev || !v_new_dev || !out_partial || !lse) TL_FAIL(TL_EINVAL, "tl_causal_block: null argument");
+  if (!(plan->flags & TL_PLAN_SELF_BLOCK)) TL_FAIL(TL_EINVAL, "tl_causal_block: plan has no self block");
+  if (!(scale > 0.f) || !std::isfinite(scale)) TL_FAIL(TL_EINVAL, "tl_causal_block: scale must be positive and finite");
+  tl_status rc = plan_device_ready(plan);
+  if (rc != TL_OK) return rc;
+  AttnArgs a;
+  fill_args(a, plan, q_dev, scale, out_partial, lse);
+  a.k = (const uint16_t*)k_new_dev;
+  a.v = (const uint16_t*)v_new_dev;
+  a.fill = nullptr;
+  a.seg_len = 0;
+  a.work = plan->d_ctiles;
+  a.n_work = (int)plan->ctiles.size();
+  return launch_causal_row_tiles(a, a.n_work, (hipStream_t)stream);
+}
+
+tl_status tl_merge(tl_plan* plan, const float* out_partial, const float* lse, void* out_dev, int32_t out_is_bf16,
+                   float* lse_out, void* stream) {
+  if (!plan || !out_partial || !lse || !out_dev) TL_FAIL(TL_EINVAL, "tl_merge: null argument");
+  tl_status rc = plan_device_ready(plan);
+  if (rc != TL_OK) return rc;
+  if (plan->n_tokens == 0) return TL_OK;
+  hipStream_t st = (hipStream_t)stream;
+  const dim3 grid((unsigned)plan->n_tokens), block(256);
+  if (out_is_bf16)
+    hipLaunchKernelGGL(lse_merge_kernel<true>, grid, block, 0, st, out_partial, lse, plan->d_merge_ptr, plan->d_merge_rows,
+                       out_dev, lse_out, plan->q_heads);
+  else
+    hipLaunchKernelGGL(lse_merge_kernel<false>, grid, block, 0, st, out_partial, lse, plan->d_merge_ptr, plan->d_merge_rows,
+                       out_dev, lse_out, plan->q_heads);
+  TL_HIP(hipGetLastError());
+  return TL_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,332 @@
+// Host-side plan builder (paper Section 3.2: plans are generated per batch before the data
+// plane runs; Section 4.3: segments near the root of the prefix tree are hot, so requests
+// that share a run of segments are batched against it).
+//
+// Requests' slot lists are walked as a radix tree: a maximal run of list positions that the
+// same set of requests passes through becomes one work item whose query rows are all new
+// tokens of those requests.  Items with few rows per kv head are cut into split-K chunks.
+#include <algorithm>
+#include <cstring>
+#include <new>
+#include <unordered_set>
+
+#include "tl_internal.h"
+
+using namespace tl;
+
+namespace {
+
+struct RawItem {
+  std::vector<int32_t> reqs;   // ascending
+  int32_t src_req;             // request whose list supplies the run
+  int32_t begin, end;          // list positions [begin, end)
+};
+
+bool is_pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
+
+}  // namespace
+
+extern "C" {
+
+tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, int32_t n_req,
+                         const int32_t* req_row_ptr, const int32_t* req_seg_ptr, const uint64_t* seg_ids,
+                         int32_t flags, int32_t split_segments) {
+  if (!out) TL_FAIL(TL_EINVAL, "tl_plan_create: null out");
+  *out = nullptr;
+  if (!pool || n_req < 0 || !req_row_ptr || !req_seg_ptr) TL_FAIL(TL_EINVAL, "tl_plan_create: bad argument");
+  if (q_heads <= 0 || q_heads % pool->kv_heads) TL_FAIL(TL_EINVAL, "tl_plan_create: q_heads must be a multiple of kv_heads");
+  const int G = q_heads / pool->kv_heads;
+  if (!is_pow2(G) || G > 32) TL_FAIL(TL_EINVAL, "tl_plan_create: q_heads/kv_heads must be a power of two <= 32");
+  if (split_segments < 0) TL_FAIL(TL_EINVAL, "tl_plan_create: negative split_segments");
+  if (req_row_ptr[0] != 0 || req_seg_ptr[0] != 0) TL_FAIL(TL_EINVAL, "tl_plan_create: offsets must start at 0");
+  for (int32_t r = 0; r < n_req; ++r)
+    if (req_row_ptr[r + 1] < req_row_ptr[r] || req_seg_ptr[r + 1] < req_seg_ptr[r])
+      TL_FAIL(TL_EINVAL, "tl_plan_create: offsets of request %d decrease", r);
+  const int32_t T = req_row_ptr[n_req];
+  const int32_t n_entries = req_seg_ptr[n_req];
+  if (n_entries > 0 && !seg_ids) TL_FAIL(TL_EINVAL, "tl_plan_create: null seg_ids");
+
+  tl_plan* p = new (std::nothrow) tl_plan();
+  if (!p) TL_FAIL(TL_ENOMEM, "tl_plan_create: host allocation failed");
+  tl_status rc = TL_OK;
+  try {
+    p->pool = pool;
+    p->q_heads = q_heads;
+    p->kv_heads = pool->kv_heads;
+    p->group = G;
+    p->n_req = n_req;
+    p->n_tokens = T;
+    p->flags = flags;
+    p->on_device = false;
+    p->blob = nullptr;
+
+    // ---- a0: segment id -> slot ------------------------------------------------------
+    std::vector<int32_t> slots(n_entries);
+    for (int32_t i = 0; i < n_entries; ++i) {
+      auto it = pool->slot_of.find(seg_ids[i]);
+      if (it == pool->slot_of.end()) {
+        set_error("tl_plan_create: segment id %llu (list entry %d) is not resident", (unsigned long long)seg_ids[i], i);
+        delete p;
+        return TL_ENOTFOUND;
+      }
+      slots[i] = it->second;
+    }
+    const uint64_t now = ++pool->clock;
+    for (int32_t s : slots) pool->stamp[s] = now;
+
+    auto len_of = [&](int32_t r) { return req_seg_ptr[r + 1] - req_seg_ptr[r]; };
+    auto slot_at = [&](int32_t r, int32_t pos) { return slots[req_seg_ptr[r] + pos]; };
+    auto ntok_of = [&](int32_t r) { return req_row_ptr[r + 1] - req_row_ptr[r]; };
+
+    // ---- group requests along shared runs ----------------------------------------------
+    std::vector<RawItem> raw;
+    std::vector<int32_t> live;
+    for (int32_t r = 0; r < n_req; ++r)
+      if (ntok_of(r) > 0 && len_of(r) > 0) live.push_back(r);
+    if (flags & TL_PLAN_NO_SHARING) {
+      for (int32_t r : live) raw.push_back(RawItem{{r}, r, 0, len_of(r)});
+    } else {
+      struct Frame { std::vector<int32_t> reqs; int32_t depth; };
+      std::vector<Frame> stack;
+      stack.push_back(Frame{live, 0});
+      while (!stack.empty()) {
+        Frame f = std::move(stack.back());
+        stack.pop_back();
+        // partition by the slot at this depth, in order of first appearance
+        std::vector<int32_t> keys;
+        std::unordered_map<int32_t, std::vector<int32_t>> parts;
+        for (int32_t r : f.reqs) {
+          if (len_of(r) <= f.depth) continue;
+          int32_t s = slot_at(r, f.depth);
+          auto ins = parts.emplace(s, std::vector<int32_t>());
+          if (ins.second) keys.push_back(s);
+          ins.first->second.push_back(r);
+        }
+        // children pushed in reverse so that items come out in first-appearance order
+        std::vector<Frame> next;
+        for (int32_t s : keys) {
+          std::vector<int32_t>& sub = parts[s];
+          int32_t e = f.depth + 1;
+          for (;;) {
+            bool all_continue = true, any_continue = false;
+            for (int32_t r : sub) {
+              if (len_of(r) > e) any_continue = true; else all_continue = false;
+            }
+            if (!any_continue || !all_continue) break;       // somebody ends here: the set changes
+            int32_t s0 = slot_at(sub[0], e);
+            bool same = true;
+            for (int32_t r : sub) if (slot_at(r, e) != s0) { same = false; break; }
+            if (!same) break;
+            ++e;
+          }
+          raw.push_back(RawItem{sub, sub[0], f.depth, e});
+          next.push_back(Frame{sub, e});
+        }
+        for (auto it = next.rbegin(); it != next.rend(); ++it) stack.push_back(std::move(*it));
+      }
+    }
+
+    // ---- final items, work lists ----------------------------------------------------------
+    const int tok_tile = kRowTile / G;
+    int split = split_segments;
+    if (split == 0) split = std::max(1, 512 / pool->seg_len);
+    int32_t row_cursor = 0;
+    p->item_tok_ptr.push_back(0);
+    p->item_slot_ptr.push_back(0);
+    int64_t prefix_pairs = 0;
+    for (const RawItem& it : raw) {
+      int32_t n_tok = 0;
+      for (int32_t r : it.reqs) n_tok += ntok_of(r);
+      const bool few_rows = (int64_t)n_tok * G <= kUnitRows;
+      const int32_t run = it.end - it.begin;
+      const int32_t step = few_rows ? split : run;
+      for (int32_t c0 = 0; c0 < run; c0 += step) {
+        const int32_t c1 = std::min(run, c0 + step);
+        const int32_t tok_base = (int32_t)p->item_tokens.size();
+        for (int32_t r : it.reqs)
+          for (int32_t t = req_row_ptr[r]; t < req_row_ptr[r + 1]; ++t) p->item_tokens.push_back(t);
+        const int32_t slot_base = (int32_t)p->item_slots.size();
+        for (int32_t pos = it.begin + c0; pos < it.begin + c1; ++pos) {
+          int32_t s = slot_at(it.src_req, pos);
+          p->item_slots.push_back(s);
+          prefix_pairs += (int64_t)n_tok * pool->fill[s];
+        }
+        p->item_row_base.push_back(row_cursor);
+        p->item_tok_ptr.push_back((int32_t)p->item_tokens.size());
+        p->item_slot_ptr.push_back((int32_t)p->item_slots.size());
+        if (few_rows) {
+          p->units.push_back(Work{tok_base, n_tok, row_cursor, slot_base, c1 - c0});
+        } else {
+          // row tiles never straddle two requests' token ranges unless ranges are short:
+          // tokens are simply taken tok_tile at a time in item order (Q rows are gathered).
+          for (int32_t t0 = 0; t0 < n_tok; t0 += tok_tile)
+            p->tiles.push_back(Work{tok_base + t0, std::min(tok_tile, n_tok - t0), row_cursor + t0, slot_base, c1 - c0});
+        }
+        row_cursor += n_tok;
+      }
+    }
+    // the token array doubles as the tile token list
+    p->tok = p->item_tokens;
+
+    const int32_t n_items = (int32_t)p->item_row_base.size();
+    int32_t self_base = -1;
+    int64_t self_pairs = 0;
+    if (flags & TL_PLAN_SELF_BLOCK) {
+      self_base = row_cursor;
+      const int32_t ident_base = (int32_t)p->tok.size();
+      for (int32_t t = 0; t < T; ++t) p->tok.push_back(t);
+      for (int32_t r = 0; r < n_req; ++r) {
+        const int32_t a = req_row_ptr[r], b = req_row_ptr[r + 1];
+        const int64_t lq = b - a;
+        self_pairs += lq * (lq + 1) / 2;
+        for (int32_t t0 = a; t0 < b; t0 += tok_tile) {
+          const int32_t n = std::min(tok_tile, b - t0);
+          p->ctiles.push_back(Work{ident_base + t0, n, self_base + t0, a, t0 + n - a});
+        }
+      }
+      row_cursor += T;
+    }
+
+    // longest first, so that the tail of the launch is made of short work
+    auto by_len = [&](const Work& x, const Work& y) { return x.kv_len > y.kv_len; };
+    std::stable_sort(p->tiles.begin(), p->tiles.end(), by_len);
+    std::stable_sort(p->units.begin(), p->units.end(), by_len);
+    std::stable_sort(p->ctiles.begin(), p->ctiles.end(), by_len);
+
+    // ---- merge lists --------------------------------------------------------------------------
+    p->merge_ptr.assign(T + 1, 0);
+    for (int32_t i = 0; i < n_items; ++i)
+      for (int32_t j = p->item_tok_ptr[i]; j < p->item_tok_ptr[i + 1]; ++j) p->merge_ptr[p->item_tokens[j] + 1]++;
+    if (self_base >= 0)
+      for (int32_t t = 0; t < T; ++t) p->merge_ptr[t + 1]++;
+    for (int32_t t = 0; t < T; ++t) p->merge_ptr[t + 1] += p->merge_ptr[t];
+    p->merge_rows.assign(p->merge_ptr[T], 0);
+    {
+      std::vector<int32_t> cur(p->merge_ptr.begin(), p->merge_ptr.end() - 1);
+      for (int32_t i = 0; i < n_items; ++i)
+        for (int32_t j = p->item_tok_ptr[i]; j < p->item_tok_ptr[i + 1]; ++j)
+          p->merge_rows[cur[p->item_tokens[j]]++] = p->item_row_base[i] + (j - p->item_tok_ptr[i]);
+      if (self_base >= 0)
+        for (int32_t t = 0; t < T; ++t) p->merge_rows[cur[t]++] = self_base + t;
+    }
+
+    std::unordered_set<int32_t> uniq(slots.begin(), slots.end());
+    int64_t uniq_tok = 0;
+    for (int32_t s : uniq) uniq_tok += pool->fill[s];
+
+    tl_plan_info& inf = p->info;
+    memset(&inf, 0, sizeof(inf));
+    inf.n_req = n_req;
+    inf.n_tokens = T;
+    inf.q_heads = q_heads;
+    inf.kv_heads = pool->kv_heads;
+    inf.n_items = n_items;
+    inf.n_partial_rows = row_cursor;
+    inf.self_row_base = self_base;
+    inf.n_tiles = (int32_t)p->tiles.size();
+    inf.n_units = (int32_t)p->units.size();
+    inf.n_causal_tiles = (int32_t)p->ctiles.size();
+    inf.n_list_entries = n_entries;
+    inf.n_merge_entries = (int32_t)p->merge_rows.size();
+    inf.prefix_pairs = prefix_pairs;
+    inf.self_pairs = self_pairs;
+    inf.unique_kv_tokens = uniq_tok;
+  } catch (const std::bad_alloc&) {
+    rc = TL_ENOMEM;
+    set_error("tl_plan_create: host allocation failed");
+  }
+  if (rc != TL_OK) {
+    delete p;
+    return rc;
+  }
+  *out = p;
+  return TL_OK;
+}
+
+tl_status tl_plan_destroy(tl_plan* plan) {
+  if (!plan) return TL_OK;
+  if (plan->blob) (void)hipFree(plan->blob);
+  delete plan;
+  return TL_OK;
+}
+
+tl_status tl_plan_get_info(const tl_plan* plan, tl_plan_info* info) {
+  if (!plan || !info) TL_FAIL(TL_EINVAL, "tl_plan_get_info: bad argument");
+  *info = plan->info;
+  return TL_OK;
+}
+
+tl_status tl_plan_export_sizes(const tl_plan* plan, int32_t* n_item_tokens, int32_t* n_item_slots) {
+  if (!plan) TL_FAIL(TL_EINVAL, "tl_plan_export_sizes: null plan");
+  if (n_item_tokens) *n_item_tokens = (int32_t)plan->item_tokens.size();
+  if (n_item_slots) *n_item_slots = (int32_t)plan->item_slots.size();
+  return TL_OK;
+}
+
+tl_status tl_plan_export(const tl_plan* plan, int32_t* item_row_base, int32_t* item_tok_ptr, int32_t* item_tokens,
+                         int32_t* item_slot_ptr, int32_t* item_slots, int32_t* merge_ptr, int32_t* merge_rows) {
+  if (!plan) TL_FAIL(TL_EINVAL, "tl_plan_export: null plan");
+  auto cp = [](int32_t* dst, const std::vector<int32_t>& src) {
+    if (dst && !src.empty()) memcpy(dst, src.data(), sizeof(int32_t) * src.size());
+  };
+  cp(item_row_base, plan->item_row_base);
+  cp(item_tok_ptr, plan->item_tok_ptr);
+  cp(item_tokens, plan->item_tokens);
+  cp(item_slot_ptr, plan->item_slot_ptr);
+  cp(item_slots, plan->item_slots);
+  cp(merge_ptr, plan->merge_ptr);
+  cp(merge_rows, plan->merge_rows);
+  return TL_OK;
+}
+
+}  // extern "C"
+
+namespace tl {
+
+tl_status plan_device_ready(tl_plan* p) {
+  if (p->on_device) return TL_OK;
+  auto al = [](size_t x) { return (x + 255) & ~(size_t)255; };
+  const size_t b_tiles = al(sizeof(Work) * p->tiles.size());
+  const size_t b_units = al(sizeof(Work) * p->units.size());
+  const size_t b_ctiles = al(sizeof(Work) * p->ctiles.size());
+  const size_t b_tok = al(sizeof(int32_t) * p->tok.size());
+  const size_t b_slots = al(sizeof(int32_t) * p->item_slots.size());
+  const size_t b_mptr = al(sizeof(int32_t) * p->merge_ptr.size());
+  const size_t b_mrows = al(sizeof(int32_t) * p->merge_rows.size());
+  const size_t total = b_tiles + b_units + b_ctiles + b_tok + b_slots + b_mptr + b_mrows + 256;
+  std::vector<char> host(total, 0);
+  size_t off = 0;
+  auto put = [&](const void* src, size_t bytes, size_t reserved) {
+    size_t at = off;
+    if (bytes) memcpy(host.data() + off, src, bytes);
+    off += reserved;
+    return at;
+  };
+  const size_t o_tiles = put(p->tiles.data(), sizeof(Work) * p->tiles.size(), b_tiles);
+  const size_t o_units = put(p->units.data(), sizeof(Work) * p->units.size(), b_units);
+  const size_t o_ctiles = put(p->ctiles.data(), sizeof(Work) * p->ctiles.size(), b_ctiles);
+  const size_t o_tok = put(p->tok.data(), sizeof(int32_t) * p->tok.size(), b_tok);
+  const size_t o_slots = put(p->item_slots.data(), sizeof(int32_t) * p->item_slots.size(), b_slots);
+  const size_t o_mptr = put(p->merge_ptr.data(), sizeof(int32_t) * p->merge_ptr.size(), b_mptr);
+  const size_t o_mrows = put(p->merge_rows.data(), sizeof(int32_t) * p->merge_rows.size(), b_mrows);
+  void* blob = nullptr;
+  TL_HIP(hipMalloc(&blob, total));
+  hipError_t e = hipMemcpy(blob, host.data(), total, hipMemcpyHostToDevice);
+  if (e != hipSuccess) {
+    (void)hipFree(blob);
+    TL_FAIL(TL_EHIP, "plan upload failed: %s", hipGetErrorString(e));
+  }
+  char* b = (char*)blob;
+  p->blob = blob;
+  p->d_tiles = (Work*)(b + o_tiles);
+  p->d_units = (Work*)(b + o_units);
+  p->d_ctiles = (Work*)(b + o_ctiles);
+  p->d_tok = (int32_t*)(b + o_tok);
+  p->d_slots = (int32_t*)(b + o_slots);
+  p->d_merge_ptr = (int32_t*)(b + o_mptr);
+  p->d_merge_rows = (int32_t*)(b + o_mrows);
+  p->on_device = true;
+  return TL_OK;
+}
+
+}  // namespace tl

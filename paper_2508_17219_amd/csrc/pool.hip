@@ -1,0 +1,311 @@
+// Segment pool: id -> slot table, per-slot fill / reference count / last-use stamp on the
+// host; K/V slots and a mirror of fill[] on the device.  (Paper Section 3.1: fixed-size
+// segments in cache slots; Section 1 and 4: one copy per segment; Section 4.3: eviction by
+// last access time.)
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "tl_internal.h"
+
+namespace tl {
+
+static thread_local char g_err[512] = "";
+static int g_opt_vread = 0;
+
+void set_error(const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+}
+
+int get_option_vread() { return g_opt_vread; }
+
+// 16 bytes per thread, grid-stride.  dst/src are 16-byte aligned (rows are 256 B).
+__global__ void copy16_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src, size_t n16) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n16; i += stride) dst[i] = src[i];
+}
+
+__global__ void zero16_kernel(uint4* __restrict__ dst, size_t n16) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n16; i += stride) dst[i] = make_uint4(0, 0, 0, 0);
+}
+
+__global__ void set_i32_kernel(int32_t* p, int32_t idx, int32_t v) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) p[idx] = v;
+}
+
+// out[(i, :)] = pool[(slots[i], :)], slot_elems16 uint4 per slot; one block column per slot.
+__global__ void gather_slots_kernel(uint4* __restrict__ out, const uint4* __restrict__ pool,
+                                    const int32_t* __restrict__ slots, size_t slot16) {
+  const int32_t s = slots[blockIdx.y];
+  const uint4* src = pool + (size_t)s * slot16;
+  uint4* dst = out + (size_t)blockIdx.y * slot16;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < slot16; i += (size_t)gridDim.x * blockDim.x)
+    dst[i] = src[i];
+}
+
+static int blocks_for(size_t n16) {
+  size_t b = (n16 + 255) / 256;
+  if (b > 4096) b = 4096;
+  if (b < 1) b = 1;
+  return (int)b;
+}
+
+tl_status pool_device_ready(const tl_pool* pool, hipStream_t stream) {
+  if (!pool->fill_dev) {
+    int32_t* p = nullptr;
+    TL_HIP(hipMalloc((void**)&p, sizeof(int32_t) * (size_t)pool->n_slots));
+    pool->fill_dev = p;
+    pool->fill_dirty = true;
+  }
+  if (pool->fill_dirty) {
+    TL_HIP(hipMemcpyAsync(pool->fill_dev, pool->fill.data(), sizeof(int32_t) * (size_t)pool->n_slots,
+                          hipMemcpyHostToDevice, stream));
+    pool->fill_dirty = false;
+  }
+  return TL_OK;
+}
+
+}  // namespace tl
+
+using namespace tl;
+
+extern "C" {
+
+const char* tl_status_str(tl_status s) {
+  switch (s) {
+    case TL_OK: return "ok";
+    case TL_EINVAL: return "invalid argument";
+    case TL_ENOMEM: return "out of memory";
+    case TL_EFULL: return "pool full";
+    case TL_ENOTFOUND: return "segment not found";
+    case TL_EHIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+const char* tl_last_error(void) { return g_err; }
+
+tl_status tl_set_option(const char* knob, int32_t value) {
+  if (!knob) TL_FAIL(TL_EINVAL, "tl_set_option: null knob");
+  if (!strcmp(knob, "vread")) {
+    if (value < 0 || value > 1) TL_FAIL(TL_EINVAL, "tl_set_option: vread must be 0 or 1");
+    g_opt_vread = value;
+    return TL_OK;
+  }
+  TL_FAIL(TL_EINVAL, "tl_set_option: unknown knob '%s'", knob);
+}
+
+tl_status tl_pool_create(tl_pool** out, int32_t n_slots, int32_t seg_len, int32_t kv_heads, int32_t head_dim,
+                         void* k_dev, void* v_dev) {
+  if (!out) TL_FAIL(TL_EINVAL, "tl_pool_create: null out");
+  *out = nullptr;
+  if (n_slots <= 0 || seg_len <= 0 || kv_heads <= 0) TL_FAIL(TL_EINVAL, "tl_pool_create: non-positive size");
+  if (head_dim != kHeadDim) TL_FAIL(TL_EINVAL, "tl_pool_create: head_dim must be %d", kHeadDim);
+  if (seg_len % kKvTile) TL_FAIL(TL_EINVAL, "tl_pool_create: seg_len must be a multiple of %d", kKvTile);
+  if ((int64_t)n_slots * seg_len > (int64_t)INT32_MAX)
+    TL_FAIL(TL_EINVAL, "tl_pool_create: n_slots * seg_len exceeds 2^31-1 tokens");
+  if ((k_dev == nullptr) != (v_dev == nullptr)) TL_FAIL(TL_EINVAL, "tl_pool_create: give both k_dev and v_dev or neither");
+  tl_pool* p = new (std::nothrow) tl_pool();
+  if (!p) TL_FAIL(TL_ENOMEM, "tl_pool_create: host allocation failed");
+  p->n_slots = n_slots;
+  p->seg_len = seg_len;
+  p->kv_heads = kv_heads;
+  p->head_dim = head_dim;
+  p->k_dev = k_dev;
+  p->v_dev = v_dev;
+  p->owns_kv = false;
+  p->clock = 0;
+  p->n_used = 0;
+  p->free_hint = 0;
+  p->fill_dev = nullptr;
+  p->fill_dirty = true;
+  try {
+    p->id_of.assign(n_slots, 0);
+    p->fill.assign(n_slots, 0);
+    p->refcnt.assign(n_slots, 0);
+    p->stamp.assign(n_slots, 0);
+  } catch (...) {
+    delete p;
+    TL_FAIL(TL_ENOMEM, "tl_pool_create: host allocation failed");
+  }
+  if (!k_dev) {
+    size_t bytes = (size_t)n_slots * seg_len * kv_heads * head_dim * 2;
+    hipError_t e = hipMalloc(&p->k_dev, bytes);
+    if (e == hipSuccess) e = hipMalloc(&p->v_dev, bytes);
+    if (e != hipSuccess) {
+      if (p->k_dev) (void)hipFree(p->k_dev);
+      delete p;
+      set_error("tl_pool_create: hipMalloc of %zu bytes x2 failed: %s", bytes, hipGetErrorString(e));
+      return e == hipErrorOutOfMemory ? TL_ENOMEM : TL_EHIP;
+    }
+    p->owns_kv = true;
+  }
+  *out = p;
+  return TL_OK;
+}
+
+tl_status tl_pool_destroy(tl_pool* pool) {
+  if (!pool) return TL_OK;
+  if (pool->fill_dev) (void)hipFree(pool->fill_dev);
+  if (pool->owns_kv) {
+    (void)hipFree(pool->k_dev);
+    (void)hipFree(pool->v_dev);
+  }
+  delete pool;
+  return TL_OK;
+}
+
+static int32_t take_slot(tl_pool* p, int32_t want) {
+  if (want >= 0) return want;
+  int32_t s = p->free_hint;
+  while (s < p->n_slots && p->fill[s] != 0) ++s;
+  p->free_hint = s;
+  return s < p->n_slots ? s : -1;
+}
+
+static void occupy(tl_pool* p, int32_t slot, uint64_t id, int32_t fill) {
+  p->slot_of.emplace(id, slot);
+  p->id_of[slot] = id;
+  p->fill[slot] = fill;
+  p->refcnt[slot] = 1;
+  p->stamp[slot] = ++p->clock;
+  p->n_used++;
+}
+
+tl_status tl_pool_put(tl_pool* pool, uint64_t segment_id, const void* k_src_dev, const void* v_src_dev, int32_t fill,
+                      int32_t want_slot, int32_t* slot_out, void* stream) {
+  if (!pool) TL_FAIL(TL_EINVAL, "tl_pool_put: null pool");
+  auto it = pool->slot_of.find(segment_id);
+  if (it != pool->slot_of.end()) {
+    int32_t s = it->second;
+    pool->refcnt[s]++;
+    pool->stamp[s] = ++pool->clock;
+    if (slot_out) *slot_out = s;
+    return TL_OK;
+  }
+  if (!k_src_dev || !v_src_dev) TL_FAIL(TL_EINVAL, "tl_pool_put: null source");
+  if (fill < 1 || fill > pool->seg_len) TL_FAIL(TL_EINVAL, "tl_pool_put: fill %d outside 1..%d", fill, pool->seg_len);
+  if (want_slot >= pool->n_slots || want_slot < -1) TL_FAIL(TL_EINVAL, "tl_pool_put: slot %d out of range", want_slot);
+  if (want_slot >= 0 && pool->fill[want_slot] != 0) TL_FAIL(TL_EINVAL, "tl_pool_put: slot %d is taken", want_slot);
+  int32_t s = take_slot(pool, want_slot);
+  if (s < 0) TL_FAIL(TL_EFULL, "tl_pool_put: no free slot (%d in use)", pool->n_used);
+  hipStream_t st = (hipStream_t)stream;
+  tl_status rc = pool_device_ready(pool, st);
+  if (rc != TL_OK) return rc;
+  const size_t row16 = (size_t)pool->kv_heads * pool->head_dim * 2 / 16;
+  const size_t slot16 = row16 * pool->seg_len;
+  const size_t n16 = row16 * fill;
+  uint4* kd = (uint4*)pool->k_dev + (size_t)s * slot16;
+  uint4* vd = (uint4*)pool->v_dev + (size_t)s * slot16;
+  hipLaunchKernelGGL(copy16_kernel, dim3(blocks_for(n16)), dim3(256), 0, st, kd, (const uint4*)k_src_dev, n16);
+  hipLaunchKernelGGL(copy16_kernel, dim3(blocks_for(n16)), dim3(256), 0, st, vd, (const uint4*)v_src_dev, n16);
+  if (n16 < slot16) {
+    hipLaunchKernelGGL(zero16_kernel, dim3(blocks_for(slot16 - n16)), dim3(256), 0, st, kd + n16, slot16 - n16);
+    hipLaunchKernelGGL(zero16_kernel, dim3(blocks_for(slot16 - n16)), dim3(256), 0, st, vd + n16, slot16 - n16);
+  }
+  hipLaunchKernelGGL(set_i32_kernel, dim3(1), dim3(64), 0, st, pool->fill_dev, s, fill);
+  TL_HIP(hipGetLastError());
+  occupy(pool, s, segment_id, fill);
+  if (slot_out) *slot_out = s;
+  return TL_OK;
+}
+
+tl_status tl_pool_adopt(tl_pool* pool, const uint64_t* ids, const int32_t* slots, const int32_t* fills, int32_t n,
+                        void* stream) {
+  (void)stream;
+  if (!pool || n < 0 || (n > 0 && (!ids || !slots || !fills))) TL_FAIL(TL_EINVAL, "tl_pool_adopt: bad argument");
+  // validate everything first so that a failure registers nothing
+  std::unordered_map<uint64_t, int> seen_id;
+  std::unordered_map<int32_t, int> seen_slot;
+  for (int32_t i = 0; i < n; ++i) {
+    if (slots[i] < 0 || slots[i] >= pool->n_slots) TL_FAIL(TL_EINVAL, "tl_pool_adopt: slot %d out of range", slots[i]);
+    if (fills[i] < 1 || fills[i] > pool->seg_len) TL_FAIL(TL_EINVAL, "tl_pool_adopt: fill %d outside 1..%d", fills[i], pool->seg_len);
+    if (pool->fill[slots[i]] != 0) TL_FAIL(TL_EINVAL, "tl_pool_adopt: slot %d is taken", slots[i]);
+    if (pool->slot_of.count(ids[i])) TL_FAIL(TL_EINVAL, "tl_pool_adopt: id %llu already resident", (unsigned long long)ids[i]);
+    if (!seen_id.emplace(ids[i], i).second) TL_FAIL(TL_EINVAL, "tl_pool_adopt: id %llu listed twice", (unsigned long long)ids[i]);
+    if (!seen_slot.emplace(slots[i], i).second) TL_FAIL(TL_EINVAL, "tl_pool_adopt: slot %d listed twice", slots[i]);
+  }
+  for (int32_t i = 0; i < n; ++i) occupy(pool, slots[i], ids[i], fills[i]);
+  pool->fill_dirty = true;
+  return TL_OK;
+}
+
+tl_status tl_pool_release(tl_pool* pool, uint64_t segment_id) {
+  if (!pool) TL_FAIL(TL_EINVAL, "tl_pool_release: null pool");
+  auto it = pool->slot_of.find(segment_id);
+  if (it == pool->slot_of.end()) TL_FAIL(TL_ENOTFOUND, "tl_pool_release: id %llu not resident", (unsigned long long)segment_id);
+  if (pool->refcnt[it->second] <= 0) TL_FAIL(TL_EINVAL, "tl_pool_release: id %llu has no references", (unsigned long long)segment_id);
+  pool->refcnt[it->second]--;
+  return TL_OK;
+}
+
+tl_status tl_pool_evict_lru(tl_pool* pool, uint64_t* evicted_id) {
+  if (!pool) TL_FAIL(TL_EINVAL, "tl_pool_evict_lru: null pool");
+  int32_t best = -1;
+  for (int32_t s = 0; s < pool->n_slots; ++s)
+    if (pool->fill[s] != 0 && pool->refcnt[s] == 0 && (best < 0 || pool->stamp[s] < pool->stamp[best])) best = s;
+  if (best < 0) TL_FAIL(TL_ENOTFOUND, "tl_pool_evict_lru: no segment with zero references");
+  if (evicted_id) *evicted_id = pool->id_of[best];
+  pool->slot_of.erase(pool->id_of[best]);
+  pool->fill[best] = 0;
+  pool->n_used--;
+  if (best < pool->free_hint) pool->free_hint = best;
+  pool->fill_dirty = true;
+  return TL_OK;
+}
+
+tl_status tl_pool_lookup(const tl_pool* pool, const uint64_t* ids, int32_t n, int32_t* slots_out) {
+  if (!pool || n < 0 || (n > 0 && (!ids || !slots_out))) TL_FAIL(TL_EINVAL, "tl_pool_lookup: bad argument");
+  for (int32_t i = 0; i < n; ++i) {
+    auto it = pool->slot_of.find(ids[i]);
+    slots_out[i] = it == pool->slot_of.end() ? -1 : it->second;
+  }
+  return TL_OK;
+}
+
+tl_status tl_pool_fills(const tl_pool* pool, const int32_t* slots, int32_t n, int32_t* fills_out) {
+  if (!pool || n < 0 || (n > 0 && (!slots || !fills_out))) TL_FAIL(TL_EINVAL, "tl_pool_fills: bad argument");
+  for (int32_t i = 0; i < n; ++i) {
+    if (slots[i] < 0 || slots[i] >= pool->n_slots) TL_FAIL(TL_EINVAL, "tl_pool_fills: slot %d out of range", slots[i]);
+    fills_out[i] = pool->fill[slots[i]];
+  }
+  return TL_OK;
+}
+
+tl_status tl_pool_used(const tl_pool* pool, int32_t* n_used) {
+  if (!pool || !n_used) TL_FAIL(TL_EINVAL, "tl_pool_used: bad argument");
+  *n_used = pool->n_used;
+  return TL_OK;
+}
+
+tl_status tl_pool_gather(tl_pool* pool, const int32_t* slots, int32_t n, void* k_out_dev, void* v_out_dev, void* stream) {
+  if (!pool || n < 0 || (n > 0 && (!slots || !k_out_dev || !v_out_dev))) TL_FAIL(TL_EINVAL, "tl_pool_gather: bad argument");
+  if (n == 0) return TL_OK;
+  if (n > 65535) TL_FAIL(TL_EINVAL, "tl_pool_gather: at most 65535 slots per call");
+  for (int32_t i = 0; i < n; ++i)
+    if (slots[i] < 0 || slots[i] >= pool->n_slots) TL_FAIL(TL_EINVAL, "tl_pool_gather: slot %d out of range", slots[i]);
+  hipStream_t st = (hipStream_t)stream;
+  int32_t* d_slots = nullptr;
+  TL_HIP(hipMalloc((void**)&d_slots, sizeof(int32_t) * (size_t)n));
+  hipError_t e = hipMemcpyAsync(d_slots, slots, sizeof(int32_t) * (size_t)n, hipMemcpyHostToDevice, st);
+  if (e == hipSuccess) {
+    const size_t slot16 = (size_t)pool->seg_len * pool->kv_heads * pool->head_dim * 2 / 16;
+    dim3 grid((unsigned)(slot16 / 256 > 64 ? 64 : (slot16 + 255) / 256), (unsigned)n);
+    hipLaunchKernelGGL(gather_slots_kernel, grid, dim3(256), 0, st, (uint4*)k_out_dev, (const uint4*)pool->k_dev, d_slots, slot16);
+    hipLaunchKernelGGL(gather_slots_kernel, grid, dim3(256), 0, st, (uint4*)v_out_dev, (const uint4*)pool->v_dev, d_slots, slot16);
+    e = hipGetLastError();
+    if (e == hipSuccess) e = hipStreamSynchronize(st);   // d_slots is freed below
+  }
+  (void)hipFree(d_slots);
+  if (e != hipSuccess) TL_FAIL(TL_EHIP, "tl_pool_gather: %s", hipGetErrorString(e));
+  return TL_OK;
+}
+
+}  // extern "C"

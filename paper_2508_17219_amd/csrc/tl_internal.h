@@ -1,0 +1,85 @@
+// Internal declarations shared by the host side of the library (not part of the ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <unordered_map>
+#include <vector>
+
+#include "tokenlake.h"
+
+namespace tl {
+
+void set_error(const char* fmt, ...) __attribute__((format(printf, 1, 2)));
+
+#define TL_FAIL(code, ...)        \
+  do {                            \
+    ::tl::set_error(__VA_ARGS__); \
+    return (code);                \
+  } while (0)
+
+#define TL_HIP(expr)                                                          \
+  do {                                                                        \
+    hipError_t e_ = (expr);                                                   \
+    if (e_ != hipSuccess) {                                                   \
+      ::tl::set_error("%s failed: %s", #expr, hipGetErrorString(e_));         \
+      return TL_EHIP;                                                         \
+    }                                                                         \
+  } while (0)
+
+constexpr int kHeadDim = 128;
+constexpr int kKvTile = 64;      // kv tokens per LDS tile of the row-tile kernel
+constexpr int kRowTile = 256;    // query rows (token x head-in-group) per workgroup
+constexpr int kUnitRows = 16;    // max rows per kv head of a split-K unit
+
+// One unit of kernel work.  Its query tokens are tok[tok_off .. tok_off+n_tok) (batch token
+// indices), its partial rows out_row .. out_row+n_tok-1.
+//  pool work:   kv_off/kv_len index the plan's slot-list array.
+//  causal work: kv_off = first new token of the request, kv_len = new tokens visible to the
+//               last row of the tile; tokens of the tile are consecutive.
+struct Work {
+  int32_t tok_off, n_tok, out_row, kv_off, kv_len;
+};
+
+int get_option_vread();
+
+}  // namespace tl
+
+struct tl_pool {
+  int32_t n_slots, seg_len, kv_heads, head_dim;
+  void* k_dev;
+  void* v_dev;
+  bool owns_kv;
+  std::unordered_map<uint64_t, int32_t> slot_of;
+  std::vector<uint64_t> id_of;
+  std::vector<int32_t> fill;     // 0 = free
+  std::vector<int32_t> refcnt;
+  mutable std::vector<uint64_t> stamp;
+  mutable uint64_t clock;
+  int32_t n_used;
+  int32_t free_hint;             // no free slot below this index
+  // device mirror of fill[]
+  mutable int32_t* fill_dev;
+  mutable bool fill_dirty;
+};
+
+struct tl_plan {
+  const tl_pool* pool;
+  int32_t q_heads, kv_heads, group, n_req, n_tokens, flags;
+  tl_plan_info info;
+  std::vector<int32_t> item_row_base, item_tok_ptr, item_tokens, item_slot_ptr, item_slots;
+  std::vector<int32_t> merge_ptr, merge_rows;
+  std::vector<tl::Work> tiles, units, ctiles;
+  std::vector<int32_t> tok;      // token index array referenced by Work::tok_off
+  // device copies (made on first use)
+  bool on_device;
+  void* blob;
+  tl::Work *d_tiles, *d_units, *d_ctiles;
+  int32_t *d_tok, *d_slots, *d_merge_ptr, *d_merge_rows;
+};
+
+namespace tl {
+tl_status pool_device_ready(const tl_pool* pool, hipStream_t stream);
+tl_status plan_device_ready(tl_plan* plan);
+}  // namespace tl

@@ -1,0 +1,189 @@
+"""CPU-side checks of the C-ABI library: it loads, exports what the header declares, and its
+host logic (segment table, plan builder) does integer work that matches the oracle's table
+and covers every (query token, list entry) pair exactly once.  No compute call is made."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import tokenlake_oracle as orc
+from paper_2508_17219_amd import binding as B
+from paper_2508_17219_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE_K, FAKE_V = 0x100000, 0x200000          # never dereferenced: host logic only
+
+
+def test_library_exports_every_declared_symbol():
+    text = open(os.path.join(ROOT, "include", "tokenlake.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(tl_[a-z0-9_]+)\s*\(", text))
+    assert declared == set(B.EXPORTED), declared ^ set(B.EXPORTED)
+    lib = B.load_library()
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert lib.tl_status_str(0) == b"ok" and lib.tl_status_str(-4) == b"segment not found"
+
+
+def _pool_for(b):
+    pool = B.tl_pool_create(b.n_slots, b.seg_len, b.kv_heads, b.head_dim, FAKE_K, FAKE_V)
+    B.tl_pool_adopt(pool, b.pool_ids, b.pool_slots, b.pool_fills)
+    return pool
+
+
+def test_create_rejects_bad_shapes():
+    for args in [(0, 128, 2, 128), (8, 100, 2, 128), (8, 128, 2, 64), (8, 128, 0, 128), (1 << 24, 256, 8, 128)]:
+        with pytest.raises(B.TokenLakeError) as e:
+            B.tl_pool_create(*args, FAKE_K, FAKE_V)
+        assert e.value.status == B.TL_EINVAL
+    with pytest.raises(B.TokenLakeError):
+        B.tl_pool_create(8, 128, 2, 128, FAKE_K, None)
+
+
+def test_segment_table_matches_oracle_table():
+    rng = np.random.default_rng(0)
+    n_slots, C = 64, 128
+    pool = B.tl_pool_create(n_slots, C, 2, 128, FAKE_K, FAKE_V)
+    table = orc.SlotTable(n_slots, C)
+    ids = rng.integers(0, 2 ** 63, size=40, dtype=np.uint64)
+    slots = rng.permutation(n_slots)[:40].astype(np.int32)
+    fills = rng.integers(1, C + 1, size=40).astype(np.int32)
+    B.tl_pool_adopt(pool, ids, slots, fills)
+    for i, s, f in zip(ids, slots, fills):
+        table.put(int(i), int(f), int(s))
+    probe = np.concatenate([ids[::-1], rng.integers(0, 2 ** 63, size=10, dtype=np.uint64)])
+    assert np.array_equal(B.tl_pool_lookup(pool, probe), table.lookup(probe))
+    assert np.array_equal(B.tl_pool_fills(pool, slots), table.fill(slots))
+    assert B.tl_pool_used(pool) == 40
+    # adopt is all-or-nothing
+    with pytest.raises(B.TokenLakeError):
+        B.tl_pool_adopt(pool, [999, ids[0]], [int(np.setdiff1d(np.arange(n_slots), slots)[0]), 1], [5, 5])
+    assert B.tl_pool_lookup(pool, [999])[0] == -1
+    with pytest.raises(B.TokenLakeError):
+        B.tl_pool_adopt(pool, [1000], [int(slots[0])], [5])          # slot taken
+    with pytest.raises(B.TokenLakeError):
+        B.tl_pool_adopt(pool, [1001], [int(np.setdiff1d(np.arange(n_slots), slots)[0])], [C + 1])
+    B.tl_pool_destroy(pool)
+
+
+def test_release_and_lru_eviction():
+    pool = B.tl_pool_create(4, 64, 1, 128, FAKE_K, FAKE_V)
+    B.tl_pool_adopt(pool, [10, 11, 12, 13], [0, 1, 2, 3], [64, 64, 64, 64])
+    with pytest.raises(B.TokenLakeError) as e:
+        B.tl_pool_evict_lru(pool)                                     # everything is referenced
+    assert e.value.status == B.TL_ENOTFOUND
+    for i in (10, 11, 12):
+        B.tl_pool_release(pool, i)
+    with pytest.raises(B.TokenLakeError):
+        B.tl_pool_release(pool, 10)                                   # already at zero
+    # a plan that names id 10 makes it the most recently used
+    plan = B.tl_plan_create(pool, 1, [0, 1], [0, 1], np.array([10], np.uint64), 0, 0)
+    B.tl_plan_destroy(plan)
+    assert B.tl_pool_evict_lru(pool) == 11
+    assert B.tl_pool_evict_lru(pool) == 12
+    assert B.tl_pool_evict_lru(pool) == 10
+    assert B.tl_pool_used(pool) == 1 and list(B.tl_pool_lookup(pool, [10, 13])) == [-1, 3]
+    B.tl_pool_adopt(pool, [20], [1], [7])
+    assert list(B.tl_pool_fills(pool, [0, 1, 2, 3])) == [0, 7, 0, 64]
+    B.tl_pool_destroy(pool)
+
+
+def _check_plan_covers(b, plan, flags):
+    info = B.tl_plan_get_info(plan)
+    ex = B.tl_plan_export(plan)
+    slots = B.tl_pool_lookup(plan_pool[0], b.seg_ids)
+    T = b.n_tokens
+    assert info.n_tokens == T and info.n_req == b.n_req
+    # each token's multiset of slots over its items == its request's list
+    got = [[] for _ in range(T)]
+    rows_seen = set()
+    for i in range(info.n_items):
+        toks = ex["item_tokens"][ex["item_tok_ptr"][i]:ex["item_tok_ptr"][i + 1]]
+        its = ex["item_slots"][ex["item_slot_ptr"][i]:ex["item_slot_ptr"][i + 1]]
+        assert len(its) > 0 and len(toks) > 0
+        for jpos, t in enumerate(toks):
+            got[int(t)].extend(int(s) for s in its)
+            row = int(ex["item_row_base"][i]) + jpos
+            assert row not in rows_seen
+            rows_seen.add(row)
+    for r in range(b.n_req):
+        want = sorted(int(s) for s in slots[b.req_seg_ptr[r]:b.req_seg_ptr[r + 1]])
+        for t in range(b.req_row_ptr[r], b.req_row_ptr[r + 1]):
+            assert sorted(got[t]) == want, (r, t)
+    n_item_rows = len(rows_seen)
+    assert rows_seen == set(range(n_item_rows))
+    self_rows = T if flags & B.TL_PLAN_SELF_BLOCK else 0
+    assert info.n_partial_rows == n_item_rows + self_rows
+    assert info.self_row_base == (n_item_rows if self_rows else -1)
+    # merge lists: every partial row exactly once, under its own token
+    mp, mr = ex["merge_ptr"], ex["merge_rows"]
+    assert mp[0] == 0 and mp[-1] == len(mr) == info.n_merge_entries == info.n_partial_rows
+    assert sorted(mr.tolist()) == list(range(info.n_partial_rows))
+    row_tok = {}
+    for i in range(info.n_items):
+        toks = ex["item_tokens"][ex["item_tok_ptr"][i]:ex["item_tok_ptr"][i + 1]]
+        for jpos, t in enumerate(toks):
+            row_tok[int(ex["item_row_base"][i]) + jpos] = int(t)
+    for t in range(T):
+        for row in mr[mp[t]:mp[t + 1]]:
+            assert row_tok.get(int(row), int(row) - info.self_row_base) == t
+    # counters
+    fill_of = dict(zip(b.pool_ids.tolist(), b.pool_fills.tolist()))
+    pairs = sum(int(b.req_row_ptr[r + 1] - b.req_row_ptr[r]) * fill_of[int(s)]
+                for r in range(b.n_req) for s in b.seg_ids[b.req_seg_ptr[r]:b.req_seg_ptr[r + 1]])
+    assert info.prefix_pairs == pairs
+    return info
+
+
+plan_pool = [None]
+
+
+@pytest.mark.parametrize("maker,kw", [
+    (wl.tiny, {}),
+    (wl.prefill, dict(n_req=5, new_tokens=37, lo=300, hi=2000, seg_len=128, n_slots=128, n_shared=3)),
+    (wl.decode, dict(n_req=9, median=900, cap=4000, seg_len=128)),
+    (wl.longctx, dict(n_req=3, entries=40, new_tokens=50, seg_len=64, n_ids=30)),
+    (wl.multiturn, dict(turn=3, n_sessions=6, new_tokens=20, seg_len=64, n_slots=512)),
+])
+def test_plan_covers_every_pair_exactly_once(maker, kw):
+    b = maker(**kw)
+    plan_pool[0] = _pool_for(b)
+    for flags in (B.TL_PLAN_SELF_BLOCK, 0, B.TL_PLAN_SELF_BLOCK | B.TL_PLAN_NO_SHARING):
+        for split in (0, 1, 5):
+            plan = B.tl_plan_create(plan_pool[0], b.q_heads, b.req_row_ptr, b.req_seg_ptr, b.seg_ids, flags, split)
+            _check_plan_covers(b, plan, flags)
+            B.tl_plan_destroy(plan)
+    B.tl_pool_destroy(plan_pool[0])
+
+
+def test_shared_run_becomes_one_item_read_once():
+    b = wl.multiturn(turn=2)
+    pool = _pool_for(b)
+    plan = B.tl_plan_create(pool, b.q_heads, b.req_row_ptr, b.req_seg_ptr, b.seg_ids)
+    info, ex = B.tl_plan_get_info(plan), B.tl_plan_export(plan)
+    n_tok = np.diff(ex["item_tok_ptr"])
+    n_slot = np.diff(ex["item_slot_ptr"])
+    assert info.n_items == 65
+    hot = int(np.argmax(n_tok))
+    assert n_tok[hot] == 64 * 256 and n_slot[hot] == 16          # system prompt: all rows, listed once
+    assert sorted(n_slot.tolist()) == [8] * 64 + [16]
+    B.tl_plan_destroy(plan)
+    B.tl_pool_destroy(pool)
+
+
+def test_plan_errors():
+    b = wl.tiny()
+    pool = _pool_for(b)
+    with pytest.raises(B.TokenLakeError) as e:
+        B.tl_plan_create(pool, b.q_heads, b.req_row_ptr, b.req_seg_ptr, b.seg_ids + np.uint64(1 << 40))
+    assert e.value.status == B.TL_ENOTFOUND
+    with pytest.raises(B.TokenLakeError):
+        B.tl_plan_create(pool, 3, b.req_row_ptr, b.req_seg_ptr, b.seg_ids)          # 3 q heads on 2 kv heads
+    with pytest.raises(B.TokenLakeError):
+        B.tl_plan_create(pool, 12, b.req_row_ptr, b.req_seg_ptr, b.seg_ids)         # group of 6: not a power of two
+    with pytest.raises(B.TokenLakeError):
+        B.tl_plan_create(pool, 8, [0, 5, 3], [0, 1, 2], b.seg_ids)                  # decreasing offsets
+    with pytest.raises(B.TokenLakeError):
+        B.tl_set_option("no-such-knob", 1)
+    B.tl_pool_destroy(pool)

@@ -1,0 +1,312 @@
+"""GPU parity: the HIP path, called through the C-ABI, against the fp64 oracle on the same
+seeded inputs.  Bars: integer/byte work bit-exact; merged O within 2e-2 max-abs and LSE
+within 1e-3 (bf16 inputs, fp32 accumulate).  Because |O| itself is ~1e-2 on long diffuse
+prefixes, every case also bounds the error relative to max|O*| and the suite includes
+peaked / offset variants on which the absolute bar is discriminating."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import tokenlake_oracle as orc
+from paper_2508_17219_amd import binding as B
+from paper_2508_17219_amd import workloads as wl
+from tests import tl_harness as H
+
+pytestmark = pytest.mark.gpu
+
+REL_O = 2e-2
+
+
+def _say(msg):
+    print("[case] " + msg, flush=True)
+
+
+def _check_all_requests(run, rows_per_req=None, seed=0, reqs=None):
+    b = run.batch
+    rng = np.random.default_rng(seed)
+    worst = {"err_o": 0.0, "err_lse": 0.0, "rel_o": 0.0}
+    for r in (range(b.n_req) if reqs is None else reqs):
+        lq = int(b.req_row_ptr[r + 1] - b.req_row_ptr[r])
+        if lq == 0:
+            continue
+        rows = None if rows_per_req is None else H.sample_rows(lq, rows_per_req, rng)
+        res = H.compare_rows(run, r, rows)
+        for k in worst:
+            worst[k] = max(worst[k], res[k])
+        assert res["err_o"] <= H.TOL_O, "request %d: O max-abs error %.3e" % (r, res["err_o"])
+        assert res["err_lse"] <= H.TOL_LSE, "request %d: LSE max-abs error %.3e" % (r, res["err_lse"])
+        assert res["rel_o"] <= REL_O, "request %d: O error %.3e relative to max|O*| %.3e" % (r, res["err_o"], res["ref_o"])
+    _say("%s worst err_o=%.2e err_lse=%.2e rel_o=%.2e" % (b.name, worst["err_o"], worst["err_lse"], worst["rel_o"]))
+    return worst
+
+
+# ---- integer / byte work -------------------------------------------------------------------
+def test_generator_bits_identical_on_device():
+    _say("generator cpu vs gpu")
+    for stream in (0, 3):
+        a = wl.normal_bf16_range(9, stream, 12345, 1 << 16, "cpu")
+        g = wl.normal_bf16_range(9, stream, 12345, 1 << 16, "cuda")
+        assert np.array_equal(wl.bits_u16(a), wl.bits_u16(g))
+    b = wl.tiny()
+    kc, vc = b.segment_kv(b.pool_ids, "cpu")
+    kg, vg = b.segment_kv(b.pool_ids, "cuda")
+    assert np.array_equal(wl.bits_u16(kc), wl.bits_u16(kg)) and np.array_equal(wl.bits_u16(vc), wl.bits_u16(vg))
+
+
+def test_slot_lookup_and_gather_bit_exact():
+    _say("lookup + gather")
+    b = wl.prefill(n_req=3, new_tokens=8, lo=300, hi=900, seg_len=128, n_slots=64, n_shared=2)
+    pk, pv = H.device_pool(b, poison=False)
+    pool = B.tl_pool_create(b.n_slots, b.seg_len, b.kv_heads, b.head_dim, pk, pv)
+    B.tl_pool_adopt(pool, b.pool_ids, b.pool_slots, b.pool_fills)
+    table = orc.SlotTable(b.n_slots, b.seg_len)
+    for sid, s, f in zip(b.pool_ids, b.pool_slots, b.pool_fills):
+        table.put(int(sid), int(f), int(s))
+    probe = np.concatenate([b.seg_ids, np.array([123456789, 2 ** 63 + 5], dtype=np.uint64)])
+    assert np.array_equal(B.tl_pool_lookup(pool, probe), table.lookup(probe))
+    slots = table.lookup(b.seg_ids)
+    assert np.array_equal(B.tl_pool_fills(pool, slots), table.fill(slots))
+    ko = torch.zeros((len(slots),) + tuple(pk.shape[1:]), dtype=torch.bfloat16, device="cuda")
+    vo = torch.zeros_like(ko)
+    B.tl_pool_gather(pool, slots, ko, vo)
+    torch.cuda.synchronize()
+    full = np.full(len(slots), b.seg_len)
+    gk, gv = orc.gather_segments(wl.bits_u16(pk), wl.bits_u16(pv), slots, full)
+    assert np.array_equal(wl.bits_u16(ko).reshape(gk.shape), gk)
+    assert np.array_equal(wl.bits_u16(vo).reshape(gv.shape), gv)
+    B.tl_pool_destroy(pool)
+
+
+def test_one_hot_attention_returns_the_slot_sentinel():
+    """Integer sentinels through the whole path: V[slot, tok, g, 0] = slot and channel 1 = tok;
+    one key per request is aligned with q so strongly that softmax is one-hot in fp32, so the
+    merged output must name that key's (slot, token) exactly."""
+    _say("one-hot sentinel")
+    n_slots, C, hkv, hq, d = 32, 128, 2, 8, 128
+    rng = np.random.default_rng(5)
+    n_req, segs = 4, 5
+    slots = rng.permutation(n_slots)[:n_req * segs].reshape(n_req, segs)
+    pk = torch.zeros(n_slots, C, hkv, d, dtype=torch.bfloat16, device="cuda")
+    pv = torch.zeros_like(pk)
+    pv[:, :, :, 0] = torch.arange(n_slots, device="cuda", dtype=torch.float32)[:, None, None].to(torch.bfloat16)
+    pv[:, :, :, 1] = torch.arange(C, device="cuda", dtype=torch.float32)[None, :, None].to(torch.bfloat16)
+    q = torch.zeros(n_req, hq, d, dtype=torch.bfloat16, device="cuda")
+    q[:, :, 2] = 16.0
+    hot = []
+    for r in range(n_req):
+        s = int(slots[r, rng.integers(segs)])
+        t = int(rng.integers(C))
+        pk[s, t, :, 2] = 64.0                       # score 16*64/sqrt(128) ~ 90 above the rest
+        hot.append((s, t))
+    pool = B.tl_pool_create(n_slots, C, hkv, d, pk, pv)
+    ids = np.arange(n_req * segs, dtype=np.uint64) + 1000
+    B.tl_pool_adopt(pool, ids, slots.reshape(-1), np.full(n_req * segs, C))
+    plan = B.tl_plan_create(pool, hq, np.arange(n_req + 1), np.arange(n_req + 1) * segs, ids, 0, 2)
+    info = B.tl_plan_get_info(plan)
+    outp = torch.zeros(info.n_partial_rows, hq, d, device="cuda")
+    lsep = torch.zeros(info.n_partial_rows, hq, device="cuda")
+    out = torch.zeros(n_req, hq, d, device="cuda")
+    B.tl_segment_attn(pool, plan, q, 1 / math.sqrt(d), outp, lsep)
+    B.tl_merge(plan, outp, lsep, out, False, None)
+    torch.cuda.synchronize()
+    for r, (s, t) in enumerate(hot):
+        assert torch.all(out[r, :, 0] == float(s)) and torch.all(out[r, :, 1] == float(t)), (r, s, t, out[r, :, :2])
+    B.tl_plan_destroy(plan)
+    B.tl_pool_destroy(pool)
+
+
+# ---- small cases, every row ------------------------------------------------------------------
+def test_tiny_config_full_and_partials():
+    _say("tiny full")
+    b = wl.tiny()
+    run = H.run_gpu(b)
+    _check_all_requests(run)
+    # per-item partials and the self block against the oracle's partials over the same keys
+    ex = B.tl_plan_export(run.plan)
+    qb, pk, pv, slots, fills, kn, vn = H.host_request_inputs(b, 0)
+    slot_pos = {int(s): i for i, s in enumerate(B.tl_pool_lookup(run.pool, b.seg_ids))}
+    groups = []
+    for i in range(run.info.n_items):
+        its = ex["item_slots"][ex["item_slot_ptr"][i]:ex["item_slot_ptr"][i + 1]]
+        groups.append([slot_pos[int(s)] for s in its])
+    outs, lses = orc.request_partials_by_segment(qb, pk, pv, slots, fills, kn, vn, b.scale, groups)
+    for i in range(run.info.n_items):
+        r0 = int(ex["item_row_base"][i])
+        got_o = run.out_partial[r0:r0 + 32].double().cpu().numpy()
+        got_l = run.lse_partial[r0:r0 + 32].double().cpu().numpy()
+        assert np.abs(got_o - outs[i]).max() <= H.TOL_O and np.abs(got_l - lses[i]).max() <= H.TOL_LSE
+    sb = run.info.self_row_base
+    got_o = run.out_partial[sb:sb + 32].double().cpu().numpy()
+    got_l = run.lse_partial[sb:sb + 32].double().cpu().numpy()
+    assert np.abs(got_o - outs[-1]).max() <= H.TOL_O and np.abs(got_l - lses[-1]).max() <= H.TOL_LSE
+    run.close()
+
+
+def test_tiny_config_scalar_lds_read_variant():
+    _say("tiny vread=1")
+    B.tl_set_option("vread", 1)
+    try:
+        run = H.run_gpu(wl.tiny())
+        _check_all_requests(run)
+        run.close()
+    finally:
+        B.tl_set_option("vread", 0)
+
+
+@pytest.mark.parametrize("kw", [
+    dict(n_req=3, new_tokens=100, lo=300, hi=900, seg_len=128, n_slots=64, n_shared=2),     # ragged tiles and tails
+    dict(n_req=2, new_tokens=70, lo=64, hi=200, seg_len=64, n_slots=16, n_shared=1, hq=8, hkv=8),   # MHA, G=1
+    dict(n_req=2, new_tokens=40, lo=500, hi=700, seg_len=256, n_slots=16, n_shared=0, hq=32, hkv=1),  # G=32
+    dict(n_req=5, new_tokens=3, lo=100, hi=400, seg_len=128, n_slots=32, n_shared=1, hq=16, hkv=2),   # few rows + sharing
+])
+def test_small_prefill_shapes_every_row(kw):
+    _say("small prefill %r" % (kw,))
+    run = H.run_gpu(wl.prefill(seed=11, **kw))
+    _check_all_requests(run)
+    run.close()
+
+
+@pytest.mark.parametrize("kw", [
+    dict(n_req=6, median=700, sigma=1.0, cap=3000, seg_len=128),
+    dict(n_req=4, median=300, sigma=0.5, cap=1000, seg_len=64, hq=8, hkv=2),
+    dict(n_req=3, median=900, sigma=0.3, cap=2000, seg_len=256, hq=16, hkv=16),
+])
+def test_small_decode_shapes_every_row(kw):
+    _say("small decode %r" % (kw,))
+    for split in (0, 1, 3):
+        run = H.run_gpu(wl.decode(seed=12, **kw), split_segments=split)
+        assert run.info.n_units > 0 and run.info.n_tiles == 0
+        _check_all_requests(run)
+        run.close()
+
+
+def test_peaked_and_offset_variants_are_discriminating():
+    _say("peaked / offset variants")
+    for maker, kw in [(wl.prefill, dict(n_req=3, new_tokens=100, lo=300, hi=900, seg_len=128, n_slots=64, n_shared=2)),
+                      (wl.decode, dict(n_req=6, median=700, cap=3000, seg_len=128))]:
+        b = maker(seed=21, k_gain=4.0, v_offset_mod=7, **kw)
+        run = H.run_gpu(b)
+        w = _check_all_requests(run)
+        # on these inputs |O| is O(1): an all-zero or segment-dropping result cannot pass 2e-2
+        ref = max(H.compare_rows(run, r)["ref_o"] for r in range(b.n_req))
+        assert ref > 0.5
+        run.close()
+
+
+def test_edge_cases_empty_prefix_zero_tokens_and_no_keys():
+    _say("edge cases")
+    base = wl.prefill(seed=13, n_req=4, new_tokens=20, lo=200, hi=500, seg_len=128, n_slots=32, n_shared=1)
+    # request 1 loses its prefix; request 2 has no new tokens
+    seg_ptr = base.req_seg_ptr.copy()
+    lens = np.diff(seg_ptr)
+    keep = [base.seg_ids[seg_ptr[r]:seg_ptr[r + 1]] for r in range(4)]
+    keep[1] = keep[1][:0]
+    base.seg_ids = np.concatenate(keep)
+    base.req_seg_ptr = np.concatenate([[0], np.cumsum([len(k) for k in keep])]).astype(np.int32)
+    base.req_row_ptr = np.array([0, 20, 40, 40, 60], np.int32)
+    run = H.run_gpu(base)
+    _check_all_requests(run)
+    run.close()
+    # without the self block a request with no prefix has no keys at all: O = 0, LSE = -inf
+    base.self_block = False
+    run = H.run_gpu(base)
+    t0, t1 = 20, 40
+    assert torch.all(run.out[t0:t1] == 0) and torch.all(torch.isneginf(run.lse[t0:t1]))
+    _check_all_requests(run, reqs=[0, 3])
+    run.close()
+
+
+def test_put_path_dedup_and_ragged_fill():
+    _say("put path")
+    b = wl.prefill(seed=14, n_req=2, new_tokens=33, lo=150, hi=400, seg_len=128, n_slots=16, n_shared=1)
+    pool = B.tl_pool_create(b.n_slots, b.seg_len, b.kv_heads, b.head_dim, None, None)   # library-owned memory
+    k, v = b.segment_kv(b.pool_ids, "cuda")
+    for i, (sid, s, f) in enumerate(zip(b.pool_ids, b.pool_slots, b.pool_fills)):
+        got = B.tl_pool_put(pool, int(sid), k[i, :f].contiguous(), v[i, :f].contiguous(), int(f), int(s))
+        assert got == int(s)
+    # putting a resident id again stores nothing and returns the same slot
+    assert B.tl_pool_put(pool, int(b.pool_ids[0]), k[1], v[1], b.seg_len, -1) == int(b.pool_slots[0])
+    assert B.tl_pool_used(pool) == len(b.pool_ids)
+    plan = B.tl_plan_create(pool, b.q_heads, b.req_row_ptr, b.req_seg_ptr, b.seg_ids)
+    info = B.tl_plan_get_info(plan)
+    q, kn, vn = b.q("cuda"), b.k_new("cuda"), b.v_new("cuda")
+    outp = torch.empty(info.n_partial_rows, b.q_heads, 128, device="cuda")
+    lsep = torch.empty(info.n_partial_rows, b.q_heads, device="cuda")
+    out = torch.empty(b.n_tokens, b.q_heads, 128, device="cuda")
+    lse = torch.empty(b.n_tokens, b.q_heads, device="cuda")
+    B.tl_segment_attn(pool, plan, q, b.scale, outp, lsep)
+    B.tl_causal_block(plan, q, kn, vn, b.scale, outp, lsep)
+    B.tl_merge(plan, outp, lsep, out, False, lse)
+    torch.cuda.synchronize()
+    run = H.GpuRun(b, pool, plan, info, q, kn, vn, None, None, outp, lsep, out, lse)
+    _check_all_requests(run)
+    run.close()
+
+
+def test_bf16_output_variant():
+    _say("bf16 output")
+    b = wl.prefill(seed=15, n_req=2, new_tokens=50, lo=300, hi=600, seg_len=128, n_slots=16, n_shared=1, k_gain=4.0)
+    r32 = H.run_gpu(b)
+    r16 = H.run_gpu(b, out_bf16=True)
+    assert torch.equal(r16.out, r32.out.to(torch.bfloat16))
+    assert torch.equal(r16.lse, r32.lse)
+    r32.close(); r16.close()
+
+
+def test_sharing_and_no_sharing_plans_agree():
+    _say("sharing vs no sharing")
+    b = wl.prefill(seed=16, n_req=4, new_tokens=64, lo=600, hi=900, seg_len=128, n_slots=64, n_shared=3)
+    a = H.run_gpu(b)
+    n = H.run_gpu(b, flags=B.TL_PLAN_SELF_BLOCK | B.TL_PLAN_NO_SHARING)
+    assert a.info.n_items > n.info.n_items - 1 and n.info.n_items == 4
+    assert (a.out - n.out).abs().max().item() <= 1e-3 and (a.lse - n.lse).abs().max().item() <= 1e-4
+    a.close(); n.close()
+
+
+def test_deterministic_bits_run_to_run():
+    _say("determinism")
+    b = wl.prefill(seed=17, n_req=3, new_tokens=90, lo=300, hi=900, seg_len=128, n_slots=64, n_shared=2)
+    r1, r2 = H.run_gpu(b), H.run_gpu(b)
+    assert torch.equal(r1.out, r2.out) and torch.equal(r1.lse, r2.lse)
+    r1.close(); r2.close()
+
+
+# ---- the named configurations at full size, sampled rows ------------------------------------------
+def test_full_prefill_config_sampled():
+    _say("full prefill (cfg 2)")
+    b = wl.prefill()
+    run = H.run_gpu(b)
+    L = b.prefix_tokens()
+    reqs = sorted({int(np.argmin(L)), int(np.argmax(L)), 0})
+    _check_all_requests(run, rows_per_req=6, seed=1, reqs=reqs)
+    run.close()
+
+
+def test_full_decode_config_sampled():
+    _say("full decode (cfg 3)")
+    b = wl.decode()
+    run = H.run_gpu(b, poison=False)
+    L = b.prefix_tokens()
+    order = np.argsort(L)
+    reqs = sorted({int(order[0]), int(order[-1]), int(order[len(order) // 2]), 7, 100})
+    _check_all_requests(run, reqs=reqs)
+    run.close()
+
+
+def test_full_longctx_config_sampled():
+    _say("full long context (cfg 4)")
+    b = wl.longctx()
+    run = H.run_gpu(b)
+    _check_all_requests(run, rows_per_req=4, seed=3, reqs=[2])
+    run.close()
+
+
+@pytest.mark.parametrize("turn", [0, 7])
+def test_full_multiturn_config_sampled(turn):
+    _say("full multi-turn (cfg 5) turn %d" % turn)
+    b = wl.multiturn(turn=turn)
+    run = H.run_gpu(b)
+    _check_all_requests(run, rows_per_req=5, seed=4, reqs=[0, 37, 63])
+    run.close()
