@@ -114,8 +114,7 @@ def cpu_baseline(batch, budget_s=15.0):
     r = int(np.argsort(L)[len(L) // 2])
     qb, pk, pv, slots, fills, kn, vn = H.host_request_inputs(batch, r)
     lq = qb.shape[0]
-    n_done, t_used = 0, 0.0
-    n = min(2, lq)
+    n_done, t_used, n = 0, 0.0, min(2, lq)
     while n_done < lq and t_used < budget_s:
         rows = np.arange(n_done, min(lq, n_done + n))
         t0 = time.perf_counter()
@@ -126,9 +125,9 @@ def cpu_baseline(batch, budget_s=15.0):
         dt = time.perf_counter() - t0
         t_used += dt
         n_done += len(rows)
-        n = max(1, min(lq - n_done, int(n * max(1.0, min(4.0, (budget_s - t_used) / max(dt, 1e-3) / 2)))))
-        if n_done >= 64:
-            break
+        # next chunk: aim at a quarter of what is left of the budget
+        per_row = dt / len(rows)
+        n = int(max(1, min(lq - n_done, (budget_s - t_used) / 4 / max(per_row, 1e-6))))
     threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     return {"value": n_done / t_used, "unit": "tok/s", "cores": int(threads), "kind": "oracle",
             "sample": "%d new tokens (all %d heads) of request %d (prefix %d tokens, median of the batch), "

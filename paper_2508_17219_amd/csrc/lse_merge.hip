@@ -13,7 +13,8 @@ tl_status launch_splitk_units(const AttnArgs& a, int n_work, hipStream_t st);
 
 namespace {
 
-// One workgroup per token; a thread owns 4 consecutive channels of one head.
+// blockIdx.x = token, blockIdx.y = chunk of 256 (head, channel-quad) positions; a thread owns
+// 4 consecutive channels of one head.
 //   M = max_j LSE_j;  w_j = exp(LSE_j - M);  O = sum w_j O_j / sum w_j;  LSE = M + ln sum w_j
 template <bool OUT_BF16>
 __global__ __launch_bounds__(256) void lse_merge_kernel(const float* __restrict__ part, const float* __restrict__ lse,
@@ -22,7 +23,8 @@ __global__ __launch_bounds__(256) void lse_merge_kernel(const float* __restrict_
                                                         float* __restrict__ lse_out, int q_heads) {
   const int t = blockIdx.x;
   const int b = mptr[t], e = mptr[t + 1];
-  for (int idx = threadIdx.x; idx < q_heads * 32; idx += blockDim.x) {
+  const int idx = blockIdx.y * blockDim.x + threadIdx.x;
+  if (idx < q_heads * 32) {
     const int hd = idx >> 5, c4 = idx & 31;
     float M = -INFINITY;
     for (int jj = b; jj < e; ++jj) M = fmaxf(M, lse[(size_t)mrows[jj] * q_heads + hd]);
@@ -127,7 +129,7 @@ tl_status tl_merge(tl_plan* plan, const float* out_partial, const float* lse, vo
   if (rc != TL_OK) return rc;
   if (plan->n_tokens == 0) return TL_OK;
   hipStream_t st = (hipStream_t)stream;
-  const dim3 grid((unsigned)plan->n_tokens), block(256);
+  const dim3 grid((unsigned)plan->n_tokens, (unsigned)((plan->q_heads * 32 + 255) / 256)), block(256);
   if (out_is_bf16)
     hipLaunchKernelGGL(lse_merge_kernel<true>, grid, block, 0, st, out_partial, lse, plan->d_merge_ptr, plan->d_merge_rows,
                        out_dev, lse_out, plan->q_heads);
