@@ -66,7 +66,7 @@ def load_library(path: Optional[str] = None):
     """Load libtokenlake.so (built by paper_2508_17219_amd.build).  Raises if it is absent."""
     global _lib
     if _lib is None:
-        p = path or LIB_PATH
+        p = path or os.environ.get("TOKENLAKE_LIB") or LIB_PATH
         if not os.path.exists(p):
             raise FileNotFoundError(
                 "%s not found: build it with `python -m paper_2508_17219_amd.build` "

@@ -15,9 +15,13 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-// LDS rows are padded from 128 to 136 bf16 (272 B) so that the 16 B reads of one MFMA
-// operand column fall in different banks.
+// LDS rows are padded from 128 bf16.  K rows: 136 (272 B), so that the 16-byte reads of 16
+// consecutive rows fall in different banks.  V rows of the row-tile kernel: 160 (320 B =
+// 64 mod 256), so that the 4 rows x 64 B which 32 lanes fetch in one transposing read cover
+// all banks once; V rows of the split-K kernel: 144 (288 B = 32 mod 256) for its 8 rows x 32 B.
 constexpr int kLdsStride = 136;
+constexpr int kVStrideTile = 160;
+constexpr int kVStrideUnit = 144;
 
 struct AttnArgs {
   const uint16_t* q;      // [n_tokens, q_heads, 128] bf16
@@ -27,6 +31,8 @@ struct AttnArgs {
   const Work* work;
   const int32_t* tok;     // token index lists
   const int32_t* slots;   // slot lists (pool work)
+  const int32_t* tile_base;  // first kv row of each full 64-token tile (pool row tiles)
+  const int32_t* part_tile;  // (first kv row, valid tokens) of each cut-short tile
   float* out;             // [rows, q_heads, 128]
   float* lse;             // [rows, q_heads]
   int32_t q_heads, kv_heads, log2g, seg_len, n_work;

@@ -16,7 +16,7 @@ namespace {
 constexpr int kThreads = 512;
 constexpr int kWaves = 8;
 constexpr int kTok = 32;                                   // kv tokens per wave tile
-constexpr int kWaveElems = 2 * kTok * kLdsStride;          // K tile + V tile, bf16 elements
+constexpr int kWaveElems = kTok * (kLdsStride + kVStrideUnit);   // K tile + V tile, bf16 elements
 constexpr size_t kLdsBytes = (size_t)kWaves * kWaveElems * sizeof(uint16_t);
 
 template <int VREAD>
@@ -76,7 +76,7 @@ __global__ __launch_bounds__(kThreads) void splitk_unit_attn_kernel(const AttnAr
       const int cidx = lane + 64 * i;
       const int tr = cidx >> 4, part = cidx & 15;
       *(uint4*)&kt[tr * kLdsStride + part * 8] = kst[i];
-      *(uint4*)&vt[tr * kLdsStride + part * 8] = vst[i];
+      *(uint4*)&vt[tr * kVStrideUnit + part * 8] = vst[i];
     }
   };
 
@@ -150,12 +150,12 @@ __global__ __launch_bounds__(kThreads) void splitk_unit_attn_kernel(const AttnAr
       for (int d = 0; d < 8; ++d) {
         bf16x8 av;
         if (VREAD == 0) {
-          const uint16_t* p = vt + (4 * c4 + (l16 >> 2)) * kLdsStride + 16 * d + 4 * (l16 & 3);
-          av = join_tr(lds_read_tr(p), lds_read_tr(p + 16 * kLdsStride));
+          const uint16_t* p = vt + (4 * c4 + (l16 >> 2)) * kVStrideUnit + 16 * d + 4 * (l16 & 3);
+          av = join_tr(lds_read_tr(p), lds_read_tr(p + 16 * kVStrideUnit));
         } else {
           s16x8 t;
 #pragma unroll
-          for (int e = 0; e < 8; ++e) t[e] = (short)vt[(16 * (e >> 2) + 4 * c4 + (e & 3)) * kLdsStride + 16 * d + l16];
+          for (int e = 0; e < 8; ++e) t[e] = (short)vt[(16 * (e >> 2) + 4 * c4 + (e & 3)) * kVStrideUnit + 16 * d + l16];
           av = __builtin_bit_cast(bf16x8, t);
         }
         f32x4 acc = o[d];

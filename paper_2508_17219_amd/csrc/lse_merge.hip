@@ -63,6 +63,8 @@ void fill_args(AttnArgs& a, const tl_plan* plan, const void* q, float scale, flo
   a.q = (const uint16_t*)q;
   a.tok = plan->d_tok;
   a.slots = plan->d_slots;
+  a.tile_base = plan->d_tile_base;
+  a.part_tile = plan->d_part_tile;
   a.out = out;
   a.lse = lse;
   a.q_heads = plan->q_heads;

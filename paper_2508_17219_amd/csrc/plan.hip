@@ -155,12 +155,29 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
         p->item_tok_ptr.push_back((int32_t)p->item_tokens.size());
         p->item_slot_ptr.push_back((int32_t)p->item_slots.size());
         if (few_rows) {
-          p->units.push_back(Work{tok_base, n_tok, row_cursor, slot_base, c1 - c0});
+          p->units.push_back(Work{tok_base, n_tok, row_cursor, slot_base, c1 - c0, 0, 0, 0, 0});
         } else {
+          // the item's kv tokens as tiles of kKvTile rows (shared by all its row tiles)
+          const int32_t full_off = (int32_t)p->tile_base.size();
+          const int32_t part_off = (int32_t)p->part_tile.size() / 2;
+          for (int32_t pos = slot_base; pos < slot_base + (c1 - c0); ++pos) {
+            const int32_t s = p->item_slots[pos], f = pool->fill[s];
+            for (int32_t off = 0; off < f; off += kKvTile) {
+              if (off + kKvTile <= f) {
+                p->tile_base.push_back(s * pool->seg_len + off);
+              } else {
+                p->part_tile.push_back(s * pool->seg_len + off);
+                p->part_tile.push_back(f - off);
+              }
+            }
+          }
+          const int32_t n_full = (int32_t)p->tile_base.size() - full_off;
+          const int32_t n_part = (int32_t)p->part_tile.size() / 2 - part_off;
           // row tiles never straddle two requests' token ranges unless ranges are short:
           // tokens are simply taken tok_tile at a time in item order (Q rows are gathered).
           for (int32_t t0 = 0; t0 < n_tok; t0 += tok_tile)
-            p->tiles.push_back(Work{tok_base + t0, std::min(tok_tile, n_tok - t0), row_cursor + t0, slot_base, c1 - c0});
+            p->tiles.push_back(Work{tok_base + t0, std::min(tok_tile, n_tok - t0), row_cursor + t0, slot_base, c1 - c0,
+                                    full_off, n_full, part_off, n_part});
         }
         row_cursor += n_tok;
       }
@@ -181,14 +198,16 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
         self_pairs += lq * (lq + 1) / 2;
         for (int32_t t0 = a; t0 < b; t0 += tok_tile) {
           const int32_t n = std::min(tok_tile, b - t0);
-          p->ctiles.push_back(Work{ident_base + t0, n, self_base + t0, a, t0 + n - a});
+          p->ctiles.push_back(Work{ident_base + t0, n, self_base + t0, a, t0 + n - a, 0, 0, 0, 0});
         }
       }
       row_cursor += T;
     }
 
     // longest first, so that the tail of the launch is made of short work
-    auto by_len = [&](const Work& x, const Work& y) { return x.kv_len > y.kv_len; };
+    auto by_len = [&](const Work& x, const Work& y) {
+      return (x.n_full + x.n_part ? x.n_full + x.n_part : x.kv_len) > (y.n_full + y.n_part ? y.n_full + y.n_part : y.kv_len);
+    };
     std::stable_sort(p->tiles.begin(), p->tiles.end(), by_len);
     std::stable_sort(p->units.begin(), p->units.end(), by_len);
     std::stable_sort(p->ctiles.begin(), p->ctiles.end(), by_len);
@@ -293,7 +312,9 @@ tl_status plan_device_ready(tl_plan* p) {
   const size_t b_slots = al(sizeof(int32_t) * p->item_slots.size());
   const size_t b_mptr = al(sizeof(int32_t) * p->merge_ptr.size());
   const size_t b_mrows = al(sizeof(int32_t) * p->merge_rows.size());
-  const size_t total = b_tiles + b_units + b_ctiles + b_tok + b_slots + b_mptr + b_mrows + 256;
+  const size_t b_tbase = al(sizeof(int32_t) * p->tile_base.size());
+  const size_t b_part = al(sizeof(int32_t) * p->part_tile.size());
+  const size_t total = b_tiles + b_units + b_ctiles + b_tok + b_slots + b_mptr + b_mrows + b_tbase + b_part + 256;
   std::vector<char> host(total, 0);
   size_t off = 0;
   auto put = [&](const void* src, size_t bytes, size_t reserved) {
@@ -309,6 +330,8 @@ tl_status plan_device_ready(tl_plan* p) {
   const size_t o_slots = put(p->item_slots.data(), sizeof(int32_t) * p->item_slots.size(), b_slots);
   const size_t o_mptr = put(p->merge_ptr.data(), sizeof(int32_t) * p->merge_ptr.size(), b_mptr);
   const size_t o_mrows = put(p->merge_rows.data(), sizeof(int32_t) * p->merge_rows.size(), b_mrows);
+  const size_t o_tbase = put(p->tile_base.data(), sizeof(int32_t) * p->tile_base.size(), b_tbase);
+  const size_t o_part = put(p->part_tile.data(), sizeof(int32_t) * p->part_tile.size(), b_part);
   void* blob = nullptr;
   TL_HIP(hipMalloc(&blob, total));
   hipError_t e = hipMemcpy(blob, host.data(), total, hipMemcpyHostToDevice);
@@ -325,6 +348,8 @@ tl_status plan_device_ready(tl_plan* p) {
   p->d_slots = (int32_t*)(b + o_slots);
   p->d_merge_ptr = (int32_t*)(b + o_mptr);
   p->d_merge_rows = (int32_t*)(b + o_mrows);
+  p->d_tile_base = (int32_t*)(b + o_tbase);
+  p->d_part_tile = (int32_t*)(b + o_part);
   p->on_device = true;
   return TL_OK;
 }

@@ -35,11 +35,14 @@ constexpr int kUnitRows = 16;    // max rows per kv head of a split-K unit
 
 // One unit of kernel work.  Its query tokens are tok[tok_off .. tok_off+n_tok) (batch token
 // indices), its partial rows out_row .. out_row+n_tok-1.
-//  pool work:   kv_off/kv_len index the plan's slot-list array.
+//  pool work:   kv_off/kv_len index the plan's slot-list array; for row tiles the item's kv
+//               tokens are also listed as tiles of 64: full_off/n_full index tile_base[]
+//               (first kv row of each completely filled tile), part_off/n_part index
+//               part_tile[] (first kv row, valid tokens) for the tiles cut short by a fill.
 //  causal work: kv_off = first new token of the request, kv_len = new tokens visible to the
 //               last row of the tile; tokens of the tile are consecutive.
 struct Work {
-  int32_t tok_off, n_tok, out_row, kv_off, kv_len;
+  int32_t tok_off, n_tok, out_row, kv_off, kv_len, full_off, n_full, part_off, n_part;
 };
 
 int get_option_vread();
@@ -72,11 +75,13 @@ struct tl_plan {
   std::vector<int32_t> merge_ptr, merge_rows;
   std::vector<tl::Work> tiles, units, ctiles;
   std::vector<int32_t> tok;      // token index array referenced by Work::tok_off
+  std::vector<int32_t> tile_base;  // Work::full_off
+  std::vector<int32_t> part_tile;  // Work::part_off, pairs (first kv row, valid tokens)
   // device copies (made on first use)
   bool on_device;
   void* blob;
   tl::Work *d_tiles, *d_units, *d_ctiles;
-  int32_t *d_tok, *d_slots, *d_merge_ptr, *d_merge_rows;
+  int32_t *d_tok, *d_slots, *d_merge_ptr, *d_merge_rows, *d_tile_base, *d_part_tile;
 };
 
 namespace tl {
