@@ -13,14 +13,21 @@
 //   O^T[d, row] += V^T[d, kv] . P^T[kv, row]  A = V block read transposed from LDS, B = P
 // Scores never leave registers between the two products.
 //
-// Completely filled tiles run through a software pipeline three blocks deep: while the MFMA
-// unit computes the scores of block j+1 and accumulates block j-1 into O, the vector ALU turns
-// the scores of block j into probabilities.  The running maximum is only a reference point
-// for the exponent (any reference gives the same normalised result), so it is raised -- and O
-// rescaled -- only when a block maximum exceeds it by more than 2^8; that test is the single
-// branch of a pipeline step.  Tiles cut short by a slot's fill, and the tiles on the causal
-// diagonal, are masked and go through a plain (unpipelined) path afterwards.
+// Completely filled tiles run in a ping-pong between the two wavefronts that share a SIMD
+// (waves w and w+4): waves 0-3 go scores -> softmax -> accumulate within an iteration, waves 4-7
+// accumulate the previous tile first and then do scores -> softmax, so that one wave's MFMA
+// phase lines up with the other's vector-ALU phase.  V is triple buffered for that reason.
+// The running maximum is only a reference point for the exponent (any reference gives the
+// same normalised result), so it is raised -- and O rescaled -- only when a tile maximum
+// exceeds it by more than 2^8.  Tiles cut short by a slot's fill, and the tiles on the causal
+// diagonal, are masked and go through a plain path afterwards.
 #include "attn_common.h"
+
+#ifdef TL_NO_SETPRIO
+#define TL_SETPRIO(x)
+#else
+#define TL_SETPRIO(x) __builtin_amdgcn_s_setprio(x)
+#endif
 
 namespace tl {
 
@@ -31,7 +38,7 @@ constexpr int kKS = kLdsStride;      // K row stride in LDS (bf16)
 constexpr int kVS = kVStrideTile;    // V row stride in LDS (bf16)
 constexpr int kKTile = kKvTile * kKS;
 constexpr int kVTile = kKvTile * kVS;
-constexpr size_t kLdsBytes = (size_t)2 * (kKTile + kVTile) * sizeof(uint16_t);
+constexpr size_t kLdsBytes = (size_t)(2 * kKTile + 3 * kVTile) * sizeof(uint16_t);
 constexpr float kRescaleLog2 = 8.0f;  // raise the reference maximum when exceeded by 2^8
 
 // Lanes l and l^32 exchange x: returns {own, partner} in some order.  The swap instruction
@@ -69,6 +76,26 @@ __device__ __forceinline__ float max16(const f32x16& s) {
   return fmaxf(fmaxf(fmaxf(a, b), fmaxf(c, d)), fmaxf(e, s[15]));
 }
 
+// Instruction order for one tile's MFMA phase: LDS reads run two groups of four MFMAs ahead
+// of their use, so that the matrix unit is not left waiting on LDS latency.
+// (mask 0x008 = MFMA, 0x100 = LDS read)
+__device__ __forceinline__ void sched_qk_tile() {
+  __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+  __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+  __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+  __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+  __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+  __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+}
+__device__ __forceinline__ void sched_pv_tile() {
+  __builtin_amdgcn_sched_group_barrier(0x100, 16, 0);
+  __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+  __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+  __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+  __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+  __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+}
+
 struct RowState {
   f32x16 o[4];     // O^T accumulators: o[d][r] = channel 32 d + 8 (r/4) + 4 h + r%4 of row l32
   float m_ref;     // reference maximum of the exponent (raw score units), -inf before any key
@@ -79,7 +106,7 @@ template <bool CAUSAL, int VREAD>
 __global__ __launch_bounds__(kThreads) void row_tile_attn_kernel(const AttnArgs a) {
   extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
   uint16_t* lds_k = lds;                 // [2][64][kKS]
-  uint16_t* lds_v = lds + 2 * kKTile;    // [2][64][kVS]
+  uint16_t* lds_v = lds + 2 * kKTile;    // [3][64][kVS]
 
   const int g = blockIdx.x % a.kv_heads;
   const Work wk = a.work[blockIdx.x / a.kv_heads];
@@ -129,22 +156,12 @@ __global__ __launch_bounds__(kThreads) void row_tile_attn_kernel(const AttnArgs 
   // ---- global <-> LDS staging: 2 chunks of 16 B per thread per tile, for K and for V ----
   const size_t kv_row = (size_t)a.kv_heads * kHeadDim;
   const int c_tr = tid >> 4, c_part = tid & 15;          // chunk 0: token c_tr, chunk 1: token c_tr + 32
-  auto gload_tile = [&](const uint16_t* src, int base, uint4 (&dst)[2]) {
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-      dst[i] = ((const uint4*)src)[((size_t)(base + c_tr + 32 * i) * kv_row + (size_t)g * kHeadDim) / 8 + c_part];
+  // (plain scalars, not arrays: the staged chunks must live in registers across iterations)
+  auto chunk_ptr = [&](const uint16_t* src, int base, int i) -> const uint4* {
+    return (const uint4*)src + ((size_t)(base + c_tr + 32 * i) * kv_row + (size_t)g * kHeadDim) / 8 + c_part;
   };
-  auto gload_tile_masked = [&](const uint16_t* src, int base, int valid, uint4 (&dst)[2]) {
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      dst[i] = make_uint4(0, 0, 0, 0);
-      if (c_tr + 32 * i < valid)
-        dst[i] = ((const uint4*)src)[((size_t)(base + c_tr + 32 * i) * kv_row + (size_t)g * kHeadDim) / 8 + c_part];
-    }
-  };
-  auto lwrite_tile = [&](uint16_t* tile, int stride, const uint4 (&srcv)[2]) {
-#pragma unroll
-    for (int i = 0; i < 2; ++i) *(uint4*)&tile[(c_tr + 32 * i) * stride + c_part * 8] = srcv[i];
+  auto lds_chunk = [&](uint16_t* tile, int stride, int i) -> uint4* {
+    return (uint4*)&tile[(c_tr + 32 * i) * stride + c_part * 8];
   };
 
   // ---- the three stages of a block ----
@@ -157,6 +174,20 @@ __global__ __launch_bounds__(kThreads) void row_tile_attn_kernel(const AttnArgs 
     for (int s8 = 0; s8 < 8; ++s8) {
       const bf16x8 ak = *(const bf16x8*)&p[16 * s8];
       s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak, qreg[s8], s, 0, 0, 0);
+    }
+  };
+  // scores of both blocks of a tile, the two accumulation chains interleaved so that
+  // consecutive MFMAs are independent
+  auto qk_tile = [&](const uint16_t* kt, f32x16& sa, f32x16& sb) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { sa[r] = 0.f; sb[r] = 0.f; }
+    const uint16_t* p = kt + l32 * kKS + 8 * h;
+#pragma unroll
+    for (int s8 = 0; s8 < 8; ++s8) {
+      const bf16x8 ak0 = *(const bf16x8*)&p[16 * s8];
+      const bf16x8 ak1 = *(const bf16x8*)&p[32 * kKS + 16 * s8];
+      sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak0, qreg[s8], sa, 0, 0, 0);
+      sb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak1, qreg[s8], sb, 0, 0, 0);
     }
   };
   // probabilities of a block against the current reference: p = 2^(c (s - m_ref)); B operands
@@ -195,10 +226,9 @@ __global__ __launch_bounds__(kThreads) void row_tile_attn_kernel(const AttnArgs 
       }
     }
   };
-  // raise the reference maximum to cover block scores `s` if they exceed it by too much;
-  // `pend` holds probabilities computed against the old reference and not yet accumulated
-  auto maybe_rescale = [&](const f32x16& s, bf16x8 (*pend)[2]) {
-    const float mx = xor32_max(max16(s));
+  // raise the reference maximum if the scores of a tile (two blocks) exceed it by too much
+  auto maybe_rescale = [&](const f32x16& sa, const f32x16& sb) {
+    const float mx = xor32_max(fmaxf(max16(sa), max16(sb)));
     const bool need = (mx - st.m_ref) * c > kRescaleLog2 || st.m_ref == -INFINITY;
     if (__builtin_amdgcn_ballot_w64(need) != 0) {
       const float m_new = fmaxf(st.m_ref, mx);
@@ -209,76 +239,83 @@ __global__ __launch_bounds__(kThreads) void row_tile_attn_kernel(const AttnArgs 
       for (int d = 0; d < 4; ++d)
 #pragma unroll
         for (int r = 0; r < 16; ++r) st.o[d][r] *= alpha;
-      if (pend) {
-#pragma unroll
-        for (int sp = 0; sp < 2; ++sp) {
-          f32x8 f = __builtin_convertvector((*pend)[sp], f32x8);
-#pragma unroll
-          for (int e = 0; e < 8; ++e) f[e] *= alpha;
-          (*pend)[sp] = __builtin_convertvector(f, bf16x8);
-        }
-      }
     }
   };
 
-  // ======================= pass 1: full tiles, pipelined =======================
+  // ======================= pass 1: full tiles, ping-pong =======================
   if (n_full > 0) {
-    uint4 kst[2], vst[2];
-    // prologue: K(0), V(0), K(1) into LDS; K(2), V(1) into the staging registers
-    gload_tile(a.k, full_base(0), kst);
-    gload_tile(a.v, full_base(0), vst);
-    lwrite_tile(lds_k, kKS, kst);
-    lwrite_tile(lds_v, kVS, vst);
-    if (n_full > 1) {
-      gload_tile(a.k, full_base(1), kst);
-      gload_tile(a.v, full_base(1), vst);
-      lwrite_tile(lds_k + kKTile, kKS, kst);
+#ifdef TL_PINGPONG
+    const bool group_b = wave >= 4;
+#else
+    const bool group_b = false;
+#endif
+    uint4 k0, k1, v0, v1;
+    {
+      const int b0 = full_base(0);
+      k0 = *chunk_ptr(a.k, b0, 0); k1 = *chunk_ptr(a.k, b0, 1);
+      v0 = *chunk_ptr(a.v, b0, 0); v1 = *chunk_ptr(a.v, b0, 1);
+      *lds_chunk(lds_k, kKS, 0) = k0; *lds_chunk(lds_k, kKS, 1) = k1;
+      *lds_chunk(lds_v, kVS, 0) = v0; *lds_chunk(lds_v, kVS, 1) = v1;
     }
-    if (n_full > 2) gload_tile(a.k, full_base(2), kst);
+    if (n_full > 1) {
+      const int b1 = full_base(1);
+      k0 = *chunk_ptr(a.k, b1, 0); k1 = *chunk_ptr(a.k, b1, 1);
+      v0 = *chunk_ptr(a.v, b1, 0); v1 = *chunk_ptr(a.v, b1, 1);
+    }
+    int base_t2 = n_full > 2 ? full_base(2) : 0;   // first kv row of tile t+2, fetched one iteration early
     __syncthreads();
 
     f32x16 s0, s1;
-    bf16x8 p0[2], p1[2];
-    qk_block(lds_k, 0, s0);
-
+    bf16x8 pa[2], pb[2];      // probabilities of the two 32-token halves of a tile
+    int vprev = 0;            // V buffer of the previous tile
+    int vcur = 0;
     for (int t = 0; t < n_full; ++t) {
-      const uint16_t* k_cur = lds_k + (t & 1) * kKTile;
-      const uint16_t* k_nxt = lds_k + ((t + 1) & 1) * kKTile;
-      const uint16_t* v_cur = lds_v + (t & 1) * kVTile;
-      const uint16_t* v_prv = lds_v + ((t + 1) & 1) * kVTile;
-
-      // ---- step A: scores of block 2t+1 | probabilities of block 2t | accumulate block 2t-1
-      if (t > 0) {
-        maybe_rescale(s0, &p1);
-        qk_block(k_cur, 1, s1);
-        exp_block(s0, p0);
-        pv_block(v_prv, 1, p1);
-      } else {
-        maybe_rescale(s0, nullptr);
-        qk_block(k_cur, 1, s1);
-        exp_block(s0, p0);
-      }
-
-      // K(t) and V(t-1) are dead now: refill their buffers with K(t+2) and V(t+1)
-      __syncthreads();
-      if (t + 2 < n_full) lwrite_tile(lds_k + (t & 1) * kKTile, kKS, kst);
-      if (t + 1 < n_full) lwrite_tile(lds_v + ((t + 1) & 1) * kVTile, kVS, vst);
-      if (t + 3 < n_full) gload_tile(a.k, full_base(t + 3), kst);
-      if (t + 2 < n_full) gload_tile(a.v, full_base(t + 2), vst);
-
-      // ---- step B: scores of block 2t+2 | probabilities of block 2t+1 | accumulate block 2t
-      maybe_rescale(s1, &p0);
+      const uint16_t* kt = lds_k + (t & 1) * kKTile;
+      const uint16_t* vt = lds_v + vcur * kVTile;
+      const int vnext = vcur == 2 ? 0 : vcur + 1;
+      // tile t+1 (fetched during the previous iteration) goes to the free buffers; fetch t+2
       if (t + 1 < n_full) {
-        qk_block(k_nxt, 0, s0);
-        exp_block(s1, p1);
-        pv_block(v_cur, 0, p0);
-      } else {
-        exp_block(s1, p1);
-        pv_block(v_cur, 0, p0);
+        uint16_t* kn = lds_k + ((t + 1) & 1) * kKTile;
+        uint16_t* vn = lds_v + vnext * kVTile;
+        *lds_chunk(kn, kKS, 0) = k0; *lds_chunk(kn, kKS, 1) = k1;
+        *lds_chunk(vn, kVS, 0) = v0; *lds_chunk(vn, kVS, 1) = v1;
       }
+      if (t + 2 < n_full) {
+        k0 = *chunk_ptr(a.k, base_t2, 0); k1 = *chunk_ptr(a.k, base_t2, 1);
+        v0 = *chunk_ptr(a.v, base_t2, 0); v1 = *chunk_ptr(a.v, base_t2, 1);
+      }
+      if (t + 3 < n_full) base_t2 = full_base(t + 3);
+      if (group_b && t > 0) {
+        const uint16_t* vp = lds_v + vprev * kVTile;
+        TL_SETPRIO(1);
+        pv_block(vp, 0, pa);
+        pv_block(vp, 1, pb);
+        sched_pv_tile();
+        TL_SETPRIO(0);
+      }
+      TL_SETPRIO(1);
+      qk_tile(kt, s0, s1);
+      sched_qk_tile();
+      TL_SETPRIO(0);
+      maybe_rescale(s0, s1);
+      exp_block(s0, pa);
+      exp_block(s1, pb);
+      if (!group_b) {
+        TL_SETPRIO(1);
+        pv_block(vt, 0, pa);
+        pv_block(vt, 1, pb);
+        sched_pv_tile();
+        TL_SETPRIO(0);
+      }
+      __syncthreads();
+      vprev = vcur;
+      vcur = vnext;
     }
-    // the last block is still pending
-    pv_block(lds_v + ((n_full - 1) & 1) * kVTile, 1, p1);
+    if (group_b) {
+      const uint16_t* vp = lds_v + vprev * kVTile;
+      pv_block(vp, 0, pa);
+      pv_block(vp, 1, pb);
+    }
     __syncthreads();
   }
 
@@ -293,11 +330,16 @@ __global__ __launch_bounds__(kThreads) void row_tile_attn_kernel(const AttnArgs 
       base = a.part_tile[2 * (wk.part_off + pt)];
       valid = a.part_tile[2 * (wk.part_off + pt) + 1];
     }
-    uint4 kst[2], vst[2];
-    gload_tile_masked(a.k, base, valid, kst);
-    gload_tile_masked(a.v, base, valid, vst);   // rows beyond `valid` are zero: 0 * garbage cannot make NaN
-    lwrite_tile(lds_k, kKS, kst);
-    lwrite_tile(lds_v, kVS, vst);
+    {
+      // rows beyond `valid` are written as zero: 0 * garbage cannot make NaN
+      const uint4 z = make_uint4(0, 0, 0, 0);
+      const uint4 k0 = c_tr < valid ? *chunk_ptr(a.k, base, 0) : z;
+      const uint4 k1 = c_tr + 32 < valid ? *chunk_ptr(a.k, base, 1) : z;
+      const uint4 v0 = c_tr < valid ? *chunk_ptr(a.v, base, 0) : z;
+      const uint4 v1 = c_tr + 32 < valid ? *chunk_ptr(a.v, base, 1) : z;
+      *lds_chunk(lds_k, kKS, 0) = k0; *lds_chunk(lds_k, kKS, 1) = k1;
+      *lds_chunk(lds_v, kVS, 0) = v0; *lds_chunk(lds_v, kVS, 1) = v1;
+    }
     __syncthreads();
 #pragma unroll 1
     for (int hb = 0; hb < 2; ++hb) {
@@ -311,7 +353,7 @@ __global__ __launch_bounds__(kThreads) void row_tile_attn_kernel(const AttnArgs 
         if (CAUSAL) hide = hide || (base + kv > token);
         if (hide) s[r] = -INFINITY;
       }
-      maybe_rescale(s, nullptr);
+      maybe_rescale(s, s);
       bf16x8 pb[2];
       if (st.m_ref == -INFINITY) {
         // every key so far is hidden from this row: probabilities are zero
