@@ -23,6 +23,9 @@
 // diagonal, are masked and go through a plain path afterwards.
 #include "attn_common.h"
 
+#ifndef TL_STAGE_POS
+#define TL_STAGE_POS 0
+#endif
 #ifdef TL_NO_SETPRIO
 #define TL_SETPRIO(x)
 #else
@@ -40,6 +43,7 @@ constexpr int kKTile = kKvTile * kKS;
 constexpr int kVTile = kKvTile * kVS;
 constexpr size_t kLdsBytes = (size_t)(2 * kKTile + 3 * kVTile) * sizeof(uint16_t);
 constexpr float kRescaleLog2 = 8.0f;  // raise the reference maximum when exceeded by 2^8
+constexpr float kOptimisticLimit = 4294967296.0f;  // 2^32
 
 // Lanes l and l^32 exchange x: returns {own, partner} in some order.  The swap instruction
 // exchanges the upper half of its first operand with the lower half of its second; the second
@@ -274,17 +278,22 @@ __global__ __launch_bounds__(kThreads) void row_tile_attn_kernel(const AttnArgs 
       const uint16_t* vt = lds_v + vcur * kVTile;
       const int vnext = vcur == 2 ? 0 : vcur + 1;
       // tile t+1 (fetched during the previous iteration) goes to the free buffers; fetch t+2
-      if (t + 1 < n_full) {
-        uint16_t* kn = lds_k + ((t + 1) & 1) * kKTile;
-        uint16_t* vn = lds_v + vnext * kVTile;
-        *lds_chunk(kn, kKS, 0) = k0; *lds_chunk(kn, kKS, 1) = k1;
-        *lds_chunk(vn, kVS, 0) = v0; *lds_chunk(vn, kVS, 1) = v1;
-      }
-      if (t + 2 < n_full) {
-        k0 = *chunk_ptr(a.k, base_t2, 0); k1 = *chunk_ptr(a.k, base_t2, 1);
-        v0 = *chunk_ptr(a.v, base_t2, 0); v1 = *chunk_ptr(a.v, base_t2, 1);
-      }
-      if (t + 3 < n_full) base_t2 = full_base(t + 3);
+      auto stage_next = [&]() {
+        if (t + 1 < n_full) {
+          uint16_t* kn = lds_k + ((t + 1) & 1) * kKTile;
+          uint16_t* vn = lds_v + vnext * kVTile;
+          *lds_chunk(kn, kKS, 0) = k0; *lds_chunk(kn, kKS, 1) = k1;
+          *lds_chunk(vn, kVS, 0) = v0; *lds_chunk(vn, kVS, 1) = v1;
+        }
+        if (t + 2 < n_full) {
+          k0 = *chunk_ptr(a.k, base_t2, 0); k1 = *chunk_ptr(a.k, base_t2, 1);
+          v0 = *chunk_ptr(a.v, base_t2, 0); v1 = *chunk_ptr(a.v, base_t2, 1);
+        }
+        if (t + 3 < n_full) base_t2 = full_base(t + 3);
+      };
+#if TL_STAGE_POS == 0
+      stage_next();
+#endif
       if (group_b && t > 0) {
         const uint16_t* vp = lds_v + vprev * kVTile;
         TL_SETPRIO(1);
@@ -297,9 +306,26 @@ __global__ __launch_bounds__(kThreads) void row_tile_attn_kernel(const AttnArgs 
       qk_tile(kt, s0, s1);
       sched_qk_tile();
       TL_SETPRIO(0);
-      maybe_rescale(s0, s1);
+#if TL_STAGE_POS == 1
+      stage_next();
+#endif
+      // The exponent's reference point is set from the first tile; afterwards probabilities are
+      // computed optimistically against it and the (rare) tile whose row sum comes out above
+      // 2^32 -- scores far above the reference -- is redone with the reference raised first.
+      if (t == 0) maybe_rescale(s0, s1);
+      const float l_before = st.l_run;
       exp_block(s0, pa);
       exp_block(s1, pb);
+      if (__builtin_amdgcn_ballot_w64(!(st.l_run - l_before < kOptimisticLimit)) != 0) {
+        st.l_run = l_before;
+        qk_tile(kt, s0, s1);
+        maybe_rescale(s0, s1);
+        exp_block(s0, pa);
+        exp_block(s1, pb);
+      }
+#if TL_STAGE_POS == 2
+      stage_next();
+#endif
       if (!group_b) {
         TL_SETPRIO(1);
         pv_block(vt, 0, pa);
@@ -307,6 +333,9 @@ __global__ __launch_bounds__(kThreads) void row_tile_attn_kernel(const AttnArgs 
         sched_pv_tile();
         TL_SETPRIO(0);
       }
+#if TL_STAGE_POS == 3
+      stage_next();
+#endif
       __syncthreads();
       vprev = vcur;
       vcur = vnext;
