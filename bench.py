@@ -28,6 +28,32 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 
 
+def measured_traffic(kernel, workload):
+    """HBM bytes per launch of `kernel` on `workload`, from the rocprofv3 --pmc FETCH_SIZE /
+    WRITE_SIZE runs summarised under profiles/ (scaled by a plain copy of known size); None if
+    that pair has not been profiled."""
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    try:
+        with open(path) as f:
+            table = json.load(f)
+    except (OSError, ValueError):
+        return None
+    ent = table.get("%s@%s" % (kernel, workload))
+    return ent["hbm_bytes_per_launch"] if ent else None
+
+
+def calibrate_copy(torch, n_bytes=1 << 30):
+    """A plain device copy of known size, for scaling the FETCH_SIZE / WRITE_SIZE counters."""
+    src = torch.ones(n_bytes // 2, dtype=torch.bfloat16, device="cuda")
+    dst = torch.empty_like(src)
+    torch.cuda.synchronize()
+    for _ in range(3):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    print(json.dumps({"calibrate_copy_bytes_read": n_bytes, "calibrate_copy_bytes_written": n_bytes,
+                      "kernel": "torch elementwise copy (bf16)", "launches": 3}))
+
+
 def _setup(batch, torch, B):
     dev = "cuda"
     shape = (batch.n_slots, batch.seg_len, batch.kv_heads, batch.head_dim)
@@ -143,6 +169,8 @@ def main():
     ap.add_argument("--split-segments", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true", help="skip the appended decode measurement")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run a 1 GiB device copy (to scale rocprofv3 FETCH_SIZE/WRITE_SIZE) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding or collectives); use --gpus 1", file=sys.stderr)
@@ -155,6 +183,9 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     B.load_library()
+    if args.calibrate_copy:
+        calibrate_copy(torch)
+        return
 
     maker = {"prefill": wl.prefill, "decode": wl.decode, "longctx": wl.longctx, "tiny": wl.tiny,
              "multiturn": lambda: wl.multiturn(turn=7)}[args.workload]
@@ -169,10 +200,14 @@ def main():
             by = w["kv_bytes"] + w["q_bytes"] + w["partial_bytes"]
             ach = by / seg_s / 1e9
             return {"kernel": "splitk_unit_attn_kernel", "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS,
-                    "unit": "GB/s", "frac": ach / PEAK_HBM_GBS, "traffic": None, "avg_kernel_ms": r["segment_attn_ms"]}
+                    "unit": "GB/s", "frac": ach / PEAK_HBM_GBS,
+                    "traffic": measured_traffic("splitk_unit_attn_kernel", b.name),
+                    "algorithmic_bytes": by, "avg_kernel_ms": r["segment_attn_ms"]}
         ach = w["flops_prefix"] / seg_s / 1e12
         return {"kernel": "row_tile_attn_kernel", "bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS,
-                "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS, "traffic": None, "avg_kernel_ms": r["segment_attn_ms"]}
+                "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS,
+                "traffic": measured_traffic("row_tile_attn_kernel", b.name),
+                "algorithmic_flops": w["flops_prefix"], "avg_kernel_ms": r["segment_attn_ms"]}
 
     line = {
         "metric": "merged tok/s (one layer: partial attention over the segment pool + causal self block + LSE merge)",
