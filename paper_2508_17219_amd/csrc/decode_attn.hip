@@ -9,6 +9,15 @@
 // LDS -> MFMA 16x16x32 operands.  The 8 (or fewer) GQA rows ride in a 16-row MFMA tile.
 #include "attn_common.h"
 
+// Each wave stages its kv head's tiles in an LDS region of its own, and a wave's LDS
+// operations execute in program order, so no workgroup barrier is needed between the
+// wave's writes and its reads: a compiler-level ordering point is enough.
+#ifdef TL_UNIT_BLOCK_BARRIER
+#define TL_UNIT_SYNC() __syncthreads()
+#else
+#define TL_UNIT_SYNC() do { __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront"); __builtin_amdgcn_wave_barrier(); } while (0)
+#endif
+
 namespace tl {
 
 namespace {
@@ -109,7 +118,7 @@ __global__ __launch_bounds__(kThreads) void splitk_unit_attn_kernel(const AttnAr
     int nbase = 0, nvalid = 0;
     const bool have_next = next_tile(nbase, nvalid);
     if (have_next) gload(nbase, nvalid);
-    __syncthreads();
+    TL_UNIT_SYNC();
 
     if (active) {
       // S^T = K Q^T : two blocks of 16 tokens
@@ -163,7 +172,7 @@ __global__ __launch_bounds__(kThreads) void splitk_unit_attn_kernel(const AttnAr
         o[d] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, pb, acc, 0, 0, 0);
       }
     }
-    __syncthreads();
+    TL_UNIT_SYNC();
     have = have_next;
     base = nbase;
     valid = nvalid;

@@ -129,7 +129,19 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
     // ---- final items, work lists ----------------------------------------------------------
     const int tok_tile = kRowTile / G;
     int split = split_segments;
-    if (split == 0) split = std::max(1, 512 / pool->seg_len);
+    if (split == 0) {
+      // Split-K chunk: long enough to amortise a unit's start-up (measured on the decode
+      // workload: 2 slots 5.6 TB/s, 8 slots 6.0, 16 slots 6.1), short enough to leave about
+      // 2048 units for 256 CUs; never below 512 tokens or above 32 slots.
+      int64_t few_entries = 0;
+      for (const RawItem& it : raw) {
+        int64_t n_tok = 0;
+        for (int32_t r : it.reqs) n_tok += ntok_of(r);
+        if (n_tok * G <= kUnitRows) few_entries += it.end - it.begin;
+      }
+      const int lo = std::max(1, 512 / pool->seg_len);
+      split = (int)std::min<int64_t>(32, std::max<int64_t>(lo, (few_entries + 2047) / 2048));
+    }
     int32_t row_cursor = 0;
     p->item_tok_ptr.push_back(0);
     p->item_slot_ptr.push_back(0);
