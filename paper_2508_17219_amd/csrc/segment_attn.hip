@@ -3,8 +3,9 @@
 // tokens' self-attention is one more such partial).
 //
 // One workgroup = 8 wavefronts = 256 query rows of one kv head (row = (token, head in the
-// GQA group)); wave w owns rows 32w..32w+31.  The workgroup walks the work item's kv tokens
-// in tiles of 64, staged through LDS with 16-byte coalesced loads.
+// GQA group)); wave w owns rows 32w..32w+31 (two waves per SIMD).  The workgroup walks the work
+// item's kv tokens in tiles of 64, brought into LDS by direct global->LDS loads (16 bytes per
+// lane, whole 256-byte rows, three tile buffers each for K and V).
 //
 // With 32x32x16 bf16 MFMA, per 32-token block and wave:
 //   S^T[kv, row] = K[kv, :] . Q[row, :]      A = K block from LDS, B = Q (registers)
@@ -13,37 +14,49 @@
 //   O^T[d, row] += V^T[d, kv] . P^T[kv, row]  A = V block read transposed from LDS, B = P
 // Scores never leave registers between the two products.
 //
-// Completely filled tiles run in a ping-pong between the two wavefronts that share a SIMD
-// (waves w and w+4): waves 0-3 go scores -> softmax -> accumulate within an iteration, waves 4-7
-// accumulate the previous tile first and then do scores -> softmax, so that one wave's MFMA
-// phase lines up with the other's vector-ALU phase.  V is triple buffered for that reason.
-// The running maximum is only a reference point for the exponent (any reference gives the
-// same normalised result), so it is raised -- and O rescaled -- only when a tile maximum
-// exceeds it by more than 2^8.  Tiles cut short by a slot's fill, and the tiles on the causal
-// diagonal, are masked and go through a plain path afterwards.
+// Fast path (completely filled tiles): the stream of 32-token blocks is software-pipelined
+// inside each wave.  While the vector ALU turns the scores of block i into probabilities, the
+// matrix unit computes the scores of block i+1 and accumulates block i-1; the three touch
+// different registers, so neither unit waits for the other.  (Measured on gfx950: MFMA and
+// vector-ALU instructions of the SAME wave overlap, those of two waves of a SIMD hardly do, and
+// both kinds leave through one issue port, so the vector-ALU instruction count per MFMA is what
+// the loop is trimmed for: LDS addresses are loop-invariant registers plus immediates -- the
+// loop is unrolled over the three tile buffers -- and LDS operands are fetched three operand
+// groups ahead of their MFMA.)  The exponent's reference point is fixed from the first block
+// (any reference gives the same normalised result), which leaves the loop free of branches and
+// of rescaling; if a row sum ends up above 2^60 or not finite -- scores far above the reference
+// -- the workgroup discards the result and redoes the full tiles on the careful path.
+// Careful path (tiles cut short by a slot's fill, tiles on the causal diagonal, and the
+// redo): one tile at a time, masked, running maximum raised (and O rescaled) when a block
+// exceeds it by more than 2^8.
+#include <type_traits>
+
 #include "attn_common.h"
 
-#ifndef TL_STAGE_POS
-#define TL_STAGE_POS 0
-#endif
-#ifdef TL_NO_SETPRIO
-#define TL_SETPRIO(x)
-#else
-#define TL_SETPRIO(x) __builtin_amdgcn_s_setprio(x)
+#ifndef TL_RG
+#define TL_RG 1
 #endif
 
 namespace tl {
 
 namespace {
 
-constexpr int kThreads = 512;
-constexpr int kKS = kLdsStride;      // K row stride in LDS (bf16)
-constexpr int kVS = kVStrideTile;    // V row stride in LDS (bf16)
+constexpr int kRG = TL_RG;                                    // 32-row groups per wave
+constexpr int kWaves = kRowTile / (32 * kRG);             // 8
+constexpr int kThreads = 64 * kWaves;                     // 512
+constexpr int kChunks = kKvTile * 16 / kThreads;          // 16-byte chunks per thread per K (or V) tile: 2
+constexpr int kChunkRows = kThreads / 16;                 // rows covered by one chunk index: 32
+constexpr int kKS = kHeadDim;        // K row stride in LDS (bf16): unpadded, 16-byte chunks swizzled
+constexpr int kVS = kHeadDim;        // V row stride in LDS (bf16): unpadded, 16-byte chunks swizzled
 constexpr int kKTile = kKvTile * kKS;
 constexpr int kVTile = kKvTile * kVS;
-constexpr size_t kLdsBytes = (size_t)(2 * kKTile + 3 * kVTile) * sizeof(uint16_t);
-constexpr float kRescaleLog2 = 8.0f;  // raise the reference maximum when exceeded by 2^8
-constexpr float kOptimisticLimit = 4294967296.0f;  // 2^32
+constexpr int kIdxRing = 512;        // tile-base entries kept in LDS (ring over the work item's tile list)
+constexpr int kBufs = 3;             // LDS tile buffers: K(t+2) and V(t+1) stream in while tile t is computed
+constexpr size_t kLdsBytes = (size_t)kBufs * (kKTile + kVTile) * sizeof(uint16_t) + (kIdxRing + 4) * sizeof(int32_t);
+constexpr float kRescaleLog2 = 8.0f;             // careful path: raise the maximum when exceeded by 2^8
+constexpr float kFastPathLimit = 1.152921504606846976e18f;  // 2^60
+constexpr int kDmaPerWave = 16 / kWaves;                  // direct-load instructions per wave per K (or V) tile
+constexpr int kDepth = 3;            // LDS operands in flight ahead of the MFMA that uses them (ring of kDepth + 1)
 
 // Lanes l and l^32 exchange x: returns {own, partner} in some order.  The swap instruction
 // exchanges the upper half of its first operand with the lower half of its second; the second
@@ -80,70 +93,63 @@ __device__ __forceinline__ float max16(const f32x16& s) {
   return fmaxf(fmaxf(fmaxf(a, b), fmaxf(c, d)), fmaxf(e, s[15]));
 }
 
-// Instruction order for one tile's MFMA phase: LDS reads run two groups of four MFMAs ahead
-// of their use, so that the matrix unit is not left waiting on LDS latency.
-// (mask 0x008 = MFMA, 0x100 = LDS read)
-__device__ __forceinline__ void sched_qk_tile() {
-  __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
-  __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
-  __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
-  __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
-  __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
-  __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
-}
-__device__ __forceinline__ void sched_pv_tile() {
-  __builtin_amdgcn_sched_group_barrier(0x100, 16, 0);
-  __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
-  __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
-  __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
-  __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
-  __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
-}
-
-struct RowState {
-  f32x16 o[4];     // O^T accumulators: o[d][r] = channel 32 d + 8 (r/4) + 4 h + r%4 of row l32
-  float m_ref;     // reference maximum of the exponent (raw score units), -inf before any key
-  float l_run;     // this lane's share of sum exp(s - m_ref)
-};
-
 template <bool CAUSAL, int VREAD>
-__global__ __launch_bounds__(kThreads) void row_tile_attn_kernel(const AttnArgs a) {
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kRG, 2 / kRG))) void row_tile_attn_kernel(const AttnArgs a) {
   extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
-  uint16_t* lds_k = lds;                 // [2][64][kKS]
-  uint16_t* lds_v = lds + 2 * kKTile;    // [3][64][kVS]
+  uint16_t* lds_k = lds;                 // [kBufs][64][kKS]
+  uint16_t* lds_v = lds + kBufs * kKTile;    // [kBufs][64][kVS]
+  int32_t* lds_idx = (int32_t*)(lds + kBufs * (kKTile + kVTile));   // [kIdxRing]
+  int32_t* lds_flag = lds_idx + kIdxRing;
 
   const int g = blockIdx.x % a.kv_heads;
   const Work wk = a.work[blockIdx.x / a.kv_heads];
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63, l32 = lane & 31, h = lane >> 5;
   const int G = 1 << a.log2g;
-
-  const int row = wave * 32 + l32;
-  const int tok_local = row >> a.log2g;
-  const int j = row & (G - 1);
-  const bool row_ok = tok_local < wk.n_tok;
-  const int token = row_ok ? a.tok[wk.tok_off + tok_local] : -1;
   const int first_token = a.tok[wk.tok_off];   // causal work: tokens of a tile are consecutive
 
-  // Q as the B operand: lane holds row l32, head-dim elements 16 s + 8 h .. +7 of step s
-  bf16x8 qreg[8];
-  {
-    const uint4* qp = (const uint4*)(a.q + ((size_t)(row_ok ? token : 0) * a.q_heads + g * G + j) * kHeadDim);
+  // per row group: this lane's row, its token and head
+  int tok_local[kRG], head_j[kRG], token[kRG];
+  bool row_ok[kRG];
+#pragma unroll
+  for (int rg = 0; rg < kRG; ++rg) {
+    const int row = wave * (32 * kRG) + 32 * rg + l32;
+    tok_local[rg] = row >> a.log2g;
+    head_j[rg] = row & (G - 1);
+    row_ok[rg] = tok_local[rg] < wk.n_tok;
+    token[rg] = row_ok[rg] ? a.tok[wk.tok_off + tok_local[rg]] : -1;
+  }
+
+  // Q as the B operand: lane holds its row, head-dim elements 16 s + 8 h .. +7 of step s
+  bf16x8 qreg[kRG][8];
+#pragma unroll
+  for (int rg = 0; rg < kRG; ++rg) {
+    const uint4* qp =
+        (const uint4*)(a.q + ((size_t)(row_ok[rg] ? token[rg] : 0) * a.q_heads + g * G + head_j[rg]) * kHeadDim);
 #pragma unroll
     for (int s = 0; s < 8; ++s) {
       uint4 u = make_uint4(0, 0, 0, 0);
-      if (row_ok) u = qp[2 * s + h];
-      qreg[s] = as_bf16x8(u);
+      if (row_ok[rg]) u = qp[2 * s + h];
+      qreg[rg][s] = as_bf16x8(u);
     }
   }
 
-  RowState st;
+  // O^T accumulators: o[rg][d][r] = channel 32 d + 8 (r/4) + 4 h + r%4 of the lane's row in group rg
+  f32x16 o[kRG][4];
+  float m_ref[kRG];   // reference point of the exponent (raw score units), -inf before any key
+  float l_run[kRG];   // this lane's share of sum exp(s - m_ref)
+  auto reset_state = [&]() {
 #pragma unroll
-  for (int d = 0; d < 4; ++d)
+    for (int rg = 0; rg < kRG; ++rg) {
 #pragma unroll
-    for (int r = 0; r < 16; ++r) st.o[d][r] = 0.f;
-  st.m_ref = -INFINITY;
-  st.l_run = 0.f;
+      for (int d = 0; d < 4; ++d)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[rg][d][r] = 0.f;
+      m_ref[rg] = -INFINITY;
+      l_run[rg] = 0.f;
+    }
+  };
+  reset_state();
   const float c = a.scale_log2e;
 
   // which tiles are full (no masking needed for any row of this workgroup)
@@ -155,200 +161,346 @@ __global__ __launch_bounds__(kThreads) void row_tile_attn_kernel(const AttnArgs 
     n_full = wk.n_full;
     n_part = wk.n_part;
   }
-  auto full_base = [&](int t) -> int { return CAUSAL ? wk.kv_off + kKvTile * t : a.tile_base[wk.full_off + t]; };
+  // first kv row of full tile t: arithmetic for the causal block, else from the item's tile
+  // list, kept in an LDS ring (a dependent global load per iteration would stall the wave)
+  auto full_base = [&](int t) -> int { return CAUSAL ? wk.kv_off + kKvTile * t : lds_idx[t & (kIdxRing - 1)]; };
+  auto ring_fill = [&](int first, int count) {   // entries [first, first+count) of the list, clipped
+    if (!CAUSAL)
+      for (int i = first + tid; i < first + count && i < n_full; i += kThreads)
+        lds_idx[i & (kIdxRing - 1)] = a.tile_base[wk.full_off + i];
+  };
 
-  // ---- global <-> LDS staging: 2 chunks of 16 B per thread per tile, for K and for V ----
-  const size_t kv_row = (size_t)a.kv_heads * kHeadDim;
-  const int c_tr = tid >> 4, c_part = tid & 15;          // chunk 0: token c_tr, chunk 1: token c_tr + 32
+  // ---- global <-> LDS staging: 4 chunks of 16 B per thread per tile, for K and for V ----
+  // chunk i of a thread: tile row (tid >> 4) + 16 i, 16-byte column tid & 15
   // (plain scalars, not arrays: the staged chunks must live in registers across iterations)
+  const size_t kv_row = (size_t)a.kv_heads * kHeadDim;
+  const int c_tr = tid >> 4, c_part = tid & 15;
+  // address = (tile's first row: workgroup-uniform, 64-bit, scalar registers) + (this thread's
+  // constant 32-bit offset inside a tile), so that a tile costs no per-lane 64-bit arithmetic
+  const unsigned lane_off0 = (unsigned)((c_tr * kv_row + (size_t)g * kHeadDim) * 2 + c_part * 16);
+  const unsigned chunk_step = (unsigned)(kChunkRows * kv_row * 2);
   auto chunk_ptr = [&](const uint16_t* src, int base, int i) -> const uint4* {
-    return (const uint4*)src + ((size_t)(base + c_tr + 32 * i) * kv_row + (size_t)g * kHeadDim) / 8 + c_part;
+    const char* tile = (const char*)src + (size_t)__builtin_amdgcn_readfirstlane(base) * (kv_row * 2);
+    return (const uint4*)(tile + (lane_off0 + chunk_step * i));
   };
-  auto lds_chunk = [&](uint16_t* tile, int stride, int i) -> uint4* {
-    return (uint4*)&tile[(c_tr + 32 * i) * stride + c_part * 8];
+  auto lds_chunk_k = [&](uint16_t* tile, int i) -> uint4* {
+    const int r_ = c_tr + kChunkRows * i;
+    return (uint4*)&tile[r_ * kKS + 8 * (c_part ^ (r_ & 15))];
   };
+  auto lds_chunk_v = [&](uint16_t* tile, int i) -> uint4* {
+    const int r_ = c_tr + kChunkRows * i;
+    return (uint4*)&tile[r_ * kVS + 8 * (c_part ^ (4 * (r_ & 3)))];
+  };
+  // direct global -> LDS load of a whole tile: wave w issues instructions w and w + 8 (of 16), each
+  // filling rows 4 i .. 4 i + 3; lane L lands at row 4 i + L / 16, position L % 16, so it fetches
+  // the logical chunk that belongs there
+  unsigned dma_off_k[kDmaPerWave], dma_off_v[kDmaPerWave];
+#pragma unroll
+  for (int u = 0; u < kDmaPerWave; ++u) {
+    const int r_ = 4 * (wave + kWaves * u) + (lane >> 4), pos = lane & 15;
+    dma_off_k[u] = (unsigned)((r_ * kv_row + (size_t)g * kHeadDim) * 2 + 16 * (pos ^ (r_ & 15)));
+    dma_off_v[u] = (unsigned)((r_ * kv_row + (size_t)g * kHeadDim) * 2 + 16 * (pos ^ (4 * (r_ & 3))));
+  }
+  // (issued as inline assembly: the compiler does not see these loads, so it puts no wait for them
+  // in front of the LDS reads that follow; dma_wait() before the iteration's barrier is the wait)
+  const unsigned lds_base_addr = __builtin_amdgcn_readfirstlane((unsigned)(size_t)(__attribute__((address_space(3))) void*)lds);
+  const unsigned dma_wave_off = __builtin_amdgcn_readfirstlane(wave) * (4 * kHeadDim * 2);
+  auto dma_tile = [&](const uint16_t* src, int base, uint16_t* tile, const unsigned (&off)[kDmaPerWave]) {
+    const char* trow = (const char*)src + (size_t)__builtin_amdgcn_readfirstlane(base) * (kv_row * 2);
+#pragma unroll
+    for (int u = 0; u < kDmaPerWave; ++u) {
+      const unsigned dst = lds_base_addr + (unsigned)((tile - lds) + kWaves * u * 4 * kHeadDim) * 2u + dma_wave_off;
+      asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(trow + off[u]), "s"(dst) : "memory");
+    }
+  };
+  // wait for all of this wave's direct loads (vmcnt(0); the other counters are left alone so that
+  // LDS operand reads already in flight stay in flight)
+  auto dma_wait = [&]() { __builtin_amdgcn_s_waitcnt(0x0F70); };
 
-  // ---- the three stages of a block ----
-  // scores of one 32-token block (half hb of the K tile at `kt`)
-  auto qk_block = [&](const uint16_t* kt, int hb, f32x16& s) {
+  // ---- building blocks ----
+  // LDS tiles are unpadded rows of 256 B = 16 chunks of 16 B, written by direct global->LDS
+  // loads (one wave instruction fills 4 rows contiguously).  Bank conflicts are avoided by
+  // storing logical chunk c of row r at position c ^ swz(r):
+  //   K: swz(r) = r & 15      -> the 16 rows that 16 lanes read at one logical chunk hit 16 positions
+  //   V: swz(r) = 4 (r & 3)   -> the 4 rows x 4 chunks of one transposing read hit 16 positions
+  auto k_operand = [&](const uint16_t* kt, int hb, int s8) -> bf16x8 {
+    return *(const bf16x8*)&kt[(32 * hb + l32) * kKS + 8 * ((2 * s8 + h) ^ (l32 & 15))];
+  };
+  // V^T operand of accumulation step (sp, d) of block hb: channels 32 d .. 32 d + 31, block
+  // tokens 16 sp + {4h..4h+3, 8+4h..8+4h+3} -- the order in which the score registers hold them
+  auto v_operand = [&](const uint16_t* vt, int hb, int sp, int d) -> bf16x8 {
+    const int kvb = 32 * hb + 16 * sp;
+    if (VREAD == 0) {
+      const int blk = lane >> 4, jj = lane & 15;
+      // logical chunk 4 d + 2 (blk & 1) + (jj & 3) / 2 of row kvb + 4 (blk >> 1) + jj / 4 (row & 3 = jj / 4)
+      const int chunk = (4 * d + 2 * (blk & 1) + ((jj & 3) >> 1)) ^ (4 * (jj >> 2));
+      const uint16_t* p = vt + (kvb + 4 * (blk >> 1) + (jj >> 2)) * kVS + 8 * chunk + 4 * (jj & 1);
+      return join_tr(lds_read_tr(p), lds_read_tr(p + 8 * kVS));
+    } else {
+      s16x8 t;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) s[r] = 0.f;
-    const uint16_t* p = kt + (32 * hb + l32) * kKS + 8 * h;
-#pragma unroll
-    for (int s8 = 0; s8 < 8; ++s8) {
-      const bf16x8 ak = *(const bf16x8*)&p[16 * s8];
-      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak, qreg[s8], s, 0, 0, 0);
+      for (int e = 0; e < 8; ++e) {
+        const int r_ = kvb + 8 * (e >> 2) + 4 * h + (e & 3), col = 32 * d + l32;
+        t[e] = (short)vt[r_ * kVS + 8 * ((col >> 3) ^ (4 * (r_ & 3))) + (col & 7)];
+      }
+      return __builtin_bit_cast(bf16x8, t);
     }
   };
-  // scores of both blocks of a tile, the two accumulation chains interleaved so that
-  // consecutive MFMAs are independent
-  auto qk_tile = [&](const uint16_t* kt, f32x16& sa, f32x16& sb) {
-#pragma unroll
-    for (int r = 0; r < 16; ++r) { sa[r] = 0.f; sb[r] = 0.f; }
-    const uint16_t* p = kt + l32 * kKS + 8 * h;
+  // scores of block hb of the K tile at kt, both row groups (each K operand is used twice)
+  auto qk_block = [&](const uint16_t* kt, int hb, f32x16 (&s)[kRG]) {
+    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int s8 = 0; s8 < 8; ++s8) {
-      const bf16x8 ak0 = *(const bf16x8*)&p[16 * s8];
-      const bf16x8 ak1 = *(const bf16x8*)&p[32 * kKS + 16 * s8];
-      sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak0, qreg[s8], sa, 0, 0, 0);
-      sb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak1, qreg[s8], sb, 0, 0, 0);
+      const bf16x8 ak = k_operand(kt, hb, s8);
+#pragma unroll
+      for (int rg = 0; rg < kRG; ++rg)
+        s[rg] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak, qreg[rg][s8], s8 == 0 ? zero : s[rg], 0, 0, 0);
     }
   };
-  // probabilities of a block against the current reference: p = 2^(c (s - m_ref)); B operands
-  // pb[sp] cover registers 8 sp .. 8 sp + 7, i.e. block tokens 16 sp + {4h..4h+3, 8+4h..8+4h+3}
-  auto exp_block = [&](f32x16& s, bf16x8 (&pb)[2]) {
-    const float mc = st.m_ref * c;
-    float lsum = 0.f;
+  // probabilities of a block against the reference: p = 2^(c (s - m_ref)); B operands pb[sp]
+  // hold registers 8 sp .. 8 sp + 7
+  auto exp_block = [&](int rg, f32x16& s, bf16x8 (&pb)[2]) {
+    const float mc = m_ref[rg] * c;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      s[r] = fast_exp2(fmaf(s[r], c, -mc));
-      lsum += s[r];
-    }
-    st.l_run += lsum;
+    for (int r = 0; r < 16; ++r) s[r] = fast_exp2(fmaf(s[r], c, -mc));
     pb[0] = pack_bf16x8(s[0], s[1], s[2], s[3], s[4], s[5], s[6], s[7]);
     pb[1] = pack_bf16x8(s[8], s[9], s[10], s[11], s[12], s[13], s[14], s[15]);
-  };
-  // O^T += V^T P^T for one block (half hb of the V tile at `vt`)
-  auto pv_block = [&](const uint16_t* vt, int hb, const bf16x8 (&pb)[2]) {
+    // the normaliser sums the probabilities before their rounding to bf16, in fp32
+    float lsum = 0.f;
 #pragma unroll
-    for (int sp = 0; sp < 2; ++sp) {
-      const int kvb = 32 * hb + 16 * sp;
+    for (int r = 0; r < 16; ++r) lsum += s[r];
+    l_run[rg] += lsum;
+  };
+  auto pv_block = [&](const uint16_t* vt, int hb, const bf16x8 (&pb)[kRG][2]) {
+#pragma unroll
+    for (int sp = 0; sp < 2; ++sp)
 #pragma unroll
       for (int d = 0; d < 4; ++d) {
-        bf16x8 av;
-        if (VREAD == 0) {
-          const int blk = lane >> 4, jj = lane & 15;
-          const uint16_t* p = vt + (kvb + 4 * (blk >> 1) + (jj >> 2)) * kVS + 32 * d + 16 * (blk & 1) + 4 * (jj & 3);
-          av = join_tr(lds_read_tr(p), lds_read_tr(p + 8 * kVS));
-        } else {
-          s16x8 t;
+        const bf16x8 av = v_operand(vt, hb, sp, d);
 #pragma unroll
-          for (int e = 0; e < 8; ++e) t[e] = (short)vt[(kvb + 8 * (e >> 2) + 4 * h + (e & 3)) * kVS + 32 * d + l32];
-          av = __builtin_bit_cast(bf16x8, t);
-        }
-        st.o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, pb[sp], st.o[d], 0, 0, 0);
+        for (int rg = 0; rg < kRG; ++rg)
+          o[rg][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, pb[rg][sp], o[rg][d], 0, 0, 0);
       }
-    }
   };
-  // raise the reference maximum if the scores of a tile (two blocks) exceed it by too much
-  auto maybe_rescale = [&](const f32x16& sa, const f32x16& sb) {
-    const float mx = xor32_max(fmaxf(max16(sa), max16(sb)));
-    const bool need = (mx - st.m_ref) * c > kRescaleLog2 || st.m_ref == -INFINITY;
+  // careful path: raise the reference maximum if the block's scores exceed it by too much
+  auto maybe_rescale = [&](int rg, const f32x16& s) {
+    const float mx = xor32_max(max16(s));
+    const bool need = (mx - m_ref[rg]) * c > kRescaleLog2 || m_ref[rg] == -INFINITY;
     if (__builtin_amdgcn_ballot_w64(need) != 0) {
-      const float m_new = fmaxf(st.m_ref, mx);
-      const float alpha = (m_new == -INFINITY) ? 1.f : fast_exp2((st.m_ref - m_new) * c);
-      st.m_ref = m_new;
-      st.l_run *= alpha;
+      const float m_new = fmaxf(m_ref[rg], mx);
+      const float alpha = (m_new == -INFINITY) ? 1.f : fast_exp2((m_ref[rg] - m_new) * c);
+      m_ref[rg] = m_new;
+      l_run[rg] *= alpha;
 #pragma unroll
       for (int d = 0; d < 4; ++d)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) st.o[d][r] *= alpha;
+        for (int r = 0; r < 16; ++r) o[rg][d][r] *= alpha;
     }
   };
-
-  // ======================= pass 1: full tiles, ping-pong =======================
-  if (n_full > 0) {
-#ifdef TL_PINGPONG
-    const bool group_b = wave >= 4;
-#else
-    const bool group_b = false;
-#endif
-    uint4 k0, k1, v0, v1;
+  // careful path: one tile (rows beyond `valid` hidden; causal work also hides later tokens)
+  auto careful_tile = [&](int base, int valid) {
     {
-      const int b0 = full_base(0);
-      k0 = *chunk_ptr(a.k, b0, 0); k1 = *chunk_ptr(a.k, b0, 1);
-      v0 = *chunk_ptr(a.v, b0, 0); v1 = *chunk_ptr(a.v, b0, 1);
-      *lds_chunk(lds_k, kKS, 0) = k0; *lds_chunk(lds_k, kKS, 1) = k1;
-      *lds_chunk(lds_v, kVS, 0) = v0; *lds_chunk(lds_v, kVS, 1) = v1;
+      // rows beyond `valid` are written as zero: 0 * garbage cannot make NaN
+      const uint4 z = make_uint4(0, 0, 0, 0);
+#pragma unroll
+      for (int i = 0; i < kChunks; ++i) {
+        const bool in = c_tr + kChunkRows * i < valid;
+        const uint4 kk = in ? *chunk_ptr(a.k, base, i) : z;
+        const uint4 vv = in ? *chunk_ptr(a.v, base, i) : z;
+        *lds_chunk_k(lds_k, i) = kk;
+        *lds_chunk_v(lds_v, i) = vv;
+      }
     }
-    if (n_full > 1) {
-      const int b1 = full_base(1);
-      k0 = *chunk_ptr(a.k, b1, 0); k1 = *chunk_ptr(a.k, b1, 1);
-      v0 = *chunk_ptr(a.v, b1, 0); v1 = *chunk_ptr(a.v, b1, 1);
+    __syncthreads();
+#pragma unroll 1
+    for (int hb = 0; hb < 2; ++hb) {
+      if (32 * hb >= valid) break;              // uniform
+      f32x16 s[kRG];
+      qk_block(lds_k, hb, s);
+      bf16x8 pb[kRG][2];
+#pragma unroll
+      for (int rg = 0; rg < kRG; ++rg) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int kv = 32 * hb + 8 * (r >> 2) + 4 * h + (r & 3);
+          bool hide = kv >= valid;
+          if (CAUSAL) hide = hide || (base + kv > token[rg]);
+          if (hide) s[rg][r] = -INFINITY;
+        }
+        maybe_rescale(rg, s[rg]);
+        if (m_ref[rg] == -INFINITY) {
+          // every key so far is hidden from this row: probabilities are zero
+          pb[rg][0] = pack_bf16x8(0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f);
+          pb[rg][1] = pb[rg][0];
+        } else {
+          exp_block(rg, s[rg], pb[rg]);
+        }
+      }
+      pv_block(lds_v, hb, pb);
     }
-    int base_t2 = n_full > 2 ? full_base(2) : 0;   // first kv row of tile t+2, fetched one iteration early
+    __syncthreads();
+  };
+
+  bool redo = false;
+  // ======================= fast path: full tiles, software-pipelined by 32-token block =======================
+  // Steady state, per block i of the tile stream (two blocks per tile = two steps per iteration):
+  //   MFMA:  scores(block i+1)  and  accumulate(block i-1)      16 kRG MFMA each
+  //   VALU:  probabilities(block i)
+  // An iteration is 32 operand groups: one LDS operand (a K fragment, or a transposed V fragment)
+  // and the kRG MFMAs that use it, plus a slice of the probabilities; the operand is fetched
+  // kDepth groups earlier.  sched_barrier(0) after every group keeps the compiler to this order.
+  if (n_full > 0) {
+    if (tid == 0) *lds_flag = 0;
+    ring_fill(0, kIdxRing);
+    {
+      // "tile -1" (V buffer kBufs-1) is multiplied by zero probabilities in the first iteration
+      const uint4 z = make_uint4(0, 0, 0, 0);
+      for (int i = tid; i < kVTile / 8; i += kThreads) ((uint4*)(lds_v + (kBufs - 1) * kVTile))[i] = z;
+    }
+    __syncthreads();
+    dma_tile(a.k, full_base(0), lds_k, dma_off_k);
+    dma_tile(a.v, full_base(0), lds_v, dma_off_v);
+    if (n_full > 1) dma_tile(a.k, full_base(1), lds_k + kKTile, dma_off_k);
+    dma_wait();
     __syncthreads();
 
-    f32x16 s0, s1;
-    bf16x8 pa[2], pb[2];      // probabilities of the two 32-token halves of a tile
-    int vprev = 0;            // V buffer of the previous tile
-    int vcur = 0;
-    for (int t = 0; t < n_full; ++t) {
-      const uint16_t* kt = lds_k + (t & 1) * kKTile;
-      const uint16_t* vt = lds_v + vcur * kVTile;
-      const int vnext = vcur == 2 ? 0 : vcur + 1;
-      // tile t+1 (fetched during the previous iteration) goes to the free buffers; fetch t+2
-      auto stage_next = [&]() {
-        if (t + 1 < n_full) {
-          uint16_t* kn = lds_k + ((t + 1) & 1) * kKTile;
-          uint16_t* vn = lds_v + vnext * kVTile;
-          *lds_chunk(kn, kKS, 0) = k0; *lds_chunk(kn, kKS, 1) = k1;
-          *lds_chunk(vn, kVS, 0) = v0; *lds_chunk(vn, kVS, 1) = v1;
-        }
-        if (t + 2 < n_full) {
-          k0 = *chunk_ptr(a.k, base_t2, 0); k1 = *chunk_ptr(a.k, base_t2, 1);
-          v0 = *chunk_ptr(a.v, base_t2, 0); v1 = *chunk_ptr(a.v, base_t2, 1);
-        }
-        if (t + 3 < n_full) base_t2 = full_base(t + 3);
-      };
-#if TL_STAGE_POS == 0
-      stage_next();
-#endif
-      if (group_b && t > 0) {
-        const uint16_t* vp = lds_v + vprev * kVTile;
-        TL_SETPRIO(1);
-        pv_block(vp, 0, pa);
-        pv_block(vp, 1, pb);
-        sched_pv_tile();
-        TL_SETPRIO(0);
-      }
-      TL_SETPRIO(1);
-      qk_tile(kt, s0, s1);
-      sched_qk_tile();
-      TL_SETPRIO(0);
-#if TL_STAGE_POS == 1
-      stage_next();
-#endif
-      // The exponent's reference point is set from the first tile; afterwards probabilities are
-      // computed optimistically against it and the (rare) tile whose row sum comes out above
-      // 2^32 -- scores far above the reference -- is redone with the reference raised first.
-      if (t == 0) maybe_rescale(s0, s1);
-      const float l_before = st.l_run;
-      exp_block(s0, pa);
-      exp_block(s1, pb);
-      if (__builtin_amdgcn_ballot_w64(!(st.l_run - l_before < kOptimisticLimit)) != 0) {
-        st.l_run = l_before;
-        qk_tile(kt, s0, s1);
-        maybe_rescale(s0, s1);
-        exp_block(s0, pa);
-        exp_block(s1, pb);
-      }
-#if TL_STAGE_POS == 2
-      stage_next();
-#endif
-      if (!group_b) {
-        TL_SETPRIO(1);
-        pv_block(vt, 0, pa);
-        pv_block(vt, 1, pb);
-        sched_pv_tile();
-        TL_SETPRIO(0);
-      }
-#if TL_STAGE_POS == 3
-      stage_next();
-#endif
-      __syncthreads();
-      vprev = vcur;
-      vcur = vnext;
+    f32x16 s0[kRG], s1[kRG];            // scores of block 0 / block 1 of a tile (then their probabilities)
+    bf16x8 p0[kRG][2], p1[kRG][2];      // packed probabilities
+    qk_block(lds_k, 0, s0);
+    float mc[kRG];
+#pragma unroll
+    for (int rg = 0; rg < kRG; ++rg) {
+      m_ref[rg] = xor32_max(max16(s0[rg]));   // reference: first block's row maximum
+      mc[rg] = m_ref[rg] * c;
+      p1[rg][0] = pack_bf16x8(0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f);
+      p1[rg][1] = p1[rg][0];
     }
-    if (group_b) {
-      const uint16_t* vp = lds_v + vprev * kVTile;
-      pv_block(vp, 0, pa);
-      pv_block(vp, 1, pb);
+
+    // operand group g of an iteration (0..31): step g / 16; even = K operand (head-dim step g%16 / 2),
+    // odd = V operand ((sp, d) = g%16 / 2).  Step 0: K(t, block 1), V(t-1, block 1); step 1:
+    // K(t+1, block 0), V(t, block 0).
+    auto operand = [&](int gq, const uint16_t* k_t, const uint16_t* k_n, const uint16_t* v_p, const uint16_t* v_t) -> bf16x8 {
+      const int step = gq >> 4, idx = (gq & 15) >> 1;
+      if ((gq & 1) == 0) return k_operand(step == 0 ? k_t : k_n, step == 0 ? 1 : 0, idx);
+      return v_operand(step == 0 ? v_p : v_t, step == 0 ? 1 : 0, idx >> 2, idx & 3);
+    };
+    bf16x8 ring[kDepth + 1];
+    {
+      const uint16_t* k_t = lds_k;
+      const uint16_t* k_n = lds_k + kKTile;
+      const uint16_t* v_p = lds_v + (kBufs - 1) * kVTile;
+      const uint16_t* v_t = lds_v;
+#pragma unroll
+      for (int gq = 0; gq < kDepth; ++gq) ring[gq] = operand(gq, k_t, k_n, v_p, v_t);
     }
+    __builtin_amdgcn_sched_barrier(0);
+
+    // first rows of the tiles that the coming iteration streams in, K(t+2) and V(t+1) (indices past
+    // the end are clamped: such a value is never used for a load)
+    int base_k = full_base(min(2, n_full - 1)), base_v = full_base(min(1, n_full - 1));
+    // one tile; kb = t % kBufs is a compile-time constant (the loop below is unrolled kBufs times),
+    // so that every LDS address is a loop-invariant per-lane register plus an immediate offset
+    auto tile_iteration = [&](auto KB, int t) {
+      constexpr int kb = decltype(KB)::value;
+      constexpr int kb1 = kb + 1 == kBufs ? 0 : kb + 1;
+      constexpr int km1 = kb == 0 ? kBufs - 1 : kb - 1;
+      constexpr int km2 = km1 == 0 ? kBufs - 1 : km1 - 1;
+      const uint16_t* k_t = lds_k + kb * kKTile;     // K(t), V(t)
+      const uint16_t* v_t = lds_v + kb * kVTile;
+      const uint16_t* k_n = lds_k + kb1 * kKTile;    // K(t+1), V(t+1)
+      const uint16_t* v_n = lds_v + kb1 * kVTile;
+      const uint16_t* v_p = lds_v + km1 * kVTile;    // V(t-1)
+      if (!CAUSAL && t > 0 && (t & (kIdxRing / 2 - 1)) == 0) ring_fill(t + kIdxRing / 2, kIdxRing / 2);
+      // K(t+2) replaces K(t-1), V(t+1) replaces V(t-2): both were last read before the previous barrier
+      if (t + 2 < n_full) dma_tile(a.k, base_k, lds_k + km1 * kKTile, dma_off_k);
+      if (t + 1 < n_full) dma_tile(a.v, base_v, lds_v + km2 * kVTile, dma_off_v);
+      int base_k_next = 0, base_k_next_v = 0;
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int gq = 0; gq < 32; ++gq) {
+        const int step = gq >> 4, gi = gq & 15, idx = gi >> 1;
+        // read early and made wave-uniform well before the next iteration's start needs it
+        if (gq == 6) base_k_next_v = full_base(min(t + 3, n_full - 1));
+        if (gq == 20) base_k_next = __builtin_amdgcn_readfirstlane(base_k_next_v);
+        // fetch ahead (the first groups of the next iteration read tiles that are already resident)
+        {
+          const int gp = gq + kDepth;
+          ring[gp % (kDepth + 1)] = gp < 32 ? operand(gp, k_t, k_n, v_p, v_t) : operand(gp - 32, k_n, k_n, v_t, v_n);
+        }
+        const bf16x8 x = ring[gq % (kDepth + 1)];
+        if ((gi & 1) == 0) {
+          const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int rg = 0; rg < kRG; ++rg) {
+            if (step == 0) s1[rg] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, qreg[rg][idx], idx == 0 ? zero : s1[rg], 0, 0, 0);
+            else s0[rg] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, qreg[rg][idx], idx == 0 ? zero : s0[rg], 0, 0, 0);
+          }
+        } else {
+          const int sp = idx >> 2, d = idx & 3;
+#pragma unroll
+          for (int rg = 0; rg < kRG; ++rg)
+            o[rg][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, step == 0 ? p1[rg][sp] : p0[rg][sp], o[rg][d], 0, 0, 0);
+        }
+        // probabilities of the block whose scores are complete: kRG elements per group
+#pragma unroll
+        for (int j = 0; j < kRG; ++j) {
+          const int e = gi * kRG + j, rg = e >> 4, r = e & 15;
+          f32x16& s = step == 0 ? s0[rg] : s1[rg];
+          s[r] = fast_exp2(fmaf(s[r], c, -mc[rg]));
+          if ((r & 7) == 7) {
+            const int r0 = r - 7;
+            const bf16x8 pk = pack_bf16x8(s[r0], s[r0 + 1], s[r0 + 2], s[r0 + 3], s[r0 + 4], s[r0 + 5], s[r0 + 6], s[r0 + 7]);
+            if (step == 0) p0[rg][r >> 3] = pk; else p1[rg][r >> 3] = pk;
+            l_run[rg] += ((s[r0] + s[r0 + 1]) + (s[r0 + 2] + s[r0 + 3])) + ((s[r0 + 4] + s[r0 + 5]) + (s[r0 + 6] + s[r0 + 7]));
+          }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      // this wave's share of K(t+2) / V(t+1) has landed; after the barrier everybody's has, and
+      // everybody is done reading K(t) block 1 and V(t-1), the buffers the next loads overwrite
+      dma_wait();
+      __builtin_amdgcn_s_barrier();
+      asm volatile("" ::: "memory");   // no memory access moves across the barrier at compile time
+      __builtin_amdgcn_sched_barrier(0);
+      base_v = base_k;
+      base_k = base_k_next;
+    };
+    {
+      int t = 0;
+      while (true) {
+        tile_iteration(std::integral_constant<int, 0>{}, t);
+        if (++t == n_full) break;
+        tile_iteration(std::integral_constant<int, 1>{}, t);
+        if (++t == n_full) break;
+        tile_iteration(std::integral_constant<int, 2>{}, t);
+        if (++t == n_full) break;
+      }
+    }
+    // drain: accumulate block 1 of the last tile
+    pv_block(lds_v + ((n_full - 1) % kBufs) * kVTile, 1, p1);
+
+    // did the fixed reference hold?  (row sums are sums of positive terms: one huge term shows)
+    bool bad = false;
+#pragma unroll
+    for (int rg = 0; rg < kRG; ++rg) bad = bad || !(l_run[rg] < kFastPathLimit);
+    if (__builtin_amdgcn_ballot_w64(bad) != 0 && lane == 0) *lds_flag = 1;
+    __syncthreads();
+    redo = *lds_flag != 0;
     __syncthreads();
   }
 
-  // ======================= pass 2: masked tiles, one at a time =======================
+  // ======================= careful redo of the full tiles (rare) =======================
+  if (redo) {
+    reset_state();
+    ring_fill(0, kIdxRing);
+    __syncthreads();
+    for (int t = 0; t < n_full; ++t) {
+      if (!CAUSAL && t > 0 && (t & (kIdxRing / 2 - 1)) == 0) ring_fill(t + kIdxRing / 2, kIdxRing / 2);
+      careful_tile(full_base(t), kKvTile);
+    }
+  }
+
+  // ======================= masked tiles, one at a time =======================
   for (int pt = 0; pt < n_part; ++pt) {
     int base, valid;
     if (CAUSAL) {
@@ -359,61 +511,28 @@ __global__ __launch_bounds__(kThreads) void row_tile_attn_kernel(const AttnArgs 
       base = a.part_tile[2 * (wk.part_off + pt)];
       valid = a.part_tile[2 * (wk.part_off + pt) + 1];
     }
-    {
-      // rows beyond `valid` are written as zero: 0 * garbage cannot make NaN
-      const uint4 z = make_uint4(0, 0, 0, 0);
-      const uint4 k0 = c_tr < valid ? *chunk_ptr(a.k, base, 0) : z;
-      const uint4 k1 = c_tr + 32 < valid ? *chunk_ptr(a.k, base, 1) : z;
-      const uint4 v0 = c_tr < valid ? *chunk_ptr(a.v, base, 0) : z;
-      const uint4 v1 = c_tr + 32 < valid ? *chunk_ptr(a.v, base, 1) : z;
-      *lds_chunk(lds_k, kKS, 0) = k0; *lds_chunk(lds_k, kKS, 1) = k1;
-      *lds_chunk(lds_v, kVS, 0) = v0; *lds_chunk(lds_v, kVS, 1) = v1;
-    }
-    __syncthreads();
-#pragma unroll 1
-    for (int hb = 0; hb < 2; ++hb) {
-      if (32 * hb >= valid) break;              // uniform
-      f32x16 s;
-      qk_block(lds_k, hb, s);
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int kv = 32 * hb + 8 * (r >> 2) + 4 * h + (r & 3);
-        bool hide = kv >= valid;
-        if (CAUSAL) hide = hide || (base + kv > token);
-        if (hide) s[r] = -INFINITY;
-      }
-      maybe_rescale(s, s);
-      bf16x8 pb[2];
-      if (st.m_ref == -INFINITY) {
-        // every key so far is hidden from this row: probabilities are zero
-#pragma unroll
-        for (int r = 0; r < 16; ++r) s[r] = 0.f;
-        pb[0] = pack_bf16x8(0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f);
-        pb[1] = pb[0];
-      } else {
-        exp_block(s, pb);
-      }
-      pv_block(lds_v, hb, pb);
-    }
-    __syncthreads();
+    careful_tile(base, valid);
   }
 
   // ---- epilogue: normalise, LSE, store ----
-  const float l_tot = xor32_sum(st.l_run);
-  if (row_ok) {
-    const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
-    const int head = g * G + j;
-    const size_t orow = (size_t)(wk.out_row + tok_local) * a.q_heads + head;
-    float* op = a.out + orow * kHeadDim;
 #pragma unroll
-    for (int d = 0; d < 4; ++d)
+  for (int rg = 0; rg < kRG; ++rg) {
+    const float l_tot = xor32_sum(l_run[rg]);
+    if (row_ok[rg]) {
+      const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+      const int head = g * G + head_j[rg];
+      const size_t orow = (size_t)(wk.out_row + tok_local[rg]) * a.q_heads + head;
+      float* op = a.out + orow * kHeadDim;
 #pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4) {
-        float4 val = make_float4(st.o[d][4 * q4 + 0] * inv, st.o[d][4 * q4 + 1] * inv, st.o[d][4 * q4 + 2] * inv,
-                                 st.o[d][4 * q4 + 3] * inv);
-        *(float4*)&op[32 * d + 8 * q4 + 4 * h] = val;
-      }
-    if (h == 0) a.lse[orow] = l_tot > 0.f ? st.m_ref * a.scale + __logf(l_tot) : -INFINITY;
+      for (int d = 0; d < 4; ++d)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          float4 val = make_float4(o[rg][d][4 * q4 + 0] * inv, o[rg][d][4 * q4 + 1] * inv, o[rg][d][4 * q4 + 2] * inv,
+                                   o[rg][d][4 * q4 + 3] * inv);
+          *(float4*)&op[32 * d + 8 * q4 + 4 * h] = val;
+        }
+      if (h == 0) a.lse[orow] = l_tot > 0.f ? m_ref[rg] * a.scale + __logf(l_tot) : -INFINITY;
+    }
   }
 }
 

@@ -108,6 +108,8 @@ class Batch:
     head_dim: int = HEAD_DIM
     k_gain: float = 1.0                # power of two; >1 makes the softmax peaked
     v_offset_mod: int = 0              # >0: V of segment id s gets the integer offset (s % mod) - mod//2
+    k_boost: tuple = ()                # (lo, hi, gain): K of segments at list positions lo <= p < hi (the low
+                                       # 32 bits of the id) is multiplied by the power of two `gain`
     self_block: bool = True
     row_base: int = 0                  # first element index of this batch in the Q/Knew/Vnew streams
     notes: str = ""
@@ -167,6 +169,11 @@ class Batch:
         v = normal_bf16(self.seed, STREAM_POOL_V, idx).view(shape)
         if self.k_gain != 1.0:
             k = k * self.k_gain
+        if self.k_boost:
+            lo, hi, gain = self.k_boost
+            pos = ids_t & 0xFFFFFFFF
+            boosted = ((pos >= lo) & (pos < hi))[:, None, None, None]
+            k = torch.where(boosted, k * gain, k)
         if self.v_offset_mod > 0:
             off = (ids_t % self.v_offset_mod - self.v_offset_mod // 2).to(torch.float32)
             v = (v.to(torch.float32) + off[:, None, None, None]).to(torch.bfloat16)

@@ -186,12 +186,28 @@ def test_peaked_and_offset_variants_are_discriminating():
     _say("peaked / offset variants")
     for maker, kw in [(wl.prefill, dict(n_req=3, new_tokens=100, lo=300, hi=900, seg_len=128, n_slots=64, n_shared=2)),
                       (wl.decode, dict(n_req=6, median=700, cap=3000, seg_len=128))]:
-        b = maker(seed=21, k_gain=4.0, v_offset_mod=7, **kw)
+        b = maker(seed=21, k_gain=4.0, v_offset_mod=3, **kw)
         run = H.run_gpu(b)
         w = _check_all_requests(run)
         # on these inputs |O| is O(1): an all-zero or segment-dropping result cannot pass 2e-2
         ref = max(H.compare_rows(run, r)["ref_o"] for r in range(b.n_req))
         assert ref > 0.5
+        run.close()
+
+
+def test_scores_far_from_the_first_blocks_range():
+    """The row-tile kernel fixes the exponent's reference point from the first 32 keys of a work
+    item and must fall back to its running-maximum path when later scores exceed it by more than
+    fp32 can hold (here: keys 32x larger from the third segment on, i.e. scaled scores ~100
+    above the first block's), and must stay exact when the first keys dwarf all later ones."""
+    _say("late / early score peaks")
+    for boost in [(2, 1 << 30, 32.0), (0, 1, 32.0), (3, 4, 32.0)]:
+        b = wl.prefill(seed=23, n_req=2, new_tokens=96, lo=700, hi=1100, seg_len=128, n_slots=32, n_shared=1,
+                       k_boost=boost, v_offset_mod=3)
+        run = H.run_gpu(b)
+        assert run.info.n_tiles > 0
+        w = _check_all_requests(run)
+        assert max(H.compare_rows(run, r)["ref_o"] for r in range(b.n_req)) > 0.5
         run.close()
 
 
