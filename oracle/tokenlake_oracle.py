@@ -38,6 +38,7 @@ __all__ = [
     "bf16_bits_to_f64",
     "SlotTable",
     "gather_segments",
+    "append_rows",
     "attention_rows",
     "partial_attention",
     "merge_partials",
@@ -106,6 +107,49 @@ class SlotTable:
     def fill(self, slots) -> np.ndarray:
         return self._fill[np.asarray(slots, dtype=np.int64)]
 
+    def append(self, tail_id, new_ids, n_rows: int):
+        """Placement of n_rows new token rows at the end of a chain of segments (paper Section
+        3.2: the KV of new tokens is `put` into the pool, so that later turns find it as prefix).
+
+        The rows go, in order, first to the slot of `tail_id` from its current fill up to
+        seg_len (tail_id None: there is no partly filled tail), then to new segments
+        `new_ids` in order, seg_len rows each, the last one possibly partly filled.  Each new
+        id takes the lowest-numbered free slot at the moment it is created.  `new_ids` must
+        be exactly as many ids as the rows need.  Returns [(slot, first_token, n_tokens,
+        first_row), ...]; nothing changes if an argument is invalid.
+        """
+        n_rows = int(n_rows)
+        if n_rows < 0:
+            raise ValueError("negative row count")
+        new_ids = [int(x) for x in new_ids]
+        room = 0
+        if tail_id is not None:
+            tail_id = int(tail_id)
+            if tail_id not in self._slot_of:
+                raise KeyError("tail segment not in the pool")
+            room = self.seg_len - int(self._fill[self._slot_of[tail_id]])
+        rest = max(0, n_rows - room)
+        need = -(-rest // self.seg_len)
+        if len(new_ids) != need:
+            raise ValueError("need exactly %d new ids, got %d" % (need, len(new_ids)))
+        if len(set(new_ids)) != len(new_ids) or any(i in self._slot_of for i in new_ids):
+            raise ValueError("new id repeated or already in the pool")
+        if int((~self._used).sum()) < need:
+            raise MemoryError("pool full")
+        out, row = [], 0
+        if tail_id is not None and n_rows > 0 and room > 0:
+            slot = self._slot_of[tail_id]
+            n = min(room, n_rows)
+            out.append((slot, int(self._fill[slot]), n, 0))
+            self._fill[slot] += n
+            row = n
+        for sid in new_ids:
+            n = min(self.seg_len, n_rows - row)
+            slot = self.put(sid, n)
+            out.append((slot, 0, n, row))
+            row += n
+        return out
+
 
 def gather_segments(pool_k_bits, pool_v_bits, slots, fills):
     """Concatenate, in list order, the valid tokens of the listed slots.
@@ -128,6 +172,19 @@ def gather_segments(pool_k_bits, pool_v_bits, slots, fills):
         shp = (0,) + tuple(pool_k_bits.shape[2:])
         return np.zeros(shp, np.uint16), np.zeros(shp, np.uint16)
     return np.concatenate(ks, axis=0), np.concatenate(vs, axis=0)
+
+
+def append_rows(pool_k_bits, pool_v_bits, table: SlotTable, tail_id, new_ids, k_rows_bits, v_rows_bits):
+    """Store new token rows [n, kv_heads, head_dim] (bf16 bit patterns) at the end of a chain
+    of segments: `table.append` decides where each row goes, the rows are copied there.
+    Returns the placement list of `table.append`."""
+    if k_rows_bits.shape != v_rows_bits.shape or k_rows_bits.shape[1:] != pool_k_bits.shape[2:]:
+        raise ValueError("row shape mismatch")
+    placement = table.append(tail_id, new_ids, k_rows_bits.shape[0])
+    for slot, tok, n, row in placement:
+        pool_k_bits[slot, tok:tok + n] = k_rows_bits[row:row + n]
+        pool_v_bits[slot, tok:tok + n] = v_rows_bits[row:row + n]
+    return placement
 
 
 # --------------------------------------------------------------------------------------

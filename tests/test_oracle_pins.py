@@ -330,3 +330,63 @@ def test_duplicate_slot_counts_twice():
     o1, l1 = orc.request_attention(qb, pk, pv, slots, fills, None, None, 0.3)
     o2, l2 = orc.request_attention(qb, pk, pv, list(slots) * 2, list(fills) * 2, None, None, 0.3)
     assert np.allclose(o1, o2, atol=1e-12) and np.allclose(l2, l1 + math.log(2.0), atol=1e-12)
+
+
+def test_append_chain_equals_concatenation_of_rows():
+    """Pin for SlotTable.append / append_rows: whatever the sizes of the appends, reading a
+    chain's segments back in order gives exactly the rows that were appended, in order; every
+    segment but the last is full; new segments take the lowest free slot; a refused call
+    changes nothing.  (The check keeps its own per-chain list of rows and never looks at the
+    placement arithmetic.)"""
+    rng = np.random.default_rng(5)
+    n_slots, C, hkv, d = 24, 8, 2, 4
+    pk = np.zeros((n_slots, C, hkv, d), np.uint16)
+    pv = np.zeros_like(pk)
+    table = orc.SlotTable(n_slots, C)
+    table.put(1000, C, want_slot=0)          # two unrelated residents, so that slot choice is visible
+    table.put(1001, 3, want_slot=2)
+    chains = {c: {"ids": [], "rows_k": [], "rows_v": []} for c in range(3)}
+    next_id = 1
+    for step in range(40):
+        c = int(rng.integers(0, 3))
+        ch = chains[c]
+        n = int(rng.integers(0, 2 * C + 3))
+        k = rng.integers(0, 1 << 16, size=(n, hkv, d), dtype=np.uint16)
+        v = rng.integers(0, 1 << 16, size=(n, hkv, d), dtype=np.uint16)
+        total = sum(len(x) for x in ch["rows_k"])
+        tail = ch["ids"][-1] if ch["ids"] and total % C else None
+        room = (C - total % C) if tail is not None else 0
+        need = -(-max(0, n - room) // C)
+        used_before = set(np.flatnonzero(table._used).tolist())
+        if used_before.__len__() + need > n_slots:
+            with pytest.raises(MemoryError):
+                orc.append_rows(pk, pv, table, tail, [10 ** 6 + i for i in range(need)], k, v)
+            assert set(np.flatnonzero(table._used).tolist()) == used_before
+            continue
+        if need and step % 7 == 0:            # wrong id count: refused, nothing changes
+            fills_before = table._fill.copy()
+            with pytest.raises(ValueError):
+                orc.append_rows(pk, pv, table, tail, list(range(next_id, next_id + need + 1)), k, v)
+            assert np.array_equal(table._fill, fills_before)
+        ids = list(range(next_id, next_id + need))
+        next_id += need
+        placement = orc.append_rows(pk, pv, table, tail, ids, k, v)
+        new_slots = [p[0] for p in placement if p[0] not in used_before]
+        free_sorted = sorted(set(range(n_slots)) - used_before)
+        assert new_slots == free_sorted[:len(new_slots)]          # lowest free slots, in order
+        ch["ids"] += ids
+        ch["rows_k"].append(k)
+        ch["rows_v"].append(v)
+        for cc in chains.values():                                    # every chain, after every step
+            if not cc["ids"]:
+                continue
+            slots = table.lookup(cc["ids"])
+            assert (slots >= 0).all() and len(set(slots.tolist())) == len(slots)
+            fills = table.fill(slots)
+            assert (fills[:-1] == C).all() and 1 <= fills[-1] <= C
+            gk, gv = orc.gather_segments(pk, pv, slots, fills)
+            assert np.array_equal(gk, np.concatenate(cc["rows_k"], axis=0))
+            assert np.array_equal(gv, np.concatenate(cc["rows_v"], axis=0))
+    assert sum(len(c["ids"]) for c in chains.values()) > 10
+    # the unrelated residents were never touched
+    assert table.lookup([1000, 1001]).tolist() == [0, 2] and table.fill([0, 2]).tolist() == [C, 3]
