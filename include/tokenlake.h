@@ -75,6 +75,22 @@ tl_status tl_pool_destroy(tl_pool* pool);
 tl_status tl_pool_put(tl_pool* pool, uint64_t segment_id, const void* k_src_dev, const void* v_src_dev,
                       int32_t fill, int32_t want_slot, int32_t* slot_out, void* stream);
 
+/* Append the K/V of n_rows new tokens to a chain of private segments (Section 3.2: the KV of
+ * the tokens just computed is `put` into the pool and is prefix cache for the next turn).
+ * Rows go, in order, first into the slot of tail_id from its current fill up to seg_len
+ * (has_tail = 0: the chain has no partly filled tail, tail_id is ignored), then into new
+ * segments new_ids[0..n_new) in order, seg_len rows each, the last possibly partly filled
+ * (its remaining tokens are zeroed).  Each new id takes the lowest-numbered free slot.
+ * k_rows_dev/v_rows_dev: device, [n_rows, kv_heads, head_dim] bf16.  new_ids: host [n_new];
+ * n_new must be exactly ceil(max(0, n_rows - room in the tail) / seg_len).
+ * new_slots_out: host [n_new] or NULL.  One kernel launch per 48 destination slots.
+ * The tail must hold exactly one reference (a segment somebody else also uses does not grow).
+ * Nothing is written or registered on error: TL_ENOTFOUND (tail not resident), TL_EINVAL
+ * (tail shared, wrong n_new, id repeated or already resident), TL_EFULL. */
+tl_status tl_pool_append(tl_pool* pool, int32_t has_tail, uint64_t tail_id, const uint64_t* new_ids, int32_t n_new,
+                         const void* k_rows_dev, const void* v_rows_dev, int32_t n_rows, int32_t* new_slots_out,
+                         void* stream);
+
 /* Register segments whose KV the caller has already written into the pool memory
  * (no copy; the slots' tails are left as they are).  ids/slots/fills: host, [n].
  * Same id twice or slot taken -> TL_EINVAL, nothing is registered. */

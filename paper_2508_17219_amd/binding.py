@@ -43,6 +43,7 @@ _SIGNATURES = {
     "tl_pool_create": (_I32, [C.POINTER(_P), _I32, _I32, _I32, _I32, _P, _P]),
     "tl_pool_destroy": (_I32, [_P]),
     "tl_pool_put": (_I32, [_P, _U64, _P, _P, _I32, _I32, C.POINTER(_I32), _P]),
+    "tl_pool_append": (_I32, [_P, _I32, _U64, _P, _I32, _P, _P, _I32, _P, _P]),
     "tl_pool_adopt": (_I32, [_P, _P, _P, _P, _I32, _P]),
     "tl_pool_release": (_I32, [_P, _U64]),
     "tl_pool_evict_lru": (_I32, [_P, C.POINTER(_U64)]),
@@ -123,6 +124,16 @@ def tl_pool_put(pool: int, segment_id: int, k_src, v_src, fill: int, want_slot: 
     _check(load_library().tl_pool_put(pool, segment_id, _dev(k_src), _dev(v_src), fill, want_slot, C.byref(slot),
                                       _stream(stream)))
     return slot.value
+
+
+def tl_pool_append(pool: int, tail_id, new_ids, k_rows, v_rows, n_rows: int, stream=None) -> np.ndarray:
+    """tail_id None = no partly filled tail.  Returns the slots given to new_ids."""
+    ids = _host(new_ids, np.uint64)
+    slots = np.full(len(ids), -1, np.int32)
+    _check(load_library().tl_pool_append(pool, 0 if tail_id is None else 1, 0 if tail_id is None else int(tail_id),
+                                         ids.ctypes.data if len(ids) else None, len(ids), _dev(k_rows), _dev(v_rows),
+                                         n_rows, slots.ctypes.data if len(ids) else None, _stream(stream)))
+    return slots
 
 
 def tl_pool_adopt(pool: int, ids, slots, fills, stream=None):

@@ -50,6 +50,39 @@ __global__ void gather_slots_kernel(uint4* __restrict__ out, const uint4* __rest
     dst[i] = src[i];
 }
 
+// Destination chunks of one append launch: rows [src_row, src_row + n) of the source go to
+// tokens [tok, tok + n) of `slot`; `zero_to` > tok + n asks for tokens [tok + n, zero_to) to be
+// cleared; new_fill is stored in fill[slot].
+struct AppendChunk {
+  int32_t slot, tok, n, src_row, zero_to, new_fill;
+};
+constexpr int kAppendChunks = 48;
+struct AppendArgs {
+  AppendChunk c[kAppendChunks];
+};
+
+// blockIdx.y = chunk; the blocks of a column stride over the chunk's 16-byte pieces.
+__global__ void append_rows_kernel(uint4* __restrict__ pool_k, uint4* __restrict__ pool_v,
+                                   const uint4* __restrict__ src_k, const uint4* __restrict__ src_v,
+                                   int32_t* __restrict__ fill, const AppendArgs args, size_t row16, size_t slot16) {
+  const AppendChunk c = args.c[blockIdx.y];
+  const size_t dst0 = (size_t)c.slot * slot16 + (size_t)c.tok * row16;
+  const size_t src0 = (size_t)c.src_row * row16;
+  const size_t n16 = (size_t)c.n * row16;
+  const size_t z16 = c.zero_to > c.tok + c.n ? (size_t)(c.zero_to - c.tok - c.n) * row16 : 0;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) {
+    pool_k[dst0 + i] = src_k[src0 + i];
+    pool_v[dst0 + i] = src_v[src0 + i];
+  }
+  const uint4 z = make_uint4(0, 0, 0, 0);
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < z16; i += stride) {
+    pool_k[dst0 + n16 + i] = z;
+    pool_v[dst0 + n16 + i] = z;
+  }
+  if (blockIdx.x == 0 && threadIdx.x == 0) fill[c.slot] = c.new_fill;
+}
+
 static int blocks_for(size_t n16) {
   size_t b = (n16 + 255) / 256;
   if (b > 4096) b = 4096;
@@ -214,6 +247,72 @@ tl_status tl_pool_put(tl_pool* pool, uint64_t segment_id, const void* k_src_dev,
   TL_HIP(hipGetLastError());
   occupy(pool, s, segment_id, fill);
   if (slot_out) *slot_out = s;
+  return TL_OK;
+}
+
+tl_status tl_pool_append(tl_pool* pool, int32_t has_tail, uint64_t tail_id, const uint64_t* new_ids, int32_t n_new,
+                         const void* k_rows_dev, const void* v_rows_dev, int32_t n_rows, int32_t* new_slots_out,
+                         void* stream) {
+  if (!pool || n_rows < 0 || n_new < 0 || (n_new > 0 && !new_ids)) TL_FAIL(TL_EINVAL, "tl_pool_append: bad argument");
+  if (n_rows > 0 && (!k_rows_dev || !v_rows_dev)) TL_FAIL(TL_EINVAL, "tl_pool_append: null source");
+  const int32_t C = pool->seg_len;
+  // ---- validate everything first ----
+  int32_t tail_slot = -1, room = 0;
+  if (has_tail) {
+    auto it = pool->slot_of.find(tail_id);
+    if (it == pool->slot_of.end()) TL_FAIL(TL_ENOTFOUND, "tl_pool_append: tail id %llu not resident", (unsigned long long)tail_id);
+    tail_slot = it->second;
+    if (pool->refcnt[tail_slot] != 1)
+      TL_FAIL(TL_EINVAL, "tl_pool_append: tail id %llu has %d references, a shared segment does not grow",
+              (unsigned long long)tail_id, pool->refcnt[tail_slot]);
+    room = C - pool->fill[tail_slot];
+  }
+  const int32_t rest = n_rows > room ? n_rows - room : 0;
+  const int32_t need = (rest + C - 1) / C;
+  if (n_new != need) TL_FAIL(TL_EINVAL, "tl_pool_append: %d rows need exactly %d new segments, %d given", n_rows, need, n_new);
+  {
+    std::unordered_map<uint64_t, int> seen;
+    for (int32_t i = 0; i < n_new; ++i) {
+      if (pool->slot_of.count(new_ids[i])) TL_FAIL(TL_EINVAL, "tl_pool_append: id %llu already resident", (unsigned long long)new_ids[i]);
+      if (!seen.emplace(new_ids[i], i).second) TL_FAIL(TL_EINVAL, "tl_pool_append: id %llu listed twice", (unsigned long long)new_ids[i]);
+    }
+  }
+  if (pool->n_slots - pool->n_used < need) TL_FAIL(TL_EFULL, "tl_pool_append: %d free slots, %d needed", pool->n_slots - pool->n_used, need);
+  if (n_rows == 0) return TL_OK;
+  hipStream_t st = (hipStream_t)stream;
+  tl_status rc = pool_device_ready(pool, st);
+  if (rc != TL_OK) return rc;
+
+  // ---- place the rows (host state changes from here on; no failure path below but HIP's) ----
+  std::vector<AppendChunk> chunks;
+  int32_t row = 0;
+  if (has_tail && room > 0) {
+    const int32_t n = n_rows < room ? n_rows : room;
+    chunks.push_back(AppendChunk{tail_slot, pool->fill[tail_slot], n, 0, 0, pool->fill[tail_slot] + n});
+    pool->fill[tail_slot] += n;
+    pool->stamp[tail_slot] = ++pool->clock;
+    row = n;
+  }
+  for (int32_t i = 0; i < n_new; ++i) {
+    const int32_t n = n_rows - row < C ? n_rows - row : C;
+    const int32_t s = take_slot(pool, -1);
+    occupy(pool, s, new_ids[i], n);
+    chunks.push_back(AppendChunk{s, 0, n, row, C, n});
+    if (new_slots_out) new_slots_out[i] = s;
+    row += n;
+  }
+  const size_t row16 = (size_t)pool->kv_heads * pool->head_dim * 2 / 16;
+  const size_t slot16 = row16 * C;
+  for (size_t c0 = 0; c0 < chunks.size(); c0 += kAppendChunks) {
+    const size_t nc = chunks.size() - c0 < (size_t)kAppendChunks ? chunks.size() - c0 : (size_t)kAppendChunks;
+    AppendArgs args;
+    memset(&args, 0, sizeof(args));
+    for (size_t i = 0; i < nc; ++i) args.c[i] = chunks[c0 + i];
+    const unsigned bx = (unsigned)(slot16 / 256 > 32 ? 32 : (slot16 + 255) / 256);
+    hipLaunchKernelGGL(append_rows_kernel, dim3(bx, (unsigned)nc), dim3(256), 0, st, (uint4*)pool->k_dev, (uint4*)pool->v_dev,
+                       (const uint4*)k_rows_dev, (const uint4*)v_rows_dev, pool->fill_dev, args, row16, slot16);
+  }
+  TL_HIP(hipGetLastError());
   return TL_OK;
 }
 

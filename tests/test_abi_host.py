@@ -187,3 +187,38 @@ def test_plan_errors():
     with pytest.raises(B.TokenLakeError):
         B.tl_set_option("no-such-knob", 1)
     B.tl_pool_destroy(pool)
+
+
+def test_append_refuses_bad_calls_without_changing_anything():
+    """Validation of tl_pool_append happens before any device work, so it can be exercised with
+    pointers that are never dereferenced."""
+    pool = B.tl_pool_create(4, 64, 1, 128, FAKE_K, FAKE_V)
+    B.tl_pool_adopt(pool, [10, 11], [0, 1], [64, 20])
+
+    def state():
+        return (B.tl_pool_used(pool), B.tl_pool_lookup(pool, [10, 11, 12, 13]).tolist(), B.tl_pool_fills(pool, [0, 1, 2, 3]).tolist())
+
+    before = state()
+    cases = [
+        (dict(tail_id=99, new_ids=[], n_rows=5), B.TL_ENOTFOUND),          # unknown tail
+        (dict(tail_id=11, new_ids=[12], n_rows=44), B.TL_EINVAL),          # 44 rows fit the tail's room exactly
+        (dict(tail_id=11, new_ids=[], n_rows=45), B.TL_EINVAL),            # one row too many for no new id
+        (dict(tail_id=None, new_ids=[], n_rows=1), B.TL_EINVAL),           # no tail: needs one new id
+        (dict(tail_id=11, new_ids=[10], n_rows=50), B.TL_EINVAL),          # id already resident
+        (dict(tail_id=None, new_ids=[12, 12], n_rows=100), B.TL_EINVAL),   # id listed twice
+        (dict(tail_id=None, new_ids=[12, 13, 14], n_rows=130), B.TL_EFULL),  # 3 slots needed, 2 free
+    ]
+    for kw, status in cases:
+        with pytest.raises(B.TokenLakeError) as e:
+            B.tl_pool_append(pool, kw["tail_id"], kw["new_ids"], FAKE_K, FAKE_V, kw["n_rows"])
+        assert e.value.status == status, (kw, e.value)
+        assert state() == before
+    # a tail that somebody else references too does not grow
+    assert B.tl_pool_put(pool, 11, FAKE_K, FAKE_V, 20) == 1                 # second reference, no copy
+    with pytest.raises(B.TokenLakeError) as e:
+        B.tl_pool_append(pool, 11, [], FAKE_K, FAKE_V, 3)
+    assert e.value.status == B.TL_EINVAL and state() == before
+    # nothing to append is fine and does nothing
+    B.tl_pool_append(pool, None, [], None, None, 0)
+    assert state() == before
+    B.tl_pool_destroy(pool)

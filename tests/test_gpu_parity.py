@@ -326,3 +326,115 @@ def test_full_multiturn_config_sampled(turn):
     run = H.run_gpu(b)
     _check_all_requests(run, rows_per_req=5, seed=4, reqs=[0, 37, 63])
     run.close()
+
+
+def test_append_rows_grow_chains_like_the_oracle():
+    """tl_pool_append against the oracle's append: same slots, same fills, same bytes in the
+    pool after every call (bit-exact), and attention over the grown chains within tolerance.
+    Rows come from the seeded generator on both sides; the oracle keeps its own numpy pool."""
+    _say("append path")
+    seed, hq, hkv, C, n_slots, d = 31, 8, 2, 128, 24, 128
+    dev = "cuda"
+    rng = np.random.default_rng(seed)
+    pk = torch.full((n_slots, C, hkv, d), float("nan"), dtype=torch.bfloat16, device=dev)
+    pv = torch.full((n_slots, C, hkv, d), float("nan"), dtype=torch.bfloat16, device=dev)
+    pool = B.tl_pool_create(n_slots, C, hkv, d, pk, pv)
+    opk = np.zeros((n_slots, C, hkv, d), np.uint16)
+    opv = np.zeros_like(opk)
+    table = orc.SlotTable(n_slots, C)
+    cursor = [0]
+
+    def rows(n):                      # n token rows of K and of V, same bits on both devices
+        per = hkv * d
+        out = []
+        for stream in (wl.STREAM_KNEW, wl.STREAM_VNEW):
+            g = wl.normal_bf16_range(seed, stream, cursor[0] * per, n * per, dev).view(n, hkv, d)
+            c = wl.normal_bf16_range(seed, stream, cursor[0] * per, n * per, "cpu").view(n, hkv, d)
+            out += [g, wl.bits_u16(c)]
+        cursor[0] += n
+        return out
+
+    # two shared, full segments stored with put
+    shared = [7, 8]
+    for sid in shared:
+        kg, kc, vg, vc = rows(C)
+        s_lib = B.tl_pool_put(pool, sid, kg, vg, C)
+        s_orc = table.put(sid, C)
+        assert s_lib == s_orc
+        opk[s_orc], opv[s_orc] = kc, vc
+    chains = {c: [] for c in range(3)}
+    totals = {c: 0 for c in range(3)}
+    next_id = 100
+    for step in range(14):
+        c = step % 3
+        n = int(rng.integers(1, 2 * C + 40))
+        tail = chains[c][-1] if chains[c] and totals[c] % C else None
+        room = C - totals[c] % C if tail is not None else 0
+        need = -(-max(0, n - room) // C)
+        if B.tl_pool_used(pool) + need > n_slots:
+            with pytest.raises(B.TokenLakeError) as e:
+                B.tl_pool_append(pool, tail, list(range(next_id, next_id + need)), pk[0], pv[0], n)
+            assert e.value.status == B.TL_EFULL
+            continue
+        ids = list(range(next_id, next_id + need))
+        next_id += need
+        if need and step % 4 == 1:     # wrong id count is refused and changes nothing
+            with pytest.raises(B.TokenLakeError) as e:
+                B.tl_pool_append(pool, tail, ids + [next_id], pk[0], pv[0], n)
+            assert e.value.status == B.TL_EINVAL
+        kg, kc, vg, vc = rows(n)
+        new_slots = B.tl_pool_append(pool, tail, ids, kg, vg, n)
+        placement = orc.append_rows(opk, opv, table, tail, ids, kc, vc)
+        assert new_slots.tolist() == table.lookup(ids).tolist()
+        chains[c] += ids
+        totals[c] += n
+        every = shared + [i for ch in chains.values() for i in ch]
+        assert np.array_equal(B.tl_pool_lookup(pool, every), table.lookup(every))
+        slots = table.lookup(every)
+        assert np.array_equal(B.tl_pool_fills(pool, slots), table.fill(slots))
+    assert sum(len(ch) for ch in chains.values()) >= 8
+    # bytes: every valid token of every resident segment; tokens beyond the fill of a slot
+    # that append created are zero
+    every = shared + [i for ch in chains.values() for i in ch]
+    slots = table.lookup(every)
+    gk = torch.empty((len(slots), C, hkv, d), dtype=torch.bfloat16, device=dev)
+    gv = torch.empty_like(gk)
+    B.tl_pool_gather(pool, slots, gk, gv)
+    torch.cuda.synchronize()
+    gkb, gvb = wl.bits_u16(gk), wl.bits_u16(gv)
+    for i, (s, f) in enumerate(zip(slots, table.fill(slots))):
+        assert np.array_equal(gkb[i, :f], opk[s, :f]) and np.array_equal(gvb[i, :f], opv[s, :f]), "slot %d" % s
+        if every[i] >= 100:
+            assert not gkb[i, f:].any() and not gvb[i, f:].any()
+    # attention of one request per chain over shared + chain segments, plus the self block
+    lq = 40
+    req_ids = [shared + chains[c] for c in range(3)]
+    seg_ptr = np.concatenate([[0], np.cumsum([len(x) for x in req_ids])]).astype(np.int32)
+    row_ptr = (np.arange(4) * lq).astype(np.int32)
+    plan = B.tl_plan_create(pool, hq, row_ptr, seg_ptr, np.array([i for x in req_ids for i in x], np.uint64))
+    info = B.tl_plan_get_info(plan)
+    T = 3 * lq
+    qg = wl.normal_bf16_range(seed, wl.STREAM_Q, 0, T * hq * d, dev).view(T, hq, d)
+    qc = wl.bits_u16(wl.normal_bf16_range(seed, wl.STREAM_Q, 0, T * hq * d, "cpu").view(T, hq, d))
+    kng, knc, vng, vnc = rows(T)
+    outp = torch.full((info.n_partial_rows, hq, d), float("nan"), dtype=torch.float32, device=dev)
+    lsep = torch.full((info.n_partial_rows, hq), float("nan"), dtype=torch.float32, device=dev)
+    out = torch.full((T, hq, d), float("nan"), dtype=torch.float32, device=dev)
+    lse = torch.full((T, hq), float("nan"), dtype=torch.float32, device=dev)
+    scale = 1.0 / math.sqrt(d)
+    B.tl_segment_attn(pool, plan, qg, scale, outp, lsep)
+    B.tl_causal_block(plan, qg, kng, vng, scale, outp, lsep)
+    B.tl_merge(plan, outp, lsep, out, False, lse)
+    torch.cuda.synchronize()
+    for r in range(3):
+        sl = table.lookup(req_ids[r])
+        gk_, gv_ = orc.gather_segments(opk, opv, sl, table.fill(sl))
+        t0 = r * lq
+        k_all = np.concatenate([gk_, knc[t0:t0 + lq]], axis=0)
+        v_all = np.concatenate([gv_, vnc[t0:t0 + lq]], axis=0)
+        want_o, want_l = orc.partial_attention(qc[t0:t0 + lq], k_all, v_all, scale, n_visible=gk_.shape[0] + np.arange(lq) + 1)
+        got_o = out[t0:t0 + lq].double().cpu().numpy()
+        got_l = lse[t0:t0 + lq].double().cpu().numpy()
+        assert np.abs(got_o - want_o).max() <= H.TOL_O and np.abs(got_l - want_l).max() <= H.TOL_LSE
+    B.tl_plan_destroy(plan)
+    B.tl_pool_destroy(pool)
