@@ -213,6 +213,28 @@ tl_status tl_merge(tl_plan* plan, const float* out_partial, const float* lse, vo
  * for an unknown knob.  Knobs: "vread" (0 = transposing LDS reads, 1 = scalar LDS reads). */
 tl_status tl_set_option(const char* knob, int32_t value);
 
+/* ------------------------------------------------------------------------------------
+ * Analytic models (host arithmetic, no GPU work).  Units: seconds, bytes, flop/s, bytes/s,
+ * tokens; 16-bit elements as in the paper.  d_q = q_heads * head_dim (flops and the query /
+ * partial-output rows on the wire follow it), d_kv = kv_heads * head_dim (KV bytes follow it);
+ * the paper's multi-head model has d_q = d_kv = d.  TL_EINVAL for non-positive sizes or rates,
+ * negative latency or time, null outputs.
+ * ------------------------------------------------------------------------------------ */
+/* Section 4.1: T_comp = n_tokens * max(4 d_q / flops, 4 d_kv / mem_bw). */
+tl_status tl_model_segment_time(double n_tokens, double d_q, double d_kv, double flops, double mem_bw,
+                                double* seconds_out);
+/* Section 4.1: T_comm = 2 * net_latency + 4 d_q / net_bw (query row out, partial row back). */
+tl_status tl_model_comm_time(double d_q, double net_latency, double net_bw, double* seconds_out);
+/* Section 4.1: the segment size (tokens, real-valued) from which T_comp >= T_comm. */
+tl_status tl_model_segment_threshold(double d_q, double d_kv, double flops, double mem_bw, double net_latency,
+                                     double net_bw, double* tokens_out);
+/* Section 5.1 (get_cache_load): M_r = sum 4 d (prefix + input), F_r = sum 2 d prefix input,
+ * L = max(M_r / (M_r + n_gpus mem_bw t_ideal), F_r / (F_r + n_gpus flops t_ideal)).
+ * prefix_len / input_len: host [n].  Any of the three outputs may be NULL. */
+tl_status tl_model_cache_load(double d, const int64_t* prefix_len, const int64_t* input_len, int32_t n,
+                              int32_t n_gpus, double mem_bw, double flops, double t_ideal, double* traffic_out,
+                              double* flops_out, double* load_out);
+
 #ifdef __cplusplus
 }
 #endif

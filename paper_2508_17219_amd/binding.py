@@ -35,7 +35,8 @@ class tl_plan_info(C.Structure):
 
 _lib = None
 
-_P, _I32, _U64, _F32 = C.c_void_p, C.c_int32, C.c_uint64, C.c_float
+_P, _I32, _U64, _F32, _F64 = C.c_void_p, C.c_int32, C.c_uint64, C.c_float, C.c_double
+_PF64 = C.POINTER(C.c_double)
 _SIGNATURES = {
     "tl_status_str": (C.c_char_p, [_I32]),
     "tl_last_error": (C.c_char_p, []),
@@ -59,6 +60,10 @@ _SIGNATURES = {
     "tl_segment_attn": (_I32, [_P, _P, _P, _F32, _P, _P, _P]),
     "tl_causal_block": (_I32, [_P, _P, _P, _P, _F32, _P, _P, _P]),
     "tl_merge": (_I32, [_P, _P, _P, _P, _I32, _P, _P]),
+    "tl_model_segment_time": (_I32, [_F64, _F64, _F64, _F64, _F64, _PF64]),
+    "tl_model_comm_time": (_I32, [_F64, _F64, _F64, _PF64]),
+    "tl_model_segment_threshold": (_I32, [_F64, _F64, _F64, _F64, _F64, _F64, _PF64]),
+    "tl_model_cache_load": (_I32, [_F64, _P, _P, _I32, _I32, _F64, _F64, _F64, _PF64, _PF64, _PF64]),
 }
 EXPORTED = tuple(_SIGNATURES)
 
@@ -239,3 +244,34 @@ def tl_merge(plan: int, out_partial, lse, out, out_is_bf16: bool, lse_out=None, 
 
 def tl_set_option(knob: str, value: int):
     _check(load_library().tl_set_option(knob.encode(), value))
+
+
+# ---- analytic models ----------------------------------------------------------------------
+def tl_model_segment_time(n_tokens: float, d_q: float, d_kv: float, flops: float, mem_bw: float) -> float:
+    out = _F64(0.0)
+    _check(load_library().tl_model_segment_time(n_tokens, d_q, d_kv, flops, mem_bw, C.byref(out)))
+    return out.value
+
+
+def tl_model_comm_time(d_q: float, net_latency: float, net_bw: float) -> float:
+    out = _F64(0.0)
+    _check(load_library().tl_model_comm_time(d_q, net_latency, net_bw, C.byref(out)))
+    return out.value
+
+
+def tl_model_segment_threshold(d_q: float, d_kv: float, flops: float, mem_bw: float, net_latency: float,
+                               net_bw: float) -> float:
+    out = _F64(0.0)
+    _check(load_library().tl_model_segment_threshold(d_q, d_kv, flops, mem_bw, net_latency, net_bw, C.byref(out)))
+    return out.value
+
+
+def tl_model_cache_load(d: float, prefix_len, input_len, n_gpus: int, mem_bw: float, flops: float, t_ideal: float):
+    """Returns (M_r bytes, F_r flop, L)."""
+    pl, il = _host(prefix_len, np.int64), _host(input_len, np.int64)
+    if len(pl) != len(il):
+        raise ValueError("prefix_len/input_len length mismatch")
+    m, f, load = _F64(0.0), _F64(0.0), _F64(0.0)
+    _check(load_library().tl_model_cache_load(d, pl.ctypes.data if len(pl) else None, il.ctypes.data if len(il) else None,
+                                              len(pl), n_gpus, mem_bw, flops, t_ideal, C.byref(m), C.byref(f), C.byref(load)))
+    return m.value, f.value, load.value
