@@ -1,9 +1,11 @@
 #!/usr/bin/env python3
 """Benchmark of the segment-attention hot path on one MI355X.
 
-A "step" is one pass of the whole path over one batch: tl_segment_attn (partial attention of
-every work item over its pool slots) + tl_causal_block (self block of the new tokens) +
-tl_merge (LSE recombination), with all inputs already resident in HBM.
+A "step" is one pass of the whole path over one batch, with all inputs already resident in
+HBM: tl_segment_attn (partial attention of every work item over its pool slots) +
+tl_causal_block (self block of the new tokens) + tl_merge (LSE recombination) + tl_fused_attn
+(the same three in one pass for requests whose rows fill whole row tiles; the plan decides,
+TL_PLAN_FUSE_ROWS).  `--three-step` plans without the one-pass kernel.
 
 Default workload: "prefill" (Llama-3-8B layer shape, 16 requests x 512 new tokens, prefixes
 8k-32k tokens, first 2k shared) -- the configuration the prefill MFMA target is quoted on.
@@ -65,22 +67,22 @@ def _setup(batch, torch, B):
     return pk, pv, pool
 
 
-def run_workload(batch, steps, warmup, torch, B, split_segments=0):
+def run_workload(batch, steps, warmup, torch, B, split_segments=0, fuse=True):
     """Times `steps` passes of the whole path; returns timings and the plan's work counters."""
     pk, pv, pool = _setup(batch, torch, B)
     plan = B.tl_plan_create(pool, batch.q_heads, batch.req_row_ptr, batch.req_seg_ptr, batch.seg_ids,
-                            B.TL_PLAN_SELF_BLOCK, split_segments)
+                            B.TL_PLAN_SELF_BLOCK | (B.TL_PLAN_FUSE_ROWS if fuse else 0), split_segments)
     info = B.tl_plan_get_info(plan)
     dev = "cuda"
     q, kn, vn = batch.q(dev), batch.k_new(dev), batch.v_new(dev)
     H, D = batch.q_heads, batch.head_dim
-    outp = torch.empty((info.n_partial_rows, H, D), dtype=torch.float32, device=dev)
-    lsep = torch.empty((info.n_partial_rows, H), dtype=torch.float32, device=dev)
+    outp = torch.empty((max(info.n_partial_rows, 1), H, D), dtype=torch.float32, device=dev)
+    lsep = torch.empty((max(info.n_partial_rows, 1), H), dtype=torch.float32, device=dev)
     out = torch.empty((info.n_tokens, H, D), dtype=torch.bfloat16, device=dev)
     lse = torch.empty((info.n_tokens, H), dtype=torch.float32, device=dev)
     scale = batch.scale
 
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(steps)]
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(steps)]
 
     def step(marks=None):
         if marks: marks[0].record()
@@ -90,6 +92,8 @@ def run_workload(batch, steps, warmup, torch, B, split_segments=0):
         if marks: marks[2].record()
         B.tl_merge(plan, outp, lsep, out, True, lse)
         if marks: marks[3].record()
+        B.tl_fused_attn(pool, plan, q, kn, vn, scale, out, True, lse)
+        if marks: marks[4].record()
 
     for _ in range(max(warmup, 1)):
         step()
@@ -102,9 +106,10 @@ def run_workload(batch, steps, warmup, torch, B, split_segments=0):
     seg_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / steps
     causal_ms = sum(e[1].elapsed_time(e[2]) for e in ev) / steps
     merge_ms = sum(e[2].elapsed_time(e[3]) for e in ev) / steps
+    fused_ms = sum(e[3].elapsed_time(e[4]) for e in ev) / steps
     res = {
         "ms_per_step": (t1 - t0) * 1e3 / steps,
-        "segment_attn_ms": seg_ms, "causal_block_ms": causal_ms, "merge_ms": merge_ms,
+        "segment_attn_ms": seg_ms, "causal_block_ms": causal_ms, "merge_ms": merge_ms, "fused_attn_ms": fused_ms,
         "info": {n: getattr(info, n) for n, _ in info._fields_},
         "checksum": float(out.float().abs().mean().item()),
     }
@@ -124,8 +129,10 @@ def algorithmic_work(batch, info):
     q_bytes = 2.0 * hq * d * info["n_tokens"]
     part_rows = info["n_partial_rows"] - (info["n_tokens"] if info["self_row_base"] >= 0 else 0)
     part_bytes = part_rows * hq * (d + 1) * 4.0
+    # one-pass rows: K/V of the new tokens are read, the final bf16 output and fp32 LSE are written
+    fused_io_bytes = info["n_fused_tokens"] * (4.0 * hkv * d + hq * (2.0 * d + 4.0))
     return {"flops_prefix": flops_prefix, "flops_self": flops_self, "kv_bytes": kv_bytes, "q_bytes": q_bytes,
-            "partial_bytes": part_bytes}
+            "partial_bytes": part_bytes, "fused_io_bytes": fused_io_bytes}
 
 
 def cpu_baseline(batch, budget_s=15.0):
@@ -178,6 +185,8 @@ def main():
     ap.add_argument("--workload", default="prefill", choices=["prefill", "decode", "longctx", "multiturn", "tiny"])
     ap.add_argument("--split-segments", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--three-step", action="store_true",
+                    help="plan without TL_PLAN_FUSE_ROWS: every request goes through partials and the merge")
     ap.add_argument("--no-decode", action="store_true", help="skip the appended decode measurement")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a 1 GiB device copy (to scale rocprofv3 FETCH_SIZE/WRITE_SIZE) and exit")
@@ -200,7 +209,7 @@ def main():
     maker = {"prefill": wl.prefill, "decode": wl.decode, "longctx": wl.longctx, "tiny": wl.tiny,
              "multiturn": lambda: wl.multiturn(turn=7)}[args.workload]
     batch = maker()
-    res = run_workload(batch, args.steps, args.warmup, torch, B, args.split_segments)
+    res = run_workload(batch, args.steps, args.warmup, torch, B, args.split_segments, fuse=not args.three_step)
     work = algorithmic_work(batch, res["info"])
     tok_s = batch.n_tokens / (res["ms_per_step"] * 1e-3)
 
@@ -213,6 +222,15 @@ def main():
                     "unit": "GB/s", "frac": ach / PEAK_HBM_GBS,
                     "traffic": measured_traffic("splitk_unit_attn_kernel", b.name),
                     "algorithmic_bytes": by, "avg_kernel_ms": r["segment_attn_ms"]}
+        if r["info"]["n_fused_tokens"] == r["info"]["n_tokens"]:
+            # every request takes the one-pass kernel: pool tiles and causal block in one launch
+            fl = w["flops_prefix"] + w["flops_self"]
+            ach = fl / (r["fused_attn_ms"] * 1e-3) / 1e12
+            return {"kernel": "row_tile_attn_kernel<one pass>", "bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS,
+                    "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS,
+                    "traffic": measured_traffic("row_tile_attn_kernel<one pass>", b.name),
+                    "algorithmic_flops": fl, "algorithmic_bytes": w["kv_bytes"] + w["q_bytes"] + w["fused_io_bytes"],
+                    "avg_kernel_ms": r["fused_attn_ms"]}
         ach = w["flops_prefix"] / seg_s / 1e12
         return {"kernel": "row_tile_attn_kernel", "bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS,
                 "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS,
@@ -220,7 +238,7 @@ def main():
                 "algorithmic_flops": w["flops_prefix"], "avg_kernel_ms": r["segment_attn_ms"]}
 
     line = {
-        "metric": "merged tok/s (one layer: partial attention over the segment pool + causal self block + LSE merge)",
+        "metric": "merged tok/s (one layer: attention over the segment pool + causal self block, partials merged)",
         "value": tok_s, "unit": "tok/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": res["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
@@ -230,19 +248,22 @@ def main():
                    "seed": batch.seed},
         "roofline": roofline_for(batch, res, work),
         "kernels_ms": {"segment_attn": res["segment_attn_ms"], "causal_block": res["causal_block_ms"],
-                       "merge": res["merge_ms"]},
-        "partial_attn_tflops": (work["flops_prefix"] + work["flops_self"]) /
-                               ((res["segment_attn_ms"] + res["causal_block_ms"]) * 1e-3) / 1e12,
+                       "merge": res["merge_ms"], "fused_attn": res["fused_attn_ms"]},
+        "plan": {"fused_tokens": res["info"]["n_fused_tokens"], "row_tiles": res["info"]["n_tiles"],
+                 "split_k_units": res["info"]["n_units"], "causal_tiles": res["info"]["n_causal_tiles"],
+                 "fused_row_tiles": res["info"]["n_fused_tiles"]},
+        "attn_tflops": (work["flops_prefix"] + work["flops_self"]) /
+                       ((res["segment_attn_ms"] + res["causal_block_ms"] + res["fused_attn_ms"]) * 1e-3) / 1e12,
     }
     if args.workload != "decode" and not args.no_decode:
         db = wl.decode()
-        dres = run_workload(db, max(3, args.steps // 4), 1, torch, B, args.split_segments)
+        dres = run_workload(db, max(3, args.steps // 4), 1, torch, B, args.split_segments, fuse=not args.three_step)
         dwork = algorithmic_work(db, dres["info"])
         line["decode"] = {"workload": db.name, "ms_per_step": dres["ms_per_step"],
                           "merged_tok_s": db.n_tokens / (dres["ms_per_step"] * 1e-3),
                           "roofline": roofline_for(db, dres, dwork),
                           "kernels_ms": {"segment_attn": dres["segment_attn_ms"], "causal_block": dres["causal_block_ms"],
-                                         "merge": dres["merge_ms"]}}
+                                         "merge": dres["merge_ms"], "fused_attn": dres["fused_attn_ms"]}}
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(batch)
     print(json.dumps(line))

@@ -137,7 +137,14 @@ typedef struct tl_plan tl_plan;
 
 enum {
   TL_PLAN_SELF_BLOCK = 1, /* reserve partial rows for tl_causal_block and merge them   */
-  TL_PLAN_NO_SHARING = 2  /* do not group requests: one item chain per request         */
+  TL_PLAN_NO_SHARING = 2, /* do not group requests: one item chain per request         */
+  TL_PLAN_FUSE_ROWS = 4   /* requests with at least 256 query rows per kv head (new
+                             tokens x q-heads per kv-head) leave the three-step path: one
+                             pass of tl_fused_attn over their whole slot list and their own
+                             new tokens writes their final output.  Such rows have a single
+                             partial, so nothing is written to out_partial for them and
+                             tl_segment_attn / tl_causal_block / tl_merge skip them.
+                             Needs TL_PLAN_SELF_BLOCK.                                   */
 };
 
 typedef struct tl_plan_info {
@@ -153,6 +160,8 @@ typedef struct tl_plan_info {
   int64_t prefix_pairs;    /* sum over list entries of new_tokens(req) * fill(slot)      */
   int64_t self_pairs;      /* sum over requests of Lq (Lq + 1) / 2                       */
   int64_t unique_kv_tokens;/* valid tokens in the distinct slots the plan touches        */
+  int32_t n_fused_tiles;   /* row tiles of tl_fused_attn (TL_PLAN_FUSE_ROWS)             */
+  int32_t n_fused_tokens;  /* new tokens whose output tl_fused_attn writes               */
 } tl_plan_info;
 
 /* req_row_ptr: host [n_req+1], offsets of each request's new tokens in the batch's Q
@@ -206,6 +215,18 @@ tl_status tl_causal_block(tl_plan* plan, const void* q_dev, const void* k_new_de
  *   M = max_j LSE_j, w_j = exp(LSE_j - M), O = sum_j w_j O_j / sum_j w_j, LSE = M + ln sum_j w_j.
  * out_dev: device [n_tokens, q_heads, 128], bf16 if out_is_bf16 else fp32.
  * lse_out: device [n_tokens, q_heads] fp32, or NULL. */
+/* The whole path in one pass for the requests that TL_PLAN_FUSE_ROWS took out of the three
+ * steps (paper Section 3.3: prefix attention and the new tokens' self-attention of a request
+ * need not be separate passes when one engine holds both): each row tile walks the request's
+ * pool tiles, then the new tokens up to its own rows, and writes the normalised output.
+ * q_dev, k_new_dev, v_new_dev as in tl_causal_block.  out_dev: device [n_tokens, q_heads, 128],
+ * bf16 if out_is_bf16 else fp32; lse_out: device [n_tokens, q_heads] fp32 or NULL.  Only the
+ * fused requests' tokens are written; the other tokens of the same arrays are written by
+ * tl_merge.  A plan without fused requests: nothing to do, TL_OK. */
+tl_status tl_fused_attn(const tl_pool* pool, tl_plan* plan, const void* q_dev, const void* k_new_dev,
+                        const void* v_new_dev, float scale, void* out_dev, int32_t out_is_bf16, float* lse_out,
+                        void* stream);
+
 tl_status tl_merge(tl_plan* plan, const float* out_partial, const float* lse, void* out_dev,
                    int32_t out_is_bf16, float* lse_out, void* stream);
 

@@ -17,7 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libtokenlake.so")
 
 TL_OK, TL_EINVAL, TL_ENOMEM, TL_EFULL, TL_ENOTFOUND, TL_EHIP = 0, -1, -2, -3, -4, -5
-TL_PLAN_SELF_BLOCK, TL_PLAN_NO_SHARING = 1, 2
+TL_PLAN_SELF_BLOCK, TL_PLAN_NO_SHARING, TL_PLAN_FUSE_ROWS = 1, 2, 4
 
 
 class TokenLakeError(RuntimeError):
@@ -30,7 +30,8 @@ class tl_plan_info(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "n_req", "n_tokens", "q_heads", "kv_heads", "n_items", "n_partial_rows", "self_row_base",
         "n_tiles", "n_units", "n_causal_tiles", "n_list_entries", "n_merge_entries")] + [
-        (n, C.c_int64) for n in ("prefix_pairs", "self_pairs", "unique_kv_tokens")]
+        (n, C.c_int64) for n in ("prefix_pairs", "self_pairs", "unique_kv_tokens")] + [
+        (n, C.c_int32) for n in ("n_fused_tiles", "n_fused_tokens")]
 
 
 _lib = None
@@ -60,6 +61,7 @@ _SIGNATURES = {
     "tl_segment_attn": (_I32, [_P, _P, _P, _F32, _P, _P, _P]),
     "tl_causal_block": (_I32, [_P, _P, _P, _P, _F32, _P, _P, _P]),
     "tl_merge": (_I32, [_P, _P, _P, _P, _I32, _P, _P]),
+    "tl_fused_attn": (_I32, [_P, _P, _P, _P, _P, _F32, _P, _I32, _P, _P]),
     "tl_model_segment_time": (_I32, [_F64, _F64, _F64, _F64, _F64, _PF64]),
     "tl_model_comm_time": (_I32, [_F64, _F64, _F64, _PF64]),
     "tl_model_segment_threshold": (_I32, [_F64, _F64, _F64, _F64, _F64, _F64, _PF64]),
@@ -235,6 +237,11 @@ def tl_segment_attn(pool: int, plan: int, q, scale: float, out_partial, lse, str
 def tl_causal_block(plan: int, q, k_new, v_new, scale: float, out_partial, lse, stream=None):
     _check(load_library().tl_causal_block(plan, _dev(q), _dev(k_new), _dev(v_new), scale, _dev(out_partial), _dev(lse),
                                           _stream(stream)))
+
+
+def tl_fused_attn(pool: int, plan: int, q, k_new, v_new, scale: float, out, out_is_bf16: bool, lse_out=None, stream=None):
+    _check(load_library().tl_fused_attn(pool, plan, _dev(q), _dev(k_new), _dev(v_new), scale, _dev(out),
+                                        int(bool(out_is_bf16)), _dev(lse_out), _stream(stream)))
 
 
 def tl_merge(plan: int, out_partial, lse, out, out_is_bf16: bool, lse_out=None, stream=None):

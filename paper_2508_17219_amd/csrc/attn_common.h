@@ -27,6 +27,11 @@ struct AttnArgs {
   const uint16_t* q;      // [n_tokens, q_heads, 128] bf16
   const uint16_t* k;      // pool K base, or new-token K [n_tokens, kv_heads, 128]
   const uint16_t* v;
+  const uint16_t* k2;     // fused rows only: the new tokens' K/V [n_tokens, kv_heads, 128]
+  const uint16_t* v2;
+  void* final_out;        // fused rows only: [n_tokens, q_heads, 128] fp32 or bf16
+  float* final_lse;       // fused rows only: [n_tokens, q_heads] or null
+  int32_t final_is_bf16;
   const int32_t* fill;    // per-slot valid tokens (pool work)
   const Work* work;
   const int32_t* tok;     // token index lists

@@ -10,18 +10,20 @@ namespace tl {
 tl_status launch_pool_row_tiles(const AttnArgs& a, int n_work, hipStream_t st);
 tl_status launch_causal_row_tiles(const AttnArgs& a, int n_work, hipStream_t st);
 tl_status launch_splitk_units(const AttnArgs& a, int n_work, hipStream_t st);
+tl_status launch_fused_row_tiles(const AttnArgs& a, int n_work, hipStream_t st);
 
 namespace {
 
-// blockIdx.x = token, blockIdx.y = chunk of 256 (head, channel-quad) positions; a thread owns
+// blockIdx.x = position in the list of tokens to merge, blockIdx.y = chunk of 256 (head, channel-quad) positions; a thread owns
 // 4 consecutive channels of one head.
 //   M = max_j LSE_j;  w_j = exp(LSE_j - M);  O = sum w_j O_j / sum w_j;  LSE = M + ln sum w_j
 template <bool OUT_BF16>
 __global__ __launch_bounds__(256) void lse_merge_kernel(const float* __restrict__ part, const float* __restrict__ lse,
                                                         const int32_t* __restrict__ mptr,
-                                                        const int32_t* __restrict__ mrows, void* __restrict__ out,
+                                                        const int32_t* __restrict__ mrows,
+                                                        const int32_t* __restrict__ mtok, void* __restrict__ out,
                                                         float* __restrict__ lse_out, int q_heads) {
-  const int t = blockIdx.x;
+  const int t = mtok[blockIdx.x];
   const int b = mptr[t], e = mptr[t + 1];
   const int idx = blockIdx.y * blockDim.x + threadIdx.x;
   if (idx < q_heads * 32) {
@@ -72,6 +74,10 @@ void fill_args(AttnArgs& a, const tl_plan* plan, const void* q, float scale, flo
   a.log2g = ilog2(plan->group);
   a.scale = scale;
   a.scale_log2e = scale * 1.4426950408889634f;
+  a.k2 = a.v2 = nullptr;
+  a.final_out = nullptr;
+  a.final_lse = nullptr;
+  a.final_is_bf16 = 0;
 }
 
 }  // namespace
@@ -124,20 +130,48 @@ tl_status tl_causal_block(tl_plan* plan, const void* q_dev, const void* k_new_de
   return launch_causal_row_tiles(a, a.n_work, (hipStream_t)stream);
 }
 
+tl_status tl_fused_attn(const tl_pool* pool, tl_plan* plan, const void* q_dev, const void* k_new_dev,
+                        const void* v_new_dev, float scale, void* out_dev, int32_t out_is_bf16, float* lse_out,
+                        void* stream) {
+  if (!pool || !plan || !q_dev || !k_new_dev || !v_new_dev || !out_dev) TL_FAIL(TL_EINVAL, "tl_fused_attn: null argument");
+  if (plan->pool != pool) TL_FAIL(TL_EINVAL, "tl_fused_attn: plan was built for another pool");
+  if (!(scale > 0.f) || !std::isfinite(scale)) TL_FAIL(TL_EINVAL, "tl_fused_attn: scale must be positive and finite");
+  if (plan->ftiles.empty()) return TL_OK;
+  hipStream_t st = (hipStream_t)stream;
+  tl_status rc = pool_device_ready(pool, st);
+  if (rc != TL_OK) return rc;
+  rc = plan_device_ready(plan);
+  if (rc != TL_OK) return rc;
+  AttnArgs a;
+  fill_args(a, plan, q_dev, scale, nullptr, nullptr);
+  a.k = (const uint16_t*)pool->k_dev;
+  a.v = (const uint16_t*)pool->v_dev;
+  a.k2 = (const uint16_t*)k_new_dev;
+  a.v2 = (const uint16_t*)v_new_dev;
+  a.final_out = out_dev;
+  a.final_lse = lse_out;
+  a.final_is_bf16 = out_is_bf16 ? 1 : 0;
+  a.fill = pool->fill_dev;
+  a.seg_len = pool->seg_len;
+  a.work = plan->d_ftiles;
+  a.n_work = (int)plan->ftiles.size();
+  return launch_fused_row_tiles(a, a.n_work, st);
+}
+
 tl_status tl_merge(tl_plan* plan, const float* out_partial, const float* lse, void* out_dev, int32_t out_is_bf16,
                    float* lse_out, void* stream) {
   if (!plan || !out_partial || !lse || !out_dev) TL_FAIL(TL_EINVAL, "tl_merge: null argument");
   tl_status rc = plan_device_ready(plan);
   if (rc != TL_OK) return rc;
-  if (plan->n_tokens == 0) return TL_OK;
+  if (plan->merge_tok.empty()) return TL_OK;
   hipStream_t st = (hipStream_t)stream;
-  const dim3 grid((unsigned)plan->n_tokens, (unsigned)((plan->q_heads * 32 + 255) / 256)), block(256);
+  const dim3 grid((unsigned)plan->merge_tok.size(), (unsigned)((plan->q_heads * 32 + 255) / 256)), block(256);
   if (out_is_bf16)
     hipLaunchKernelGGL(lse_merge_kernel<true>, grid, block, 0, st, out_partial, lse, plan->d_merge_ptr, plan->d_merge_rows,
-                       out_dev, lse_out, plan->q_heads);
+                       plan->d_merge_tok, out_dev, lse_out, plan->q_heads);
   else
     hipLaunchKernelGGL(lse_merge_kernel<false>, grid, block, 0, st, out_partial, lse, plan->d_merge_ptr, plan->d_merge_rows,
-                       out_dev, lse_out, plan->q_heads);
+                       plan->d_merge_tok, out_dev, lse_out, plan->q_heads);
   TL_HIP(hipGetLastError());
   return TL_OK;
 }

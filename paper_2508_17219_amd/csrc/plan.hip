@@ -38,6 +38,8 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
   const int G = q_heads / pool->kv_heads;
   if (!is_pow2(G) || G > 32) TL_FAIL(TL_EINVAL, "tl_plan_create: q_heads/kv_heads must be a power of two <= 32");
   if (split_segments < 0) TL_FAIL(TL_EINVAL, "tl_plan_create: negative split_segments");
+  if ((flags & TL_PLAN_FUSE_ROWS) && !(flags & TL_PLAN_SELF_BLOCK))
+    TL_FAIL(TL_EINVAL, "tl_plan_create: TL_PLAN_FUSE_ROWS needs TL_PLAN_SELF_BLOCK");
   if (req_row_ptr[0] != 0 || req_seg_ptr[0] != 0) TL_FAIL(TL_EINVAL, "tl_plan_create: offsets must start at 0");
   for (int32_t r = 0; r < n_req; ++r)
     if (req_row_ptr[r + 1] < req_row_ptr[r] || req_seg_ptr[r + 1] < req_seg_ptr[r])
@@ -79,10 +81,16 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
     auto ntok_of = [&](int32_t r) { return req_row_ptr[r + 1] - req_row_ptr[r]; };
 
     // ---- group requests along shared runs ----------------------------------------------
+    // requests whose rows fill whole row tiles by themselves gain nothing from sharing a run
+    // with others (the work is bound by the matrix unit, not by KV traffic) and lose a partial
+    // per row: with TL_PLAN_FUSE_ROWS they are set aside for the one-pass kernel
+    std::vector<char> fused(n_req, 0);
+    if (flags & TL_PLAN_FUSE_ROWS)
+      for (int32_t r = 0; r < n_req; ++r) fused[r] = (int64_t)ntok_of(r) * G >= kRowTile;
     std::vector<RawItem> raw;
     std::vector<int32_t> live;
     for (int32_t r = 0; r < n_req; ++r)
-      if (ntok_of(r) > 0 && len_of(r) > 0) live.push_back(r);
+      if (ntok_of(r) > 0 && len_of(r) > 0 && !fused[r]) live.push_back(r);
     if (flags & TL_PLAN_NO_SHARING) {
       for (int32_t r : live) raw.push_back(RawItem{{r}, r, 0, len_of(r)});
     } else {
@@ -146,6 +154,7 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
     p->item_tok_ptr.push_back(0);
     p->item_slot_ptr.push_back(0);
     int64_t prefix_pairs = 0;
+    int32_t n_fused_tokens = 0;
     for (const RawItem& it : raw) {
       int32_t n_tok = 0;
       for (int32_t r : it.reqs) n_tok += ntok_of(r);
@@ -208,9 +217,33 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
         const int32_t a = req_row_ptr[r], b = req_row_ptr[r + 1];
         const int64_t lq = b - a;
         self_pairs += lq * (lq + 1) / 2;
+        int32_t full_off = 0, n_full = 0, part_off = 0, n_part = 0;
+        if (fused[r]) {
+          // the request's whole slot list as tiles of kKvTile rows
+          full_off = (int32_t)p->tile_base.size();
+          part_off = (int32_t)p->part_tile.size() / 2;
+          for (int32_t pos = 0; pos < len_of(r); ++pos) {
+            const int32_t s = slot_at(r, pos), f = pool->fill[s];
+            prefix_pairs += lq * f;
+            for (int32_t off = 0; off < f; off += kKvTile) {
+              if (off + kKvTile <= f) {
+                p->tile_base.push_back(s * pool->seg_len + off);
+              } else {
+                p->part_tile.push_back(s * pool->seg_len + off);
+                p->part_tile.push_back(f - off);
+              }
+            }
+          }
+          n_full = (int32_t)p->tile_base.size() - full_off;
+          n_part = (int32_t)p->part_tile.size() / 2 - part_off;
+          n_fused_tokens += (int32_t)lq;
+        }
         for (int32_t t0 = a; t0 < b; t0 += tok_tile) {
           const int32_t n = std::min(tok_tile, b - t0);
-          p->ctiles.push_back(Work{ident_base + t0, n, self_base + t0, a, t0 + n - a, 0, 0, 0, 0});
+          if (fused[r])
+            p->ftiles.push_back(Work{ident_base + t0, n, t0, a, t0 + n - a, full_off, n_full, part_off, n_part});
+          else
+            p->ctiles.push_back(Work{ident_base + t0, n, self_base + t0, a, t0 + n - a, 0, 0, 0, 0});
         }
       }
       row_cursor += T;
@@ -223,13 +256,23 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
     std::stable_sort(p->tiles.begin(), p->tiles.end(), by_len);
     std::stable_sort(p->units.begin(), p->units.end(), by_len);
     std::stable_sort(p->ctiles.begin(), p->ctiles.end(), by_len);
+    std::stable_sort(p->ftiles.begin(), p->ftiles.end(), [](const Work& x, const Work& y) {
+      return x.n_full + x.n_part + x.kv_len / kKvTile > y.n_full + y.n_part + y.kv_len / kKvTile;
+    });
 
     // ---- merge lists --------------------------------------------------------------------------
     p->merge_ptr.assign(T + 1, 0);
     for (int32_t i = 0; i < n_items; ++i)
       for (int32_t j = p->item_tok_ptr[i]; j < p->item_tok_ptr[i + 1]; ++j) p->merge_ptr[p->item_tokens[j] + 1]++;
+    std::vector<char> tok_fused(T, 0);
+    for (int32_t r = 0; r < n_req; ++r)
+      if (fused[r])
+        for (int32_t t = req_row_ptr[r]; t < req_row_ptr[r + 1]; ++t) tok_fused[t] = 1;
+    for (int32_t t = 0; t < T; ++t)
+      if (!tok_fused[t]) p->merge_tok.push_back(t);
     if (self_base >= 0)
-      for (int32_t t = 0; t < T; ++t) p->merge_ptr[t + 1]++;
+      for (int32_t t = 0; t < T; ++t)
+        if (!tok_fused[t]) p->merge_ptr[t + 1]++;
     for (int32_t t = 0; t < T; ++t) p->merge_ptr[t + 1] += p->merge_ptr[t];
     p->merge_rows.assign(p->merge_ptr[T], 0);
     {
@@ -238,7 +281,8 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
         for (int32_t j = p->item_tok_ptr[i]; j < p->item_tok_ptr[i + 1]; ++j)
           p->merge_rows[cur[p->item_tokens[j]]++] = p->item_row_base[i] + (j - p->item_tok_ptr[i]);
       if (self_base >= 0)
-        for (int32_t t = 0; t < T; ++t) p->merge_rows[cur[t]++] = self_base + t;
+        for (int32_t t = 0; t < T; ++t)
+          if (!tok_fused[t]) p->merge_rows[cur[t]++] = self_base + t;
     }
 
     std::unordered_set<int32_t> uniq(slots.begin(), slots.end());
@@ -262,6 +306,8 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
     inf.prefix_pairs = prefix_pairs;
     inf.self_pairs = self_pairs;
     inf.unique_kv_tokens = uniq_tok;
+    inf.n_fused_tiles = (int32_t)p->ftiles.size();
+    inf.n_fused_tokens = n_fused_tokens;
   } catch (const std::bad_alloc&) {
     rc = TL_ENOMEM;
     set_error("tl_plan_create: host allocation failed");
@@ -326,7 +372,9 @@ tl_status plan_device_ready(tl_plan* p) {
   const size_t b_mrows = al(sizeof(int32_t) * p->merge_rows.size());
   const size_t b_tbase = al(sizeof(int32_t) * p->tile_base.size());
   const size_t b_part = al(sizeof(int32_t) * p->part_tile.size());
-  const size_t total = b_tiles + b_units + b_ctiles + b_tok + b_slots + b_mptr + b_mrows + b_tbase + b_part + 256;
+  const size_t b_ftiles = al(sizeof(Work) * p->ftiles.size());
+  const size_t b_mtok = al(sizeof(int32_t) * p->merge_tok.size());
+  const size_t total = b_tiles + b_units + b_ctiles + b_tok + b_slots + b_mptr + b_mrows + b_tbase + b_part + b_ftiles + b_mtok + 256;
   std::vector<char> host(total, 0);
   size_t off = 0;
   auto put = [&](const void* src, size_t bytes, size_t reserved) {
@@ -344,6 +392,8 @@ tl_status plan_device_ready(tl_plan* p) {
   const size_t o_mrows = put(p->merge_rows.data(), sizeof(int32_t) * p->merge_rows.size(), b_mrows);
   const size_t o_tbase = put(p->tile_base.data(), sizeof(int32_t) * p->tile_base.size(), b_tbase);
   const size_t o_part = put(p->part_tile.data(), sizeof(int32_t) * p->part_tile.size(), b_part);
+  const size_t o_ftiles = put(p->ftiles.data(), sizeof(Work) * p->ftiles.size(), b_ftiles);
+  const size_t o_mtok = put(p->merge_tok.data(), sizeof(int32_t) * p->merge_tok.size(), b_mtok);
   void* blob = nullptr;
   TL_HIP(hipMalloc(&blob, total));
   hipError_t e = hipMemcpy(blob, host.data(), total, hipMemcpyHostToDevice);
@@ -362,6 +412,8 @@ tl_status plan_device_ready(tl_plan* p) {
   p->d_merge_rows = (int32_t*)(b + o_mrows);
   p->d_tile_base = (int32_t*)(b + o_tbase);
   p->d_part_tile = (int32_t*)(b + o_part);
+  p->d_ftiles = (Work*)(b + o_ftiles);
+  p->d_merge_tok = (int32_t*)(b + o_mtok);
   p->on_device = true;
   return TL_OK;
 }

@@ -93,7 +93,11 @@ __device__ __forceinline__ float max16(const f32x16& s) {
   return fmaxf(fmaxf(fmaxf(a, b), fmaxf(c, d)), fmaxf(e, s[15]));
 }
 
-template <bool CAUSAL, int VREAD>
+// MODE 0: pool work item (tile lists) -> partial.  MODE 1: causal block of the new tokens ->
+// partial.  MODE 2: both in one pass -- the row tile walks its request's pool tiles, then the
+// new tokens up to its own rows -- and writes the final, normalised output: such rows have one
+// partial, so they need no merge.
+template <int MODE, int VREAD>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kRG, 2 / kRG))) void row_tile_attn_kernel(const AttnArgs a) {
   extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
   uint16_t* lds_k = lds;                 // [kBufs][64][kKS]
@@ -107,6 +111,10 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
   const int wave = tid >> 6, lane = tid & 63, l32 = lane & 31, h = lane >> 5;
   const int G = 1 << a.log2g;
   const int first_token = a.tok[wk.tok_off];   // causal work: tokens of a tile are consecutive
+  constexpr bool kHasPool = MODE != 1, kHasSelf = MODE != 0;
+  // K/V of the new tokens: the launch's main K/V for the causal block alone, the second pair when fused
+  const uint16_t* self_k = MODE == 2 ? a.k2 : a.k;
+  const uint16_t* self_v = MODE == 2 ? a.v2 : a.v;
 
   // per row group: this lane's row, its token and head
   int tok_local[kRG], head_j[kRG], token[kRG];
@@ -138,7 +146,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
   f32x16 o[kRG][4];
   float m_ref[kRG];   // reference point of the exponent (raw score units), -inf before any key
   float l_run[kRG];   // this lane's share of sum exp(s - m_ref)
-  auto reset_state = [&]() {
+  auto reset_state = [&]() __attribute__((always_inline)) {
 #pragma unroll
     for (int rg = 0; rg < kRG; ++rg) {
 #pragma unroll
@@ -153,21 +161,18 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
   const float c = a.scale_log2e;
 
   // which tiles are full (no masking needed for any row of this workgroup)
-  int n_full, n_part;
-  if (CAUSAL) {
-    n_full = (first_token - wk.kv_off + 1) / kKvTile;
-    n_part = (wk.kv_len + kKvTile - 1) / kKvTile - n_full;
-  } else {
-    n_full = wk.n_full;
-    n_part = wk.n_part;
+  const int nf_pool = kHasPool ? wk.n_full : 0, np_pool = kHasPool ? wk.n_part : 0;
+  int nf_self = 0, np_self = 0;
+  if (kHasSelf) {
+    nf_self = (first_token - wk.kv_off + 1) / kKvTile;
+    np_self = (wk.kv_len + kKvTile - 1) / kKvTile - nf_self;
   }
-  // first kv row of full tile t: arithmetic for the causal block, else from the item's tile
-  // list, kept in an LDS ring (a dependent global load per iteration would stall the wave)
-  auto full_base = [&](int t) -> int { return CAUSAL ? wk.kv_off + kKvTile * t : lds_idx[t & (kIdxRing - 1)]; };
-  auto ring_fill = [&](int first, int count) {   // entries [first, first+count) of the list, clipped
-    if (!CAUSAL)
-      for (int i = first + tid; i < first + count && i < n_full; i += kThreads)
-        lds_idx[i & (kIdxRing - 1)] = a.tile_base[wk.full_off + i];
+  // first kv row of a full pool tile comes from the item's tile list, kept in an LDS ring (a
+  // dependent global load per iteration would stall the wave); that of a full tile of new tokens
+  // is arithmetic
+  auto ring_fill = [&](int first, int count) __attribute__((always_inline)) {   // entries [first, first+count) of the list, clipped
+    for (int i = first + tid; i < first + count && i < nf_pool; i += kThreads)
+      lds_idx[i & (kIdxRing - 1)] = a.tile_base[wk.full_off + i];
   };
 
   // ---- global <-> LDS staging: 4 chunks of 16 B per thread per tile, for K and for V ----
@@ -179,15 +184,15 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
   // constant 32-bit offset inside a tile), so that a tile costs no per-lane 64-bit arithmetic
   const unsigned lane_off0 = (unsigned)((c_tr * kv_row + (size_t)g * kHeadDim) * 2 + c_part * 16);
   const unsigned chunk_step = (unsigned)(kChunkRows * kv_row * 2);
-  auto chunk_ptr = [&](const uint16_t* src, int base, int i) -> const uint4* {
+  auto chunk_ptr = [&](const uint16_t* src, int base, int i) __attribute__((always_inline)) -> const uint4* {
     const char* tile = (const char*)src + (size_t)__builtin_amdgcn_readfirstlane(base) * (kv_row * 2);
     return (const uint4*)(tile + (lane_off0 + chunk_step * i));
   };
-  auto lds_chunk_k = [&](uint16_t* tile, int i) -> uint4* {
+  auto lds_chunk_k = [&](uint16_t* tile, int i) __attribute__((always_inline)) -> uint4* {
     const int r_ = c_tr + kChunkRows * i;
     return (uint4*)&tile[r_ * kKS + 8 * (c_part ^ (r_ & 15))];
   };
-  auto lds_chunk_v = [&](uint16_t* tile, int i) -> uint4* {
+  auto lds_chunk_v = [&](uint16_t* tile, int i) __attribute__((always_inline)) -> uint4* {
     const int r_ = c_tr + kChunkRows * i;
     return (uint4*)&tile[r_ * kVS + 8 * (c_part ^ (4 * (r_ & 3)))];
   };
@@ -215,7 +220,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
   };
   // wait for all of this wave's direct loads (vmcnt(0); the other counters are left alone so that
   // LDS operand reads already in flight stay in flight)
-  auto dma_wait = [&]() { __builtin_amdgcn_s_waitcnt(0x0F70); };
+  auto dma_wait = [&]() __attribute__((always_inline)) { __builtin_amdgcn_s_waitcnt(0x0F70); };
 
   // ---- building blocks ----
   // LDS tiles are unpadded rows of 256 B = 16 chunks of 16 B, written by direct global->LDS
@@ -223,12 +228,12 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
   // storing logical chunk c of row r at position c ^ swz(r):
   //   K: swz(r) = r & 15      -> the 16 rows that 16 lanes read at one logical chunk hit 16 positions
   //   V: swz(r) = 4 (r & 3)   -> the 4 rows x 4 chunks of one transposing read hit 16 positions
-  auto k_operand = [&](const uint16_t* kt, int hb, int s8) -> bf16x8 {
+  auto k_operand = [&](const uint16_t* kt, int hb, int s8) __attribute__((always_inline)) -> bf16x8 {
     return *(const bf16x8*)&kt[(32 * hb + l32) * kKS + 8 * ((2 * s8 + h) ^ (l32 & 15))];
   };
   // V^T operand of accumulation step (sp, d) of block hb: channels 32 d .. 32 d + 31, block
   // tokens 16 sp + {4h..4h+3, 8+4h..8+4h+3} -- the order in which the score registers hold them
-  auto v_operand = [&](const uint16_t* vt, int hb, int sp, int d) -> bf16x8 {
+  auto v_operand = [&](const uint16_t* vt, int hb, int sp, int d) __attribute__((always_inline)) -> bf16x8 {
     const int kvb = 32 * hb + 16 * sp;
     if (VREAD == 0) {
       const int blk = lane >> 4, jj = lane & 15;
@@ -283,7 +288,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
       }
   };
   // careful path: raise the reference maximum if the block's scores exceed it by too much
-  auto maybe_rescale = [&](int rg, const f32x16& s) {
+  auto maybe_rescale = [&](int rg, const f32x16& s) __attribute__((always_inline)) {
     const float mx = xor32_max(max16(s));
     const bool need = (mx - m_ref[rg]) * c > kRescaleLog2 || m_ref[rg] == -INFINITY;
     if (__builtin_amdgcn_ballot_w64(need) != 0) {
@@ -298,15 +303,16 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
     }
   };
   // careful path: one tile (rows beyond `valid` hidden; causal work also hides later tokens)
-  auto careful_tile = [&](int base, int valid) {
+  auto careful_tile = [&](auto SELF, const uint16_t* src_k, const uint16_t* src_v, int base, int valid) __attribute__((always_inline)) {
+    constexpr bool CAUSAL = decltype(SELF)::value;
     {
       // rows beyond `valid` are written as zero: 0 * garbage cannot make NaN
       const uint4 z = make_uint4(0, 0, 0, 0);
 #pragma unroll
       for (int i = 0; i < kChunks; ++i) {
         const bool in = c_tr + kChunkRows * i < valid;
-        const uint4 kk = in ? *chunk_ptr(a.k, base, i) : z;
-        const uint4 vv = in ? *chunk_ptr(a.v, base, i) : z;
+        const uint4 kk = in ? *chunk_ptr(src_k, base, i) : z;
+        const uint4 vv = in ? *chunk_ptr(src_v, base, i) : z;
         *lds_chunk_k(lds_k, i) = kk;
         *lds_chunk_v(lds_v, i) = vv;
       }
@@ -341,7 +347,6 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
     __syncthreads();
   };
 
-  bool redo = false;
   // ======================= fast path: full tiles, software-pipelined by 32-token block =======================
   // Steady state, per block i of the tile stream (two blocks per tile = two steps per iteration):
   //   MFMA:  scores(block i+1)  and  accumulate(block i-1)      16 kRG MFMA each
@@ -349,18 +354,22 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
   // An iteration is 32 operand groups: one LDS operand (a K fragment, or a transposed V fragment)
   // and the kRG MFMAs that use it, plus a slice of the probabilities; the operand is fetched
   // kDepth groups earlier.  sched_barrier(0) after every group keeps the compiler to this order.
-  if (n_full > 0) {
+  // Runs the n_full (> 0) full tiles of one phase; have_ref says whether the exponent's reference
+  // point exists already.  Returns false if the result overflowed and has to be discarded.
+  auto fast_phase = [&](auto SELF, const uint16_t* src_k, const uint16_t* src_v, const int n_full, const bool have_ref) __attribute__((always_inline)) -> bool {
+    constexpr bool CAUSAL = decltype(SELF)::value;
+    auto full_base = [&](int t) __attribute__((always_inline)) -> int { return CAUSAL ? wk.kv_off + kKvTile * t : lds_idx[t & (kIdxRing - 1)]; };
     if (tid == 0) *lds_flag = 0;
-    ring_fill(0, kIdxRing);
+    if (!CAUSAL) ring_fill(0, kIdxRing);
     {
       // "tile -1" (V buffer kBufs-1) is multiplied by zero probabilities in the first iteration
       const uint4 z = make_uint4(0, 0, 0, 0);
       for (int i = tid; i < kVTile / 8; i += kThreads) ((uint4*)(lds_v + (kBufs - 1) * kVTile))[i] = z;
     }
     __syncthreads();
-    dma_tile(a.k, full_base(0), lds_k, dma_off_k);
-    dma_tile(a.v, full_base(0), lds_v, dma_off_v);
-    if (n_full > 1) dma_tile(a.k, full_base(1), lds_k + kKTile, dma_off_k);
+    dma_tile(src_k, full_base(0), lds_k, dma_off_k);
+    dma_tile(src_v, full_base(0), lds_v, dma_off_v);
+    if (n_full > 1) dma_tile(src_k, full_base(1), lds_k + kKTile, dma_off_k);
     dma_wait();
     __syncthreads();
 
@@ -370,7 +379,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
     float mc[kRG];
 #pragma unroll
     for (int rg = 0; rg < kRG; ++rg) {
-      m_ref[rg] = xor32_max(max16(s0[rg]));   // reference: first block's row maximum
+      if (!have_ref) m_ref[rg] = xor32_max(max16(s0[rg]));   // reference: the first block's row maximum
       mc[rg] = m_ref[rg] * c;
       p1[rg][0] = pack_bf16x8(0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f);
       p1[rg][1] = p1[rg][0];
@@ -379,7 +388,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
     // operand group g of an iteration (0..31): step g / 16; even = K operand (head-dim step g%16 / 2),
     // odd = V operand ((sp, d) = g%16 / 2).  Step 0: K(t, block 1), V(t-1, block 1); step 1:
     // K(t+1, block 0), V(t, block 0).
-    auto operand = [&](int gq, const uint16_t* k_t, const uint16_t* k_n, const uint16_t* v_p, const uint16_t* v_t) -> bf16x8 {
+    auto operand = [&](int gq, const uint16_t* k_t, const uint16_t* k_n, const uint16_t* v_p, const uint16_t* v_t) __attribute__((always_inline)) -> bf16x8 {
       const int step = gq >> 4, idx = (gq & 15) >> 1;
       if ((gq & 1) == 0) return k_operand(step == 0 ? k_t : k_n, step == 0 ? 1 : 0, idx);
       return v_operand(step == 0 ? v_p : v_t, step == 0 ? 1 : 0, idx >> 2, idx & 3);
@@ -400,7 +409,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
     int base_k = full_base(min(2, n_full - 1)), base_v = full_base(min(1, n_full - 1));
     // one tile; kb = t % kBufs is a compile-time constant (the loop below is unrolled kBufs times),
     // so that every LDS address is a loop-invariant per-lane register plus an immediate offset
-    auto tile_iteration = [&](auto KB, int t) {
+    auto tile_iteration = [&](auto KB, int t) __attribute__((always_inline)) {
       constexpr int kb = decltype(KB)::value;
       constexpr int kb1 = kb + 1 == kBufs ? 0 : kb + 1;
       constexpr int km1 = kb == 0 ? kBufs - 1 : kb - 1;
@@ -412,8 +421,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
       const uint16_t* v_p = lds_v + km1 * kVTile;    // V(t-1)
       if (!CAUSAL && t > 0 && (t & (kIdxRing / 2 - 1)) == 0) ring_fill(t + kIdxRing / 2, kIdxRing / 2);
       // K(t+2) replaces K(t-1), V(t+1) replaces V(t-2): both were last read before the previous barrier
-      if (t + 2 < n_full) dma_tile(a.k, base_k, lds_k + km1 * kKTile, dma_off_k);
-      if (t + 1 < n_full) dma_tile(a.v, base_v, lds_v + km2 * kVTile, dma_off_v);
+      if (t + 2 < n_full) dma_tile(src_k, base_k, lds_k + km1 * kKTile, dma_off_k);
+      if (t + 1 < n_full) dma_tile(src_v, base_v, lds_v + km2 * kVTile, dma_off_v);
       int base_k_next = 0, base_k_next_v = 0;
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -485,33 +494,56 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
     for (int rg = 0; rg < kRG; ++rg) bad = bad || !(l_run[rg] < kFastPathLimit);
     if (__builtin_amdgcn_ballot_w64(bad) != 0 && lane == 0) *lds_flag = 1;
     __syncthreads();
-    redo = *lds_flag != 0;
+    const bool redo = *lds_flag != 0;
     __syncthreads();
-  }
+    return !redo;
+  };
 
-  // ======================= careful redo of the full tiles (rare) =======================
-  if (redo) {
-    reset_state();
+  // ======================= the same tiles on the careful path =======================
+  const std::false_type kPoolPhase{};
+  const std::true_type kSelfPhase{};
+  auto careful_pool_full = [&]() __attribute__((always_inline)) {
     ring_fill(0, kIdxRing);
     __syncthreads();
-    for (int t = 0; t < n_full; ++t) {
-      if (!CAUSAL && t > 0 && (t & (kIdxRing / 2 - 1)) == 0) ring_fill(t + kIdxRing / 2, kIdxRing / 2);
-      careful_tile(full_base(t), kKvTile);
+    for (int t = 0; t < nf_pool; ++t) {
+      if (t > 0 && (t & (kIdxRing / 2 - 1)) == 0) {
+        __syncthreads();
+        ring_fill(t + kIdxRing / 2, kIdxRing / 2);
+        __syncthreads();
+      }
+      careful_tile(kPoolPhase, a.k, a.v, lds_idx[t & (kIdxRing - 1)], kKvTile);
     }
-  }
+  };
+  auto careful_pool_part = [&]() __attribute__((always_inline)) {   // tiles cut short by a slot's fill
+    for (int pt = 0; pt < np_pool; ++pt)
+      careful_tile(kPoolPhase, a.k, a.v, a.part_tile[2 * (wk.part_off + pt)], a.part_tile[2 * (wk.part_off + pt) + 1]);
+  };
+  auto careful_self = [&](int first_tile, int n_tiles) __attribute__((always_inline)) {
+    for (int t = first_tile; t < first_tile + n_tiles; ++t)
+      careful_tile(kSelfPhase, self_k, self_v, wk.kv_off + kKvTile * t, min(kKvTile, wk.kv_len - kKvTile * t));
+  };
 
-  // ======================= masked tiles, one at a time =======================
-  for (int pt = 0; pt < n_part; ++pt) {
-    int base, valid;
-    if (CAUSAL) {
-      const int off = kKvTile * (n_full + pt);
-      base = wk.kv_off + off;
-      valid = min(kKvTile, wk.kv_len - off);
-    } else {
-      base = a.part_tile[2 * (wk.part_off + pt)];
-      valid = a.part_tile[2 * (wk.part_off + pt) + 1];
+  // ======================= the phases =======================
+  if constexpr (kHasPool) {
+    const bool ok = nf_pool > 0 ? fast_phase(kPoolPhase, a.k, a.v, nf_pool, false) : true;
+    if (!ok) {
+      reset_state();
+      careful_pool_full();
     }
-    careful_tile(base, valid);
+    careful_pool_part();
+  }
+  if constexpr (kHasSelf) {
+    const bool have_ref = kHasPool && nf_pool + np_pool > 0;
+    const bool ok = nf_self > 0 ? fast_phase(kSelfPhase, self_k, self_v, nf_self, have_ref) : true;
+    if (!ok) {   // everything so far is spoilt: start again, carefully
+      reset_state();
+      if constexpr (kHasPool) {
+        careful_pool_full();
+        careful_pool_part();
+      }
+      careful_self(0, nf_self);
+    }
+    careful_self(nf_self, np_self);   // tiles on the diagonal
   }
 
   // ---- epilogue: normalise, LSE, store ----
@@ -521,31 +553,57 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
     if (row_ok[rg]) {
       const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
       const int head = g * G + head_j[rg];
-      const size_t orow = (size_t)(wk.out_row + tok_local[rg]) * a.q_heads + head;
-      float* op = a.out + orow * kHeadDim;
+      const float lse_val = l_tot > 0.f ? m_ref[rg] * a.scale + __logf(l_tot) : -INFINITY;
+      if (MODE == 2) {
+        // final output of the token, in the caller's layout and type
+        const size_t orow = (size_t)token[rg] * a.q_heads + head;
+        if (a.final_is_bf16) {
+          uint16_t* op = (uint16_t*)a.final_out + orow * kHeadDim;
 #pragma unroll
-      for (int d = 0; d < 4; ++d)
+          for (int d = 0; d < 4; ++d)
 #pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-          float4 val = make_float4(o[rg][d][4 * q4 + 0] * inv, o[rg][d][4 * q4 + 1] * inv, o[rg][d][4 * q4 + 2] * inv,
-                                   o[rg][d][4 * q4 + 3] * inv);
-          *(float4*)&op[32 * d + 8 * q4 + 4 * h] = val;
+            for (int q4 = 0; q4 < 4; ++q4) {
+              const bf16x4 b = __builtin_convertvector(
+                  f32x4{o[rg][d][4 * q4 + 0] * inv, o[rg][d][4 * q4 + 1] * inv, o[rg][d][4 * q4 + 2] * inv, o[rg][d][4 * q4 + 3] * inv}, bf16x4);
+              *(uint2*)&op[32 * d + 8 * q4 + 4 * h] = __builtin_bit_cast(uint2, b);
+            }
+        } else {
+          float* op = (float*)a.final_out + orow * kHeadDim;
+#pragma unroll
+          for (int d = 0; d < 4; ++d)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4)
+              *(float4*)&op[32 * d + 8 * q4 + 4 * h] = make_float4(o[rg][d][4 * q4 + 0] * inv, o[rg][d][4 * q4 + 1] * inv,
+                                                                    o[rg][d][4 * q4 + 2] * inv, o[rg][d][4 * q4 + 3] * inv);
         }
-      if (h == 0) a.lse[orow] = l_tot > 0.f ? m_ref[rg] * a.scale + __logf(l_tot) : -INFINITY;
+        if (h == 0 && a.final_lse) a.final_lse[orow] = lse_val;
+      } else {
+        const size_t orow = (size_t)(wk.out_row + tok_local[rg]) * a.q_heads + head;
+        float* op = a.out + orow * kHeadDim;
+#pragma unroll
+        for (int d = 0; d < 4; ++d)
+#pragma unroll
+          for (int q4 = 0; q4 < 4; ++q4) {
+            float4 val = make_float4(o[rg][d][4 * q4 + 0] * inv, o[rg][d][4 * q4 + 1] * inv, o[rg][d][4 * q4 + 2] * inv,
+                                     o[rg][d][4 * q4 + 3] * inv);
+            *(float4*)&op[32 * d + 8 * q4 + 4 * h] = val;
+          }
+        if (h == 0) a.lse[orow] = lse_val;
+      }
     }
   }
 }
 
-template <bool CAUSAL>
+template <int MODE>
 tl_status launch_row_tiles(const AttnArgs& a, int n_work, hipStream_t st) {
   if (n_work == 0) return TL_OK;
   const dim3 grid((unsigned)n_work * a.kv_heads), block(kThreads);
   if (get_option_vread() == 0) {
-    auto kern = row_tile_attn_kernel<CAUSAL, 0>;
+    auto kern = row_tile_attn_kernel<MODE, 0>;
     TL_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes));
     hipLaunchKernelGGL(kern, grid, block, kLdsBytes, st, a);
   } else {
-    auto kern = row_tile_attn_kernel<CAUSAL, 1>;
+    auto kern = row_tile_attn_kernel<MODE, 1>;
     TL_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes));
     hipLaunchKernelGGL(kern, grid, block, kLdsBytes, st, a);
   }
@@ -555,7 +613,8 @@ tl_status launch_row_tiles(const AttnArgs& a, int n_work, hipStream_t st) {
 
 }  // namespace
 
-tl_status launch_pool_row_tiles(const AttnArgs& a, int n_work, hipStream_t st) { return launch_row_tiles<false>(a, n_work, st); }
-tl_status launch_causal_row_tiles(const AttnArgs& a, int n_work, hipStream_t st) { return launch_row_tiles<true>(a, n_work, st); }
+tl_status launch_pool_row_tiles(const AttnArgs& a, int n_work, hipStream_t st) { return launch_row_tiles<0>(a, n_work, st); }
+tl_status launch_causal_row_tiles(const AttnArgs& a, int n_work, hipStream_t st) { return launch_row_tiles<1>(a, n_work, st); }
+tl_status launch_fused_row_tiles(const AttnArgs& a, int n_work, hipStream_t st) { return launch_row_tiles<2>(a, n_work, st); }
 
 }  // namespace tl

@@ -73,15 +73,16 @@ struct tl_plan {
   tl_plan_info info;
   std::vector<int32_t> item_row_base, item_tok_ptr, item_tokens, item_slot_ptr, item_slots;
   std::vector<int32_t> merge_ptr, merge_rows;
-  std::vector<tl::Work> tiles, units, ctiles;
+  std::vector<tl::Work> tiles, units, ctiles, ftiles;   // ftiles: fused rows (pool tiles + causal block in one pass)
+  std::vector<int32_t> merge_tok;  // tokens that tl_merge writes (all but the fused ones)
   std::vector<int32_t> tok;      // token index array referenced by Work::tok_off
   std::vector<int32_t> tile_base;  // Work::full_off
   std::vector<int32_t> part_tile;  // Work::part_off, pairs (first kv row, valid tokens)
   // device copies (made on first use)
   bool on_device;
   void* blob;
-  tl::Work *d_tiles, *d_units, *d_ctiles;
-  int32_t *d_tok, *d_slots, *d_merge_ptr, *d_merge_rows, *d_tile_base, *d_part_tile;
+  tl::Work *d_tiles, *d_units, *d_ctiles, *d_ftiles;
+  int32_t *d_tok, *d_slots, *d_merge_ptr, *d_merge_rows, *d_tile_base, *d_part_tile, *d_merge_tok;
 };
 
 namespace tl {

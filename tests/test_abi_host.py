@@ -89,8 +89,9 @@ def test_release_and_lru_eviction():
     B.tl_pool_destroy(pool)
 
 
-def _check_plan_covers(b, plan, flags):
+def _check_plan_covers(b, plan, flags, fused_req=()):
     info = B.tl_plan_get_info(plan)
+    fused_tok = set(t for r in fused_req for t in range(b.req_row_ptr[r], b.req_row_ptr[r + 1]))
     ex = B.tl_plan_export(plan)
     slots = B.tl_pool_lookup(plan_pool[0], b.seg_ids)
     T = b.n_tokens
@@ -110,7 +111,7 @@ def _check_plan_covers(b, plan, flags):
     for r in range(b.n_req):
         want = sorted(int(s) for s in slots[b.req_seg_ptr[r]:b.req_seg_ptr[r + 1]])
         for t in range(b.req_row_ptr[r], b.req_row_ptr[r + 1]):
-            assert sorted(got[t]) == want, (r, t)
+            assert sorted(got[t]) == ([] if r in fused_req else want), (r, t)
     n_item_rows = len(rows_seen)
     assert rows_seen == set(range(n_item_rows))
     self_rows = T if flags & B.TL_PLAN_SELF_BLOCK else 0
@@ -118,16 +119,18 @@ def _check_plan_covers(b, plan, flags):
     assert info.self_row_base == (n_item_rows if self_rows else -1)
     # merge lists: every partial row exactly once, under its own token
     mp, mr = ex["merge_ptr"], ex["merge_rows"]
-    assert mp[0] == 0 and mp[-1] == len(mr) == info.n_merge_entries == info.n_partial_rows
-    assert sorted(mr.tolist()) == list(range(info.n_partial_rows))
+    assert mp[0] == 0 and mp[-1] == len(mr) == info.n_merge_entries == info.n_partial_rows - len(fused_tok)
+    assert sorted(mr.tolist()) == [x for x in range(info.n_partial_rows) if x - info.self_row_base not in fused_tok]
     row_tok = {}
     for i in range(info.n_items):
         toks = ex["item_tokens"][ex["item_tok_ptr"][i]:ex["item_tok_ptr"][i + 1]]
         for jpos, t in enumerate(toks):
             row_tok[int(ex["item_row_base"][i]) + jpos] = int(t)
     for t in range(T):
+        assert t not in fused_tok or mp[t] == mp[t + 1]          # a fused token has nothing to merge
         for row in mr[mp[t]:mp[t + 1]]:
             assert row_tok.get(int(row), int(row) - info.self_row_base) == t
+    assert info.n_fused_tokens == len(fused_tok)
     # counters
     fill_of = dict(zip(b.pool_ids.tolist(), b.pool_fills.tolist()))
     pairs = sum(int(b.req_row_ptr[r + 1] - b.req_row_ptr[r]) * fill_of[int(s)]
@@ -154,6 +157,31 @@ def test_plan_covers_every_pair_exactly_once(maker, kw):
             plan = B.tl_plan_create(plan_pool[0], b.q_heads, b.req_row_ptr, b.req_seg_ptr, b.seg_ids, flags, split)
             _check_plan_covers(b, plan, flags)
             B.tl_plan_destroy(plan)
+    B.tl_pool_destroy(plan_pool[0])
+
+
+def test_fused_rows_leave_the_three_step_path():
+    """With TL_PLAN_FUSE_ROWS a request with >= 256 query rows per kv head is handled by
+    tl_fused_attn alone: it is in no work item, has no causal tile and nothing to merge; the
+    other requests of the batch are planned as before."""
+    b = wl.prefill(seed=9, n_req=5, new_tokens=100, lo=300, hi=900, seg_len=128, n_slots=64, n_shared=2)
+    # G = 4: 100 tokens = 400 rows (fused), 63 tokens = 252 rows (not), 64 tokens = 256 rows (fused), 3 tokens, 0 tokens
+    b.req_row_ptr = np.concatenate([[0], np.cumsum([100, 63, 64, 3, 0])]).astype(np.int32)
+    plan_pool[0] = _pool_for(b)
+    flags = B.TL_PLAN_SELF_BLOCK | B.TL_PLAN_FUSE_ROWS
+    plan = B.tl_plan_create(plan_pool[0], b.q_heads, b.req_row_ptr, b.req_seg_ptr, b.seg_ids, flags)
+    info = _check_plan_covers(b, plan, flags, fused_req=(0, 2))
+    assert info.n_fused_tiles == 2 + 1 and info.n_fused_tokens == 164       # row tiles of 64 tokens
+    assert info.n_causal_tiles == 1 + 1                                      # requests 1 and 3 only
+    B.tl_plan_destroy(plan)
+    with pytest.raises(B.TokenLakeError) as e:
+        B.tl_plan_create(plan_pool[0], b.q_heads, b.req_row_ptr, b.req_seg_ptr, b.seg_ids, B.TL_PLAN_FUSE_ROWS)
+    assert e.value.status == B.TL_EINVAL                                     # needs the self block
+    # without the flag nothing is fused
+    plan = B.tl_plan_create(plan_pool[0], b.q_heads, b.req_row_ptr, b.req_seg_ptr, b.seg_ids, B.TL_PLAN_SELF_BLOCK)
+    info = _check_plan_covers(b, plan, B.TL_PLAN_SELF_BLOCK)
+    assert info.n_fused_tiles == 0
+    B.tl_plan_destroy(plan)
     B.tl_pool_destroy(plan_pool[0])
 
 

@@ -328,6 +328,58 @@ def test_full_multiturn_config_sampled(turn):
     run.close()
 
 
+# ---- one-pass (fused) rows ----------------------------------------------------------------------
+def test_fused_rows_small_shapes_every_row():
+    """TL_PLAN_FUSE_ROWS: requests with >= 256 rows per kv head go through tl_fused_attn alone
+    (pool tiles, then their own new tokens, final output written by the kernel); the others
+    still take the three steps.  Every row of every request against the oracle, fp32 and bf16
+    outputs, with ragged fills, an empty prefix, a request below the threshold and one with
+    no new tokens in the same batch."""
+    _say("fused rows, small shapes")
+    for seed, kw in [(41, dict(n_req=4, new_tokens=100, lo=300, hi=900, seg_len=128, n_slots=64, n_shared=2)),
+                     (42, dict(n_req=3, new_tokens=200, lo=64, hi=200, seg_len=64, n_slots=32, n_shared=0)),
+                     (43, dict(n_req=5, new_tokens=70, lo=1000, hi=3000, seg_len=256, n_slots=80, n_shared=3, hq=16, hkv=2))]:
+        b = wl.prefill(seed=seed, **kw)
+        lens = [int(x) for x in np.diff(b.req_row_ptr)]
+        lens[-1] = 5                     # stays on the three-step path
+        if len(lens) > 3:
+            lens[1] = 0                  # no new tokens
+        b.req_row_ptr = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+        if seed == 42:                   # first request loses its prefix: self block only
+            keep = [b.seg_ids[b.req_seg_ptr[r]:b.req_seg_ptr[r + 1]] for r in range(b.n_req)]
+            keep[0] = keep[0][:0]
+            b.seg_ids = np.concatenate(keep)
+            b.req_seg_ptr = np.concatenate([[0], np.cumsum([len(k) for k in keep])]).astype(np.int32)
+        for out_bf16 in (False, True):
+            run = H.run_gpu(b, fuse=True, out_bf16=out_bf16)
+            assert run.info.n_fused_tiles > 0 and run.info.n_fused_tokens == sum(x for x in lens if x * (b.q_heads // b.kv_heads) >= 256)
+            _check_all_requests(run)
+            run.close()
+
+
+def test_fused_rows_peaked_and_far_scores():
+    _say("fused rows, peaked / far scores")
+    for kw in [dict(k_gain=4.0, v_offset_mod=3), dict(k_boost=(2, 1 << 30, 32.0), v_offset_mod=3),
+               dict(k_boost=(0, 1, 32.0), v_offset_mod=3)]:
+        b = wl.prefill(seed=23, n_req=2, new_tokens=96, lo=700, hi=1100, seg_len=128, n_slots=32, n_shared=1, **kw)
+        run = H.run_gpu(b, fuse=True)
+        assert run.info.n_fused_tokens == 192 and run.info.n_tiles == 0
+        _check_all_requests(run)
+        run.close()
+
+
+def test_fused_and_three_step_paths_agree_on_full_configs():
+    _say("fused rows, full prefill / multi-turn / long context")
+    for b, reqs, rows in [(wl.prefill(), None, 6), (wl.multiturn(turn=7), [0, 37, 63], 5), (wl.longctx(), [2], 4)]:
+        run = H.run_gpu(b, fuse=True)
+        assert run.info.n_fused_tokens == b.n_tokens and run.info.n_merge_entries == 0
+        if reqs is None:
+            L = b.prefix_tokens()
+            reqs = sorted({int(np.argmin(L)), int(np.argmax(L)), 0})
+        _check_all_requests(run, rows_per_req=rows, seed=1, reqs=reqs)
+        run.close()
+
+
 def test_append_rows_grow_chains_like_the_oracle():
     """tl_pool_append against the oracle's append: same slots, same fills, same bytes in the
     pool after every call (bit-exact), and attention over the grown chains within tolerance.

@@ -53,13 +53,15 @@ def device_pool(batch: wl.Batch, device="cuda", poison: bool = True):
 
 
 def run_gpu(batch: wl.Batch, flags=None, split_segments: int = 0, out_bf16: bool = False, poison: bool = True,
-            pool_tensors=None) -> GpuRun:
+            pool_tensors=None, fuse: bool = False) -> GpuRun:
     dev = "cuda"
     pk, pv = pool_tensors if pool_tensors is not None else device_pool(batch, dev, poison)
     pool = B.tl_pool_create(batch.n_slots, batch.seg_len, batch.kv_heads, batch.head_dim, pk, pv)
     B.tl_pool_adopt(pool, batch.pool_ids, batch.pool_slots, batch.pool_fills)
     if flags is None:
         flags = B.TL_PLAN_SELF_BLOCK if batch.self_block else 0
+    if fuse:
+        flags |= B.TL_PLAN_FUSE_ROWS
     plan = B.tl_plan_create(pool, batch.q_heads, batch.req_row_ptr, batch.req_seg_ptr, batch.seg_ids, flags,
                             split_segments)
     info = B.tl_plan_get_info(plan)
@@ -77,6 +79,8 @@ def run_gpu(batch: wl.Batch, flags=None, split_segments: int = 0, out_bf16: bool
     if flags & B.TL_PLAN_SELF_BLOCK:
         B.tl_causal_block(plan, q, kn, vn, batch.scale, outp, lsep)
     B.tl_merge(plan, outp, lsep, out, out_bf16, lse)
+    if flags & B.TL_PLAN_FUSE_ROWS:
+        B.tl_fused_attn(pool, plan, q, kn, vn, batch.scale, out, out_bf16, lse)
     torch.cuda.synchronize()
     return GpuRun(batch, pool, plan, info, q, kn, vn, pk, pv, outp, lsep, out, lse)
 
