@@ -490,3 +490,24 @@ def test_append_rows_grow_chains_like_the_oracle():
         assert np.abs(got_o - want_o).max() <= H.TOL_O and np.abs(got_l - want_l).max() <= H.TOL_LSE
     B.tl_plan_destroy(plan)
     B.tl_pool_destroy(pool)
+
+
+@pytest.mark.parametrize("hq,hkv", [(4, 4), (8, 4), (32, 1), (16, 16)])
+def test_head_group_sizes_from_mha_to_one_kv_head(hq, hkv):
+    """The paper's own model is multi-head (one kv head per q head); the named configurations are
+    grouped-query with 4 or 8 q heads per kv head.  Every path (row tiles, one-pass rows, split-K
+    units) on both extremes, every row against the oracle."""
+    _say("head groups hq=%d hkv=%d" % (hq, hkv))
+    g = hq // hkv
+    n_new = max(2 * 256 // g + 3, 20)          # a little over two row tiles per request
+    b = wl.prefill(seed=51, n_req=2, new_tokens=n_new, lo=200, hi=500, seg_len=64, n_slots=24, n_shared=1, hq=hq, hkv=hkv)
+    for fuse in (False, True):
+        run = H.run_gpu(b, fuse=fuse)
+        assert (run.info.n_fused_tiles > 0) == fuse and (run.info.n_tiles > 0) != fuse
+        _check_all_requests(run)
+        run.close()
+    d = wl.decode(seed=52, n_req=5, median=300, cap=900, seg_len=64, hq=hq, hkv=hkv)
+    run = H.run_gpu(d)
+    assert (run.info.n_units > 0) == (g <= 16)     # a token's rows beyond 16 per kv head go to row tiles
+    _check_all_requests(run)
+    run.close()
