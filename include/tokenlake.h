@@ -138,7 +138,7 @@ typedef struct tl_plan tl_plan;
 enum {
   TL_PLAN_SELF_BLOCK = 1, /* reserve partial rows for tl_causal_block and merge them   */
   TL_PLAN_NO_SHARING = 2, /* do not group requests: one item chain per request         */
-  TL_PLAN_FUSE_ROWS = 4   /* requests with at least 256 query rows per kv head (new
+  TL_PLAN_FUSE_ROWS = 4   /* requests with at least 512 query rows per kv head (new
                              tokens x q-heads per kv-head) leave the three-step path: one
                              pass of tl_fused_attn over their whole slot list and their own
                              new tokens writes their final output.  Such rows have a single

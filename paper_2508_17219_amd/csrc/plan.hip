@@ -81,12 +81,11 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
     auto ntok_of = [&](int32_t r) { return req_row_ptr[r + 1] - req_row_ptr[r]; };
 
     // ---- group requests along shared runs ----------------------------------------------
-    // requests whose rows fill whole row tiles by themselves gain nothing from sharing a run
-    // with others (the work is bound by the matrix unit, not by KV traffic) and lose a partial
-    // per row: with TL_PLAN_FUSE_ROWS they are set aside for the one-pass kernel
+    // requests with enough rows of their own gain nothing from sharing a run with others (the
+    // work is bound by the matrix unit, not by KV traffic) and lose a partial per row: with TL_PLAN_FUSE_ROWS they are set aside for the one-pass kernel
     std::vector<char> fused(n_req, 0);
     if (flags & TL_PLAN_FUSE_ROWS)
-      for (int32_t r = 0; r < n_req; ++r) fused[r] = (int64_t)ntok_of(r) * G >= kRowTile;
+      for (int32_t r = 0; r < n_req; ++r) fused[r] = (int64_t)ntok_of(r) * G >= kFuseRows;
     std::vector<RawItem> raw;
     std::vector<int32_t> live;
     for (int32_t r = 0; r < n_req; ++r)

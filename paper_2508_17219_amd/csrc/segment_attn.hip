@@ -215,7 +215,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
 #pragma unroll
     for (int u = 0; u < kDmaPerWave; ++u) {
       const unsigned dst = lds_base_addr + (unsigned)((tile - lds) + kWaves * u * 4 * kHeadDim) * 2u + dma_wave_off;
-      asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(trow + off[u]), "s"(dst) : "memory");
+      // address = wave-uniform 64-bit tile base (scalar registers) + this lane's constant 32-bit offset
+      asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %2" ::"v"(off[u]), "s"(dst), "s"(trow) : "memory");
     }
   };
   // wait for all of this wave's direct loads (vmcnt(0); the other counters are left alone so that

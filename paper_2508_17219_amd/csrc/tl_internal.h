@@ -32,6 +32,11 @@ constexpr int kHeadDim = 128;
 constexpr int kKvTile = 64;      // kv tokens per LDS tile of the row-tile kernel
 constexpr int kRowTile = 256;    // query rows (token x head-in-group) per workgroup
 constexpr int kUnitRows = 16;    // max rows per kv head of a split-K unit
+// A request is planned for the one-pass kernel from this many query rows per kv head: it then
+// does 512 flop per KV byte it reads by itself (4 * 128 flop per row and 512-byte K+V token),
+// about twice the machine balance of the measured rooflines (1.2 PFLOP/s : 6 TB/s = 200), so
+// that giving up the sharing of hot segments between requests cannot make it bandwidth-bound.
+constexpr int kFuseRows = 2 * kRowTile;
 
 // One unit of kernel work.  Its query tokens are tok[tok_off .. tok_off+n_tok) (batch token
 // indices), its partial rows out_row .. out_row+n_tok-1.

@@ -161,18 +161,18 @@ def test_plan_covers_every_pair_exactly_once(maker, kw):
 
 
 def test_fused_rows_leave_the_three_step_path():
-    """With TL_PLAN_FUSE_ROWS a request with >= 256 query rows per kv head is handled by
+    """With TL_PLAN_FUSE_ROWS a request with >= 512 query rows per kv head is handled by
     tl_fused_attn alone: it is in no work item, has no causal tile and nothing to merge; the
     other requests of the batch are planned as before."""
-    b = wl.prefill(seed=9, n_req=5, new_tokens=100, lo=300, hi=900, seg_len=128, n_slots=64, n_shared=2)
-    # G = 4: 100 tokens = 400 rows (fused), 63 tokens = 252 rows (not), 64 tokens = 256 rows (fused), 3 tokens, 0 tokens
-    b.req_row_ptr = np.concatenate([[0], np.cumsum([100, 63, 64, 3, 0])]).astype(np.int32)
+    b = wl.prefill(seed=9, n_req=5, new_tokens=200, lo=300, hi=900, seg_len=128, n_slots=64, n_shared=2)
+    # G = 4: 200 tokens = 800 rows (fused), 127 tokens = 508 rows (not), 128 tokens = 512 rows (fused), 3 tokens, 0 tokens
+    b.req_row_ptr = np.concatenate([[0], np.cumsum([200, 127, 128, 3, 0])]).astype(np.int32)
     plan_pool[0] = _pool_for(b)
     flags = B.TL_PLAN_SELF_BLOCK | B.TL_PLAN_FUSE_ROWS
     plan = B.tl_plan_create(plan_pool[0], b.q_heads, b.req_row_ptr, b.req_seg_ptr, b.seg_ids, flags)
     info = _check_plan_covers(b, plan, flags, fused_req=(0, 2))
-    assert info.n_fused_tiles == 2 + 1 and info.n_fused_tokens == 164       # row tiles of 64 tokens
-    assert info.n_causal_tiles == 1 + 1                                      # requests 1 and 3 only
+    assert info.n_fused_tiles == 4 + 2 and info.n_fused_tokens == 328       # row tiles of 64 tokens
+    assert info.n_causal_tiles == 2 + 1                                      # requests 1 and 3 only
     B.tl_plan_destroy(plan)
     with pytest.raises(B.TokenLakeError) as e:
         B.tl_plan_create(plan_pool[0], b.q_heads, b.req_row_ptr, b.req_seg_ptr, b.seg_ids, B.TL_PLAN_FUSE_ROWS)

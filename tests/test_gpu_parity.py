@@ -330,13 +330,13 @@ def test_full_multiturn_config_sampled(turn):
 
 # ---- one-pass (fused) rows ----------------------------------------------------------------------
 def test_fused_rows_small_shapes_every_row():
-    """TL_PLAN_FUSE_ROWS: requests with >= 256 rows per kv head go through tl_fused_attn alone
+    """TL_PLAN_FUSE_ROWS: requests with >= 512 rows per kv head go through tl_fused_attn alone
     (pool tiles, then their own new tokens, final output written by the kernel); the others
     still take the three steps.  Every row of every request against the oracle, fp32 and bf16
     outputs, with ragged fills, an empty prefix, a request below the threshold and one with
     no new tokens in the same batch."""
     _say("fused rows, small shapes")
-    for seed, kw in [(41, dict(n_req=4, new_tokens=100, lo=300, hi=900, seg_len=128, n_slots=64, n_shared=2)),
+    for seed, kw in [(41, dict(n_req=4, new_tokens=150, lo=300, hi=900, seg_len=128, n_slots=64, n_shared=2)),
                      (42, dict(n_req=3, new_tokens=200, lo=64, hi=200, seg_len=64, n_slots=32, n_shared=0)),
                      (43, dict(n_req=5, new_tokens=70, lo=1000, hi=3000, seg_len=256, n_slots=80, n_shared=3, hq=16, hkv=2))]:
         b = wl.prefill(seed=seed, **kw)
@@ -352,7 +352,7 @@ def test_fused_rows_small_shapes_every_row():
             b.req_seg_ptr = np.concatenate([[0], np.cumsum([len(k) for k in keep])]).astype(np.int32)
         for out_bf16 in (False, True):
             run = H.run_gpu(b, fuse=True, out_bf16=out_bf16)
-            assert run.info.n_fused_tiles > 0 and run.info.n_fused_tokens == sum(x for x in lens if x * (b.q_heads // b.kv_heads) >= 256)
+            assert run.info.n_fused_tiles > 0 and run.info.n_fused_tokens == sum(x for x in lens if x * (b.q_heads // b.kv_heads) >= 512)
             _check_all_requests(run)
             run.close()
 
@@ -361,9 +361,9 @@ def test_fused_rows_peaked_and_far_scores():
     _say("fused rows, peaked / far scores")
     for kw in [dict(k_gain=4.0, v_offset_mod=3), dict(k_boost=(2, 1 << 30, 32.0), v_offset_mod=3),
                dict(k_boost=(0, 1, 32.0), v_offset_mod=3)]:
-        b = wl.prefill(seed=23, n_req=2, new_tokens=96, lo=700, hi=1100, seg_len=128, n_slots=32, n_shared=1, **kw)
+        b = wl.prefill(seed=23, n_req=2, new_tokens=160, lo=700, hi=1100, seg_len=128, n_slots=32, n_shared=1, **kw)
         run = H.run_gpu(b, fuse=True)
-        assert run.info.n_fused_tokens == 192 and run.info.n_tiles == 0
+        assert run.info.n_fused_tokens == 320 and run.info.n_tiles == 0
         _check_all_requests(run)
         run.close()
 
@@ -499,7 +499,7 @@ def test_head_group_sizes_from_mha_to_one_kv_head(hq, hkv):
     units) on both extremes, every row against the oracle."""
     _say("head groups hq=%d hkv=%d" % (hq, hkv))
     g = hq // hkv
-    n_new = max(2 * 256 // g + 3, 20)          # a little over two row tiles per request
+    n_new = max(2 * 256 // g + 3, 20)          # a little over two row tiles per request: enough for the one-pass plan
     b = wl.prefill(seed=51, n_req=2, new_tokens=n_new, lo=200, hi=500, seg_len=64, n_slots=24, n_shared=1, hq=hq, hkv=hkv)
     for fuse in (False, True):
         run = H.run_gpu(b, fuse=fuse)
