@@ -180,8 +180,8 @@ def cpu_baseline(batch, budget_s=15.0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="prefill", choices=["prefill", "decode", "longctx", "multiturn", "tiny"])
     ap.add_argument("--split-segments", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
