@@ -67,11 +67,11 @@ def _setup(batch, torch, B):
     return pk, pv, pool
 
 
-def run_workload(batch, steps, warmup, torch, B, split_segments=0, fuse=True):
+def run_workload(batch, steps, warmup, torch, B, split_segments=0, fuse=True, extra_flags=0):
     """Times `steps` passes of the whole path; returns timings and the plan's work counters."""
     pk, pv, pool = _setup(batch, torch, B)
     plan = B.tl_plan_create(pool, batch.q_heads, batch.req_row_ptr, batch.req_seg_ptr, batch.seg_ids,
-                            B.TL_PLAN_SELF_BLOCK | (B.TL_PLAN_FUSE_ROWS if fuse else 0), split_segments)
+                            B.TL_PLAN_SELF_BLOCK | (B.TL_PLAN_FUSE_ROWS if fuse else 0) | extra_flags, split_segments)
     info = B.tl_plan_get_info(plan)
     dev = "cuda"
     q, kn, vn = batch.q(dev), batch.k_new(dev), batch.v_new(dev)
@@ -185,6 +185,7 @@ def main():
     ap.add_argument("--workload", default="prefill", choices=["prefill", "decode", "longctx", "multiturn", "tiny"])
     ap.add_argument("--split-segments", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-sharing", action="store_true", help="plan with TL_PLAN_NO_SHARING (one item chain per request)")
     ap.add_argument("--three-step", action="store_true",
                     help="plan without TL_PLAN_FUSE_ROWS: every request goes through partials and the merge")
     ap.add_argument("--no-decode", action="store_true", help="skip the appended decode measurement")
@@ -209,7 +210,8 @@ def main():
     maker = {"prefill": wl.prefill, "decode": wl.decode, "longctx": wl.longctx, "tiny": wl.tiny,
              "multiturn": lambda: wl.multiturn(turn=7)}[args.workload]
     batch = maker()
-    res = run_workload(batch, args.steps, args.warmup, torch, B, args.split_segments, fuse=not args.three_step)
+    res = run_workload(batch, args.steps, args.warmup, torch, B, args.split_segments, fuse=not args.three_step,
+                       extra_flags=B.TL_PLAN_NO_SHARING if args.no_sharing else 0)
     work = algorithmic_work(batch, res["info"])
     tok_s = batch.n_tokens / (res["ms_per_step"] * 1e-3)
 

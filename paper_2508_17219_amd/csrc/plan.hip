@@ -255,9 +255,10 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
     std::stable_sort(p->tiles.begin(), p->tiles.end(), by_len);
     std::stable_sort(p->units.begin(), p->units.end(), by_len);
     std::stable_sort(p->ctiles.begin(), p->ctiles.end(), by_len);
-    std::stable_sort(p->ftiles.begin(), p->ftiles.end(), [](const Work& x, const Work& y) {
-      return x.n_full + x.n_part + x.kv_len / kKvTile > y.n_full + y.n_part + y.kv_len / kKvTile;
-    });
+    // one-pass rows: by the request's pool length only, so that the row tiles of a request stay
+    // next to each other in the launch order, run at the same time and share its KV through L2
+    std::stable_sort(p->ftiles.begin(), p->ftiles.end(),
+                     [](const Work& x, const Work& y) { return x.n_full + x.n_part > y.n_full + y.n_part; });
 
     // ---- merge lists --------------------------------------------------------------------------
     p->merge_ptr.assign(T + 1, 0);
