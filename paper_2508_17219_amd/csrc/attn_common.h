@@ -15,12 +15,11 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-// LDS rows are padded from 128 bf16.  K rows: 136 (272 B), so that the 16-byte reads of 16
-// consecutive rows fall in different banks.  V rows of the row-tile kernel: 160 (320 B =
-// 64 mod 256), so that the 4 rows x 64 B which 32 lanes fetch in one transposing read cover
-// all banks once; V rows of the split-K kernel: 144 (288 B = 32 mod 256) for its 8 rows x 32 B.
+// LDS rows of the split-K unit kernel are padded from 128 bf16.  K rows: 136 (272 B), so that the
+// 16-byte reads of 16 consecutive rows fall in different banks; V rows: 144 (288 B = 32 mod 256)
+// for the 8 rows x 32 B of its transposing reads.  (The row-tile kernel keeps unpadded rows and
+// swizzles 16-byte chunks instead, because direct global->LDS loads write contiguously.)
 constexpr int kLdsStride = 136;
-constexpr int kVStrideTile = 160;
 constexpr int kVStrideUnit = 144;
 
 struct AttnArgs {

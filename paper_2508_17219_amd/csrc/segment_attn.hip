@@ -175,9 +175,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
       lds_idx[i & (kIdxRing - 1)] = a.tile_base[wk.full_off + i];
   };
 
-  // ---- global <-> LDS staging: 4 chunks of 16 B per thread per tile, for K and for V ----
-  // chunk i of a thread: tile row (tid >> 4) + 16 i, 16-byte column tid & 15
-  // (plain scalars, not arrays: the staged chunks must live in registers across iterations)
+  // ---- careful path staging (global -> registers -> LDS): kChunks chunks of 16 B per thread per
+  // tile, for K and for V; chunk i of a thread: tile row (tid >> 4) + kChunkRows i, 16-byte column tid & 15
   const size_t kv_row = (size_t)a.kv_heads * kHeadDim;
   const int c_tr = tid >> 4, c_part = tid & 15;
   // address = (tile's first row: workgroup-uniform, 64-bit, scalar registers) + (this thread's
@@ -196,9 +195,9 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
     const int r_ = c_tr + kChunkRows * i;
     return (uint4*)&tile[r_ * kVS + 8 * (c_part ^ (4 * (r_ & 3)))];
   };
-  // direct global -> LDS load of a whole tile: wave w issues instructions w and w + 8 (of 16), each
-  // filling rows 4 i .. 4 i + 3; lane L lands at row 4 i + L / 16, position L % 16, so it fetches
-  // the logical chunk that belongs there
+  // ---- fast path staging: direct global -> LDS load of a whole tile.  A tile is 16 wave
+  // instructions; wave w issues instructions w + kWaves u, instruction i filling rows 4 i .. 4 i + 3;
+  // lane L lands at row 4 i + L / 16, position L % 16, so it fetches the logical chunk that belongs there
   unsigned dma_off_k[kDmaPerWave], dma_off_v[kDmaPerWave];
 #pragma unroll
   for (int u = 0; u < kDmaPerWave; ++u) {
@@ -252,7 +251,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
       return __builtin_bit_cast(bf16x8, t);
     }
   };
-  // scores of block hb of the K tile at kt, both row groups (each K operand is used twice)
+  // scores of block hb of the K tile at kt, for every row group of the wave
   auto qk_block = [&](const uint16_t* kt, int hb, f32x16 (&s)[kRG]) {
     const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
