@@ -357,6 +357,20 @@ def test_fused_rows_small_shapes_every_row():
             run.close()
 
 
+def test_only_short_segments_no_full_tile_anywhere():
+    """Every segment holds fewer than 64 tokens, so no pool tile is full: the pipelined path never
+    runs on the pool (only on the new tokens of the one-pass rows), the masked path does all of it."""
+    _say("segments shorter than a tile")
+    b = wl.prefill(seed=44, n_req=3, new_tokens=140, lo=600, hi=1200, seg_len=128, n_slots=48, n_shared=2)
+    rng = np.random.default_rng(44)
+    b.pool_fills = rng.integers(1, 64, size=len(b.pool_fills)).astype(np.int32)
+    for fuse in (False, True):
+        run = H.run_gpu(b, fuse=fuse)
+        assert (run.info.n_fused_tokens > 0) == fuse
+        _check_all_requests(run)
+        run.close()
+
+
 def test_fused_rows_peaked_and_far_scores():
     _say("fused rows, peaked / far scores")
     for kw in [dict(k_gain=4.0, v_offset_mod=3), dict(k_boost=(2, 1 << 30, 32.0), v_offset_mod=3),
