@@ -230,8 +230,13 @@ tl_status tl_fused_attn(const tl_pool* pool, tl_plan* plan, const void* q_dev, c
 tl_status tl_merge(tl_plan* plan, const float* out_partial, const float* lse, void* out_dev,
                    int32_t out_is_bf16, float* lse_out, void* stream);
 
-/* Kernel-variant switch for experiments and A/B tests (0 = default).  Returns TL_EINVAL
- * for an unknown knob.  Knobs: "vread" (0 = transposing LDS reads, 1 = scalar LDS reads). */
+/* Switches for experiments and tests (process-wide).  Returns TL_EINVAL for an unknown knob
+ * or a value out of range.  Knobs:
+ *   "vread"          0 (default) = transposing LDS reads of V, 1 = scalar LDS reads;
+ *   "compute_units"  the number of CUs the plan builder fills (default 256, MI355X; 0..4096):
+ *                    a batch with fewer row-tile workgroups than this gets KV-chunked work
+ *                    items instead of one-pass rows.  0 turns that off (tests of the one-pass
+ *                    kernel on small shapes use it). */
 tl_status tl_set_option(const char* knob, int32_t value);
 
 /* ------------------------------------------------------------------------------------

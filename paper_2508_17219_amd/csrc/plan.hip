@@ -83,9 +83,18 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
     // ---- group requests along shared runs ----------------------------------------------
     // requests with enough rows of their own gain nothing from sharing a run with others (the
     // work is bound by the matrix unit, not by KV traffic) and lose a partial per row: with TL_PLAN_FUSE_ROWS they are set aside for the one-pass kernel
+    const int tok_tile = kRowTile / G;
+    const int64_t n_cu = get_option_compute_units();
     std::vector<char> fused(n_req, 0);
-    if (flags & TL_PLAN_FUSE_ROWS)
+    if (flags & TL_PLAN_FUSE_ROWS) {
       for (int32_t r = 0; r < n_req; ++r) fused[r] = (int64_t)ntok_of(r) * G >= kFuseRows;
+      // A one-pass row tile cannot be cut along its KV: with fewer row-tile workgroups than CUs in
+      // the whole batch (one long prompt, say) the three-step plan, which can (see below), is used
+      int64_t wgs = 0;
+      for (int32_t r = 0; r < n_req; ++r)
+        if (ntok_of(r) > 0) wgs += (int64_t)((ntok_of(r) + tok_tile - 1) / tok_tile) * pool->kv_heads;
+      if (wgs < n_cu) std::fill(fused.begin(), fused.end(), 0);
+    }
     std::vector<RawItem> raw;
     std::vector<int32_t> live;
     for (int32_t r = 0; r < n_req; ++r)
@@ -134,7 +143,6 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
     }
 
     // ---- final items, work lists ----------------------------------------------------------
-    const int tok_tile = kRowTile / G;
     int split = split_segments;
     if (split == 0) {
       // Split-K chunk: long enough to amortise a unit's start-up (measured on the decode
@@ -149,6 +157,21 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
       const int lo = std::max(1, 512 / pool->seg_len);
       split = (int)std::min<int64_t>(32, std::max<int64_t>(lo, (few_entries + 2047) / 2048));
     }
+    // Row-tile items of a small batch: when all row tiles together are fewer workgroups than the
+    // GPU has CUs, long slot lists are cut into chunks (each a work item with partial rows of its
+    // own, merged like any other) until there are about two workgroups per CU; a chunk keeps at
+    // least 2048 tokens so that its start-up stays small against its work.
+    int tile_chunks = 1;
+    {
+      int64_t wgs = 0;
+      for (const RawItem& it : raw) {
+        int64_t n_tok = 0;
+        for (int32_t r : it.reqs) n_tok += ntok_of(r);
+        if (n_tok * G > kUnitRows) wgs += ((n_tok + tok_tile - 1) / tok_tile) * pool->kv_heads;
+      }
+      if (wgs > 0 && wgs < n_cu) tile_chunks = (int)std::min<int64_t>(16, (2 * n_cu + wgs - 1) / wgs);
+    }
+    const int32_t min_chunk_slots = std::max(1, 2048 / pool->seg_len);
     int32_t row_cursor = 0;
     p->item_tok_ptr.push_back(0);
     p->item_slot_ptr.push_back(0);
@@ -159,7 +182,9 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
       for (int32_t r : it.reqs) n_tok += ntok_of(r);
       const bool few_rows = (int64_t)n_tok * G <= kUnitRows;
       const int32_t run = it.end - it.begin;
-      const int32_t step = few_rows ? split : run;
+      const int32_t step = few_rows ? split
+                           : tile_chunks > 1 ? std::max(min_chunk_slots, (run + tile_chunks - 1) / tile_chunks)
+                                             : run;
       for (int32_t c0 = 0; c0 < run; c0 += step) {
         const int32_t c1 = std::min(run, c0 + step);
         const int32_t tok_base = (int32_t)p->item_tokens.size();

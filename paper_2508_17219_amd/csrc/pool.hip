@@ -13,6 +13,7 @@ namespace tl {
 
 static thread_local char g_err[512] = "";
 static int g_opt_vread = 0;
+static int g_opt_compute_units = kComputeUnits;
 
 void set_error(const char* fmt, ...) {
   va_list ap;
@@ -22,6 +23,7 @@ void set_error(const char* fmt, ...) {
 }
 
 int get_option_vread() { return g_opt_vread; }
+int get_option_compute_units() { return g_opt_compute_units; }
 
 // 16 bytes per thread, grid-stride.  dst/src are 16-byte aligned (rows are 256 B).
 __global__ void copy16_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src, size_t n16) {
@@ -130,6 +132,11 @@ tl_status tl_set_option(const char* knob, int32_t value) {
   if (!strcmp(knob, "vread")) {
     if (value < 0 || value > 1) TL_FAIL(TL_EINVAL, "tl_set_option: vread must be 0 or 1");
     g_opt_vread = value;
+    return TL_OK;
+  }
+  if (!strcmp(knob, "compute_units")) {
+    if (value < 0 || value > 4096) TL_FAIL(TL_EINVAL, "tl_set_option: compute_units must be 0..4096");
+    g_opt_compute_units = value;
     return TL_OK;
   }
   TL_FAIL(TL_EINVAL, "tl_set_option: unknown knob '%s'", knob);

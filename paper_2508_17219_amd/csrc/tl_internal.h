@@ -37,6 +37,7 @@ constexpr int kUnitRows = 16;    // max rows per kv head of a split-K unit
 // about twice the machine balance of the measured rooflines (1.2 PFLOP/s : 6 TB/s = 200), so
 // that giving up the sharing of hot segments between requests cannot make it bandwidth-bound.
 constexpr int kFuseRows = 2 * kRowTile;
+constexpr int kComputeUnits = 256;   // MI355X (default of the "compute_units" option; the plan builder makes no HIP call)
 
 // One unit of kernel work.  Its query tokens are tok[tok_off .. tok_off+n_tok) (batch token
 // indices), its partial rows out_row .. out_row+n_tok-1.
@@ -51,6 +52,7 @@ struct Work {
 };
 
 int get_option_vread();
+int get_option_compute_units();
 
 }  // namespace tl
 

@@ -169,7 +169,15 @@ def test_fused_rows_leave_the_three_step_path():
     b.req_row_ptr = np.concatenate([[0], np.cumsum([200, 127, 128, 3, 0])]).astype(np.int32)
     plan_pool[0] = _pool_for(b)
     flags = B.TL_PLAN_SELF_BLOCK | B.TL_PLAN_FUSE_ROWS
+    # this batch has 9 row tiles x 8 kv heads = 72 workgroups: on a 256-CU GPU the planner keeps
+    # the three-step plan (and cuts the slot lists, see the next test); told to fill 64 CUs it fuses
     plan = B.tl_plan_create(plan_pool[0], b.q_heads, b.req_row_ptr, b.req_seg_ptr, b.seg_ids, flags)
+    info = _check_plan_covers(b, plan, flags)
+    assert info.n_fused_tiles == 0
+    B.tl_plan_destroy(plan)
+    B.tl_set_option("compute_units", 64)
+    plan = B.tl_plan_create(plan_pool[0], b.q_heads, b.req_row_ptr, b.req_seg_ptr, b.seg_ids, flags)
+    B.tl_set_option("compute_units", 256)
     info = _check_plan_covers(b, plan, flags, fused_req=(0, 2))
     assert info.n_fused_tiles == 4 + 2 and info.n_fused_tokens == 328       # row tiles of 64 tokens
     assert info.n_causal_tiles == 2 + 1                                      # requests 1 and 3 only
@@ -181,6 +189,27 @@ def test_fused_rows_leave_the_three_step_path():
     plan = B.tl_plan_create(plan_pool[0], b.q_heads, b.req_row_ptr, b.req_seg_ptr, b.seg_ids, B.TL_PLAN_SELF_BLOCK)
     info = _check_plan_covers(b, plan, B.TL_PLAN_SELF_BLOCK)
     assert info.n_fused_tiles == 0
+    B.tl_plan_destroy(plan)
+    B.tl_pool_destroy(plan_pool[0])
+
+
+def test_small_batch_of_row_tiles_is_cut_along_its_kv():
+    """One long prompt: 8 row tiles x 8 kv heads = 64 workgroups would leave three quarters of the
+    GPU idle, so the plan cuts the slot list into chunks (more work items, each with partial rows
+    of its own); every (token, list entry) pair is still covered exactly once."""
+    b = wl.prefill(seed=10, n_req=1, new_tokens=512, lo=30000, hi=32768, seg_len=256, n_slots=160, n_shared=0)
+    plan_pool[0] = _pool_for(b)
+    for flags in (B.TL_PLAN_SELF_BLOCK, B.TL_PLAN_SELF_BLOCK | B.TL_PLAN_FUSE_ROWS):
+        plan = B.tl_plan_create(plan_pool[0], b.q_heads, b.req_row_ptr, b.req_seg_ptr, b.seg_ids, flags)
+        info = _check_plan_covers(b, plan, flags)
+        assert info.n_fused_tiles == 0 and info.n_items == 8 and info.n_tiles == 64      # 2 * 256 / 64 = 8 chunks
+        ex = B.tl_plan_export(plan)
+        assert np.diff(ex["item_slot_ptr"]).min() >= 8                                 # >= 2048 tokens per chunk
+        B.tl_plan_destroy(plan)
+    B.tl_set_option("compute_units", 0)                                                  # switched off: one item
+    plan = B.tl_plan_create(plan_pool[0], b.q_heads, b.req_row_ptr, b.req_seg_ptr, b.seg_ids, B.TL_PLAN_SELF_BLOCK)
+    B.tl_set_option("compute_units", 256)
+    assert B.tl_plan_get_info(plan).n_items == 1
     B.tl_plan_destroy(plan)
     B.tl_pool_destroy(plan_pool[0])
 

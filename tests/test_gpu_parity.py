@@ -525,3 +525,14 @@ def test_head_group_sizes_from_mha_to_one_kv_head(hq, hkv):
     assert (run.info.n_units > 0) == (g <= 16)     # a token's rows beyond 16 per kv head go to row tiles
     _check_all_requests(run)
     run.close()
+
+
+def test_single_long_prompt_is_cut_along_its_kv_and_merged():
+    """A batch too small to fill the GPU with row tiles: the plan cuts the slot list into chunks,
+    each chunk yields a partial per row, the merge puts them together."""
+    _say("single long prompt, KV-chunked work items")
+    b = wl.prefill(seed=61, n_req=1, new_tokens=300, lo=8000, hi=8192, seg_len=256, n_slots=40, n_shared=0)
+    run = H.run_gpu(b, fuse=True, fill_cus=256)
+    assert run.info.n_fused_tiles == 0 and run.info.n_items == 4 and run.info.n_merge_entries == 5 * 300
+    _check_all_requests(run, rows_per_req=24, seed=2)
+    run.close()

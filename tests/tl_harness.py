@@ -53,7 +53,7 @@ def device_pool(batch: wl.Batch, device="cuda", poison: bool = True):
 
 
 def run_gpu(batch: wl.Batch, flags=None, split_segments: int = 0, out_bf16: bool = False, poison: bool = True,
-            pool_tensors=None, fuse: bool = False) -> GpuRun:
+            pool_tensors=None, fuse: bool = False, fill_cus: int = 0) -> GpuRun:
     dev = "cuda"
     pk, pv = pool_tensors if pool_tensors is not None else device_pool(batch, dev, poison)
     pool = B.tl_pool_create(batch.n_slots, batch.seg_len, batch.kv_heads, batch.head_dim, pk, pv)
@@ -62,8 +62,10 @@ def run_gpu(batch: wl.Batch, flags=None, split_segments: int = 0, out_bf16: bool
         flags = B.TL_PLAN_SELF_BLOCK if batch.self_block else 0
     if fuse:
         flags |= B.TL_PLAN_FUSE_ROWS
+        B.tl_set_option("compute_units", fill_cus)       # 0: one-pass rows even when the batch is small
     plan = B.tl_plan_create(pool, batch.q_heads, batch.req_row_ptr, batch.req_seg_ptr, batch.seg_ids, flags,
                             split_segments)
+    B.tl_set_option("compute_units", 256)
     info = B.tl_plan_get_info(plan)
     q = batch.q(dev)
     kn = batch.k_new(dev)
