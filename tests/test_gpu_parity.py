@@ -536,3 +536,19 @@ def test_single_long_prompt_is_cut_along_its_kv_and_merged():
     assert run.info.n_fused_tiles == 0 and run.info.n_items == 4 and run.info.n_merge_entries == 5 * 300
     _check_all_requests(run, rows_per_req=24, seed=2)
     run.close()
+
+
+def test_mixed_batch_of_prefill_chunks_and_decode_tokens():
+    """One batch with one-pass rows (two prefill chunks), split-K units (single decode tokens, a
+    3-token request) and a request of 30 tokens on the row-tile + merge path: the four compute
+    calls write disjoint tokens of the same output."""
+    _say("mixed prefill / decode batch")
+    b = wl.prefill(seed=71, n_req=7, new_tokens=140, lo=500, hi=2500, seg_len=128, n_slots=160, n_shared=2)
+    lens = [140, 1, 1, 150, 1, 3, 30]
+    b.req_row_ptr = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    for split in (0, 2):
+        run = H.run_gpu(b, fuse=True, split_segments=split)
+        i = run.info
+        assert i.n_fused_tokens == 290 and i.n_units > 0 and i.n_tiles > 0 and i.n_causal_tiles == 5
+        _check_all_requests(run)
+        run.close()
