@@ -183,6 +183,7 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="prefill", choices=["prefill", "decode", "longctx", "multiturn", "tiny"])
+    ap.add_argument("--turn", type=int, default=7, help="turn of the multi-turn workload (0..7)")
     ap.add_argument("--split-segments", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sharing", action="store_true", help="plan with TL_PLAN_NO_SHARING (one item chain per request)")
@@ -208,7 +209,7 @@ def main():
         return
 
     maker = {"prefill": wl.prefill, "decode": wl.decode, "longctx": wl.longctx, "tiny": wl.tiny,
-             "multiturn": lambda: wl.multiturn(turn=7)}[args.workload]
+             "multiturn": lambda: wl.multiturn(turn=args.turn)}[args.workload]
     batch = maker()
     res = run_workload(batch, args.steps, args.warmup, torch, B, args.split_segments, fuse=not args.three_step,
                        extra_flags=B.TL_PLAN_NO_SHARING if args.no_sharing else 0)
