@@ -188,6 +188,15 @@ tl_status tl_plan_get_info(const tl_plan* plan, tl_plan_info* info);
 tl_status tl_plan_export(const tl_plan* plan, int32_t* item_row_base, int32_t* item_tok_ptr,
                          int32_t* item_tokens, int32_t* item_slot_ptr, int32_t* item_slots,
                          int32_t* merge_ptr, int32_t* merge_rows);
+/* Heavy hitters of the batch (Section 4.3: load concentrates on segments near the root of the
+ * prefix tree; they are found without walking the whole tree and are the candidates for
+ * replication).  The load of a slot is the number of new tokens whose request lists it (a slot
+ * listed twice by a request counts twice).  Writes up to max_n slots in order of decreasing
+ * load -- equal loads in order of first appearance when the requests' lists are read in request
+ * order, front to back, which puts segments nearer the root first -- with their loads, and the
+ * number written to *n_out.  slots_out: host [max_n] int32; loads_out: host [max_n] int64 or NULL. */
+tl_status tl_plan_hot_slots(const tl_plan* plan, int32_t max_n, int32_t* slots_out, int64_t* loads_out, int32_t* n_out);
+
 /* Sizes of the two variable-length arrays of tl_plan_export. */
 tl_status tl_plan_export_sizes(const tl_plan* plan, int32_t* n_item_tokens, int32_t* n_item_slots);
 

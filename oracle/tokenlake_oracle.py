@@ -39,6 +39,7 @@ __all__ = [
     "SlotTable",
     "gather_segments",
     "append_rows",
+    "segment_loads",
     "attention_rows",
     "partial_attention",
     "merge_partials",
@@ -172,6 +173,18 @@ def gather_segments(pool_k_bits, pool_v_bits, slots, fills):
         shp = (0,) + tuple(pool_k_bits.shape[2:])
         return np.zeros(shp, np.uint16), np.zeros(shp, np.uint16)
     return np.concatenate(ks, axis=0), np.concatenate(vs, axis=0)
+
+
+def segment_loads(req_lists, req_new_tokens):
+    """Load of every listed segment (paper Section 4.3: accesses concentrate on segments near the
+    root of the prefix tree): the number of new tokens whose request lists it, an id listed
+    twice by a request counting twice.  Returns [(id, load), ...] by decreasing load; equal
+    loads keep the order of first appearance (requests in order, each list front to back)."""
+    load = {}
+    for ids, n in zip(req_lists, req_new_tokens):
+        for s in ids:
+            load[int(s)] = load.get(int(s), 0) + int(n)      # dicts keep insertion order
+    return sorted(load.items(), key=lambda kv: -kv[1])          # sorted() is stable
 
 
 def append_rows(pool_k_bits, pool_v_bits, table: SlotTable, tail_id, new_ids, k_rows_bits, v_rows_bits):

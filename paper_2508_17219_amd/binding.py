@@ -57,6 +57,7 @@ _SIGNATURES = {
     "tl_plan_destroy": (_I32, [_P]),
     "tl_plan_get_info": (_I32, [_P, C.POINTER(tl_plan_info)]),
     "tl_plan_export_sizes": (_I32, [_P, C.POINTER(_I32), C.POINTER(_I32)]),
+    "tl_plan_hot_slots": (_I32, [_P, _I32, _P, _P, C.POINTER(_I32)]),
     "tl_plan_export": (_I32, [_P, _P, _P, _P, _P, _P, _P, _P]),
     "tl_segment_attn": (_I32, [_P, _P, _P, _F32, _P, _P, _P]),
     "tl_causal_block": (_I32, [_P, _P, _P, _P, _F32, _P, _P, _P]),
@@ -208,6 +209,13 @@ def tl_plan_get_info(plan: int) -> tl_plan_info:
     info = tl_plan_info()
     _check(load_library().tl_plan_get_info(plan, C.byref(info)))
     return info
+
+
+def tl_plan_hot_slots(plan: int, max_n: int):
+    """(slots, loads) of the batch's most loaded slots, at most max_n."""
+    slots, loads, n = np.zeros(max(max_n, 1), np.int32), np.zeros(max(max_n, 1), np.int64), _I32(0)
+    _check(load_library().tl_plan_hot_slots(plan, max_n, slots.ctypes.data, loads.ctypes.data, C.byref(n)))
+    return slots[:n.value], loads[:n.value]
 
 
 def tl_plan_export(plan: int) -> dict:

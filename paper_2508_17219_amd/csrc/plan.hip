@@ -310,6 +310,22 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
           if (!tok_fused[t]) p->merge_rows[cur[t]++] = self_base + t;
     }
 
+    // ---- heavy hitters: load of a slot = new tokens of the requests that list it ---------------
+    {
+      std::unordered_map<int32_t, int64_t> load;
+      std::vector<int32_t> order;   // first appearance, requests in order, lists front to back
+      for (int32_t r = 0; r < n_req; ++r)
+        for (int32_t pos = 0; pos < len_of(r); ++pos) {
+          const int32_t s = slot_at(r, pos);
+          auto ins = load.emplace(s, 0);
+          if (ins.second) order.push_back(s);
+          ins.first->second += ntok_of(r);
+        }
+      std::stable_sort(order.begin(), order.end(), [&](int32_t x, int32_t y) { return load[x] > load[y]; });
+      p->hot_slots = order;
+      for (int32_t s : order) p->hot_loads.push_back(load[s]);
+    }
+
     std::unordered_set<int32_t> uniq(slots.begin(), slots.end());
     int64_t uniq_tok = 0;
     for (int32_t s : uniq) uniq_tok += pool->fill[s];
@@ -355,6 +371,17 @@ tl_status tl_plan_destroy(tl_plan* plan) {
 tl_status tl_plan_get_info(const tl_plan* plan, tl_plan_info* info) {
   if (!plan || !info) TL_FAIL(TL_EINVAL, "tl_plan_get_info: bad argument");
   *info = plan->info;
+  return TL_OK;
+}
+
+tl_status tl_plan_hot_slots(const tl_plan* plan, int32_t max_n, int32_t* slots_out, int64_t* loads_out, int32_t* n_out) {
+  if (!plan || max_n < 0 || !n_out || (max_n > 0 && !slots_out)) TL_FAIL(TL_EINVAL, "tl_plan_hot_slots: bad argument");
+  const int32_t n = std::min<int32_t>(max_n, (int32_t)plan->hot_slots.size());
+  for (int32_t i = 0; i < n; ++i) {
+    slots_out[i] = plan->hot_slots[i];
+    if (loads_out) loads_out[i] = plan->hot_loads[i];
+  }
+  *n_out = n;
   return TL_OK;
 }
 

@@ -279,3 +279,28 @@ def test_append_refuses_bad_calls_without_changing_anything():
     B.tl_pool_append(pool, None, [], None, None, 0)
     assert state() == before
     B.tl_pool_destroy(pool)
+
+
+def test_hot_slots_match_the_oracles_segment_loads():
+    for b in (wl.multiturn(turn=3), wl.prefill(seed=9, n_req=5, new_tokens=40, lo=300, hi=900, seg_len=128, n_slots=64, n_shared=2),
+              wl.longctx(n_req=2, entries=40, new_tokens=64, n_ids=25, n_slots=32)):
+        pool = _pool_for(b)
+        plan = B.tl_plan_create(pool, b.q_heads, b.req_row_ptr, b.req_seg_ptr, b.seg_ids)
+        lists = [b.seg_ids[b.req_seg_ptr[r]:b.req_seg_ptr[r + 1]].tolist() for r in range(b.n_req)]
+        want = orc.segment_loads(lists, np.diff(b.req_row_ptr).tolist())
+        slots, loads = B.tl_plan_hot_slots(plan, 10 ** 6)
+        assert slots.tolist() == B.tl_pool_lookup(pool, [i for i, _ in want]).tolist()
+        assert loads.tolist() == [l for _, l in want]
+        top, _ = B.tl_plan_hot_slots(plan, 3)
+        assert top.tolist() == slots[:3].tolist()
+        B.tl_plan_destroy(plan)
+        B.tl_pool_destroy(pool)
+    # the multi-turn batch: the 16 segments of the system prompt carry every new token
+    b = wl.multiturn(turn=3)
+    pool = _pool_for(b)
+    plan = B.tl_plan_create(pool, b.q_heads, b.req_row_ptr, b.req_seg_ptr, b.seg_ids)
+    slots, loads = B.tl_plan_hot_slots(plan, 17)
+    assert loads[:16].tolist() == [64 * 256] * 16 and loads[16] == 256
+    assert slots[:16].tolist() == B.tl_pool_lookup(pool, np.arange(16, dtype=np.uint64)).tolist()
+    B.tl_plan_destroy(plan)
+    B.tl_pool_destroy(pool)

@@ -390,3 +390,22 @@ def test_append_chain_equals_concatenation_of_rows():
     assert sum(len(c["ids"]) for c in chains.values()) > 10
     # the unrelated residents were never touched
     assert table.lookup([1000, 1001]).tolist() == [0, 2] and table.fill([0, 2]).tolist() == [C, 3]
+
+
+def test_segment_loads_hand_case_and_invariants():
+    """Pin for segment_loads: a case counted by hand, then invariants on random lists."""
+    # requests: A = [s1, s2, s3] with 5 new tokens, B = [s1, s2, s9] with 2, C = [s7] with 4, D = [s1, s1] with 1
+    got = orc.segment_loads([[1, 2, 3], [1, 2, 9], [7], [1, 1]], [5, 2, 4, 1])
+    # s1: 5 + 2 + 1 + 1 = 9; s2: 5 + 2 = 7; s3: 5; s7: 4; s9: 2 -- and s3 before s7? no: 5 > 4
+    assert got == [(1, 9), (2, 7), (3, 5), (7, 4), (9, 2)]
+    # ties keep first appearance: s3 (request A) before s9 (request B) when both carry 3
+    assert orc.segment_loads([[3], [9]], [3, 3]) == [(3, 3), (9, 3)]
+    rng = np.random.default_rng(8)
+    lists = [rng.integers(0, 30, size=int(rng.integers(0, 12))).tolist() for _ in range(20)]
+    ntok = rng.integers(0, 50, size=20).tolist()
+    got = orc.segment_loads(lists, ntok)
+    assert sum(l for _, l in got) == sum(len(ids) * n for ids, n in zip(lists, ntok))     # every listing counted once
+    assert [l for _, l in got] == sorted((l for _, l in got), reverse=True)
+    assert set(i for i, _ in got) == set(x for ids in lists for x in ids)
+    for sid, l in got:                                                                    # brute force per id
+        assert l == sum(ids.count(sid) * n for ids, n in zip(lists, ntok))
