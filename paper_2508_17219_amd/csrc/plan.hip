@@ -310,25 +310,22 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
           if (!tok_fused[t]) p->merge_rows[cur[t]++] = self_base + t;
     }
 
-    // ---- heavy hitters: load of a slot = new tokens of the requests that list it ---------------
-    {
-      std::unordered_map<int32_t, int64_t> load;
-      std::vector<int32_t> order;   // first appearance, requests in order, lists front to back
-      for (int32_t r = 0; r < n_req; ++r)
-        for (int32_t pos = 0; pos < len_of(r); ++pos) {
-          const int32_t s = slot_at(r, pos);
-          auto ins = load.emplace(s, 0);
-          if (ins.second) order.push_back(s);
-          ins.first->second += ntok_of(r);
-        }
-      std::stable_sort(order.begin(), order.end(), [&](int32_t x, int32_t y) { return load[x] > load[y]; });
-      p->hot_slots = order;
-      for (int32_t s : order) p->hot_loads.push_back(load[s]);
-    }
+    // kept for tl_plan_hot_slots, which ranks the slots on first request
+    p->list_slots = slots;
+    p->list_ptr.assign(req_seg_ptr, req_seg_ptr + n_req + 1);
+    p->list_ntok.resize(n_req);
+    for (int32_t r = 0; r < n_req; ++r) p->list_ntok[r] = ntok_of(r);
+    p->hot_ready = false;
 
-    std::unordered_set<int32_t> uniq(slots.begin(), slots.end());
     int64_t uniq_tok = 0;
-    for (int32_t s : uniq) uniq_tok += pool->fill[s];
+    {
+      std::vector<char> seen(pool->n_slots, 0);
+      for (int32_t s : slots)
+        if (!seen[s]) {
+          seen[s] = 1;
+          uniq_tok += pool->fill[s];
+        }
+    }
 
     tl_plan_info& inf = p->info;
     memset(&inf, 0, sizeof(inf));
@@ -376,6 +373,30 @@ tl_status tl_plan_get_info(const tl_plan* plan, tl_plan_info* info) {
 
 tl_status tl_plan_hot_slots(const tl_plan* plan, int32_t max_n, int32_t* slots_out, int64_t* loads_out, int32_t* n_out) {
   if (!plan || max_n < 0 || !n_out || (max_n > 0 && !slots_out)) TL_FAIL(TL_EINVAL, "tl_plan_hot_slots: bad argument");
+  if (!plan->hot_ready) {
+    // load of a slot = new tokens of the requests that list it
+    try {
+      std::vector<int64_t> load(plan->pool->n_slots, 0);
+      std::vector<char> seen(plan->pool->n_slots, 0);
+      std::vector<int32_t> order;   // first appearance, requests in order, lists front to back
+      for (int32_t r = 0; r < plan->n_req; ++r)
+        for (int32_t i = plan->list_ptr[r]; i < plan->list_ptr[r + 1]; ++i) {
+          const int32_t s = plan->list_slots[i];
+          if (!seen[s]) {
+            seen[s] = 1;
+            order.push_back(s);
+          }
+          load[s] += plan->list_ntok[r];
+        }
+      std::stable_sort(order.begin(), order.end(), [&](int32_t x, int32_t y) { return load[x] > load[y]; });
+      plan->hot_loads.clear();
+      for (int32_t s : order) plan->hot_loads.push_back(load[s]);
+      plan->hot_slots.swap(order);
+      plan->hot_ready = true;
+    } catch (const std::bad_alloc&) {
+      TL_FAIL(TL_ENOMEM, "tl_plan_hot_slots: host allocation failed");
+    }
+  }
   const int32_t n = std::min<int32_t>(max_n, (int32_t)plan->hot_slots.size());
   for (int32_t i = 0; i < n; ++i) {
     slots_out[i] = plan->hot_slots[i];

@@ -82,8 +82,11 @@ struct tl_plan {
   std::vector<int32_t> merge_ptr, merge_rows;
   std::vector<tl::Work> tiles, units, ctiles, ftiles;   // ftiles: fused rows (pool tiles + causal block in one pass)
   std::vector<int32_t> merge_tok;  // tokens that tl_merge writes (all but the fused ones)
-  std::vector<int32_t> hot_slots;  // every listed slot, by decreasing load (new tokens that attend to it)
-  std::vector<int64_t> hot_loads;
+  // heavy hitters, computed on first request from the resolved lists kept here
+  std::vector<int32_t> list_slots, list_ptr, list_ntok;
+  mutable bool hot_ready;
+  mutable std::vector<int32_t> hot_slots;  // every listed slot, by decreasing load (new tokens that attend to it)
+  mutable std::vector<int64_t> hot_loads;
   std::vector<int32_t> tok;      // token index array referenced by Work::tok_off
   std::vector<int32_t> tile_base;  // Work::full_off
   std::vector<int32_t> part_tile;  // Work::part_off, pairs (first kv row, valid tokens)
