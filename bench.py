@@ -70,8 +70,15 @@ def _setup(batch, torch, B):
 def run_workload(batch, steps, warmup, torch, B, split_segments=0, fuse=True, extra_flags=0):
     """Times `steps` passes of the whole path; returns timings and the plan's work counters."""
     pk, pv, pool = _setup(batch, torch, B)
-    plan = B.tl_plan_create(pool, batch.q_heads, batch.req_row_ptr, batch.req_seg_ptr, batch.seg_ids,
-                            B.TL_PLAN_SELF_BLOCK | (B.TL_PLAN_FUSE_ROWS if fuse else 0) | extra_flags, split_segments)
+    plan_flags = B.TL_PLAN_SELF_BLOCK | (B.TL_PLAN_FUSE_ROWS if fuse else 0) | extra_flags
+    t_plan = []
+    for _ in range(3):       # host-side cost of a plan (built once per iteration, used by every layer)
+        t0 = time.perf_counter()
+        plan = B.tl_plan_create(pool, batch.q_heads, batch.req_row_ptr, batch.req_seg_ptr, batch.seg_ids, plan_flags,
+                                split_segments)
+        t_plan.append((time.perf_counter() - t0) * 1e3)
+        if len(t_plan) < 3:
+            B.tl_plan_destroy(plan)
     info = B.tl_plan_get_info(plan)
     dev = "cuda"
     q, kn, vn = batch.q(dev), batch.k_new(dev), batch.v_new(dev)
@@ -111,6 +118,7 @@ def run_workload(batch, steps, warmup, torch, B, split_segments=0, fuse=True, ex
         "ms_per_step": (t1 - t0) * 1e3 / steps,
         "segment_attn_ms": seg_ms, "causal_block_ms": causal_ms, "merge_ms": merge_ms, "fused_attn_ms": fused_ms,
         "info": {n: getattr(info, n) for n, _ in info._fields_},
+        "plan_create_ms": min(t_plan),
         "checksum": float(out.float().abs().mean().item()),
     }
     B.tl_plan_destroy(plan)
@@ -254,7 +262,7 @@ def main():
                        "merge": res["merge_ms"], "fused_attn": res["fused_attn_ms"]},
         "plan": {"fused_tokens": res["info"]["n_fused_tokens"], "row_tiles": res["info"]["n_tiles"],
                  "split_k_units": res["info"]["n_units"], "causal_tiles": res["info"]["n_causal_tiles"],
-                 "fused_row_tiles": res["info"]["n_fused_tiles"]},
+                 "fused_row_tiles": res["info"]["n_fused_tiles"], "host_ms_to_build": res["plan_create_ms"]},
         "attn_tflops": (work["flops_prefix"] + work["flops_self"]) /
                        ((res["segment_attn_ms"] + res["causal_block_ms"] + res["fused_attn_ms"]) * 1e-3) / 1e12,
     }
