@@ -304,3 +304,50 @@ def test_hot_slots_match_the_oracles_segment_loads():
     assert slots[:16].tolist() == B.tl_pool_lookup(pool, np.arange(16, dtype=np.uint64)).tolist()
     B.tl_plan_destroy(plan)
     B.tl_pool_destroy(pool)
+
+
+def test_random_batches_every_pair_once_under_every_plan_mode():
+    """Random trees of shared prefixes, ragged fills, repeated segments, zero-token and zero-prefix
+    requests: whatever the flags, the split size and the number of CUs the planner is told to
+    fill, every (token, list entry) pair is covered by exactly one work item or by the one-pass
+    rows, and the merge lists name every partial row once."""
+    rng = np.random.default_rng(123)
+    for case in range(25):
+        seg_len = int(rng.choice([64, 128, 256]))
+        hkv = int(rng.choice([1, 2, 8]))
+        g = int(rng.choice([1, 4, 8]))
+        n_req = int(rng.integers(1, 9))
+        n_ids = int(rng.integers(4, 40))
+        # lists: a common stem, then branches; some ids repeated inside a list
+        stem = rng.permutation(n_ids)[:int(rng.integers(0, 4))].tolist()
+        lists, ntok = [], []
+        for r in range(n_req):
+            own = rng.integers(0, n_ids, size=int(rng.integers(0, 7))).tolist()
+            lists.append(([] if rng.random() < 0.15 else stem[:int(rng.integers(0, len(stem) + 1))]) + own)
+            ntok.append(int(rng.choice([0, 1, 3, 16, 70, 200, 600])))
+        ids = sorted(set(x for l in lists for x in l))
+        fills = {i: int(rng.integers(1, seg_len + 1)) for i in ids}
+        b = wl.Batch(name="random", seed=0, q_heads=hkv * g, kv_heads=hkv, seg_len=seg_len, n_slots=64,
+                     req_row_ptr=np.concatenate([[0], np.cumsum(ntok)]).astype(np.int32),
+                     req_seg_ptr=np.concatenate([[0], np.cumsum([len(l) for l in lists])]).astype(np.int32),
+                     seg_ids=np.array([x for l in lists for x in l], dtype=np.uint64),
+                     pool_ids=np.array(ids, dtype=np.uint64),
+                     pool_slots=rng.permutation(64)[:len(ids)].astype(np.int32),
+                     pool_fills=np.array([fills[i] for i in ids], dtype=np.int32))
+        plan_pool[0] = _pool_for(b)
+        tok_tile = 256 // g
+        for flags in (0, B.TL_PLAN_SELF_BLOCK, B.TL_PLAN_SELF_BLOCK | B.TL_PLAN_NO_SHARING,
+                      B.TL_PLAN_SELF_BLOCK | B.TL_PLAN_FUSE_ROWS):
+            for cus in (0, 8, 256):
+                B.tl_set_option("compute_units", cus)
+                plan = B.tl_plan_create(plan_pool[0], b.q_heads, b.req_row_ptr, b.req_seg_ptr, b.seg_ids, flags,
+                                        int(rng.choice([0, 1, 3])))
+                B.tl_set_option("compute_units", 256)
+                fused = ()
+                if flags & B.TL_PLAN_FUSE_ROWS:
+                    wgs = sum(-(-n // tok_tile) * hkv for n in ntok if n > 0)
+                    if wgs >= cus:
+                        fused = tuple(r for r in range(n_req) if ntok[r] * g >= 512)
+                _check_plan_covers(b, plan, flags, fused_req=fused)
+                B.tl_plan_destroy(plan)
+        B.tl_pool_destroy(plan_pool[0])
