@@ -552,3 +552,37 @@ def test_mixed_batch_of_prefill_chunks_and_decode_tokens():
         assert i.n_fused_tokens == 290 and i.n_units > 0 and i.n_tiles > 0 and i.n_causal_tiles == 5
         _check_all_requests(run)
         run.close()
+
+
+def test_random_batches_against_the_oracle():
+    """Random small batches (shared stems, repeated segments, ragged fills, requests with no
+    prefix or no tokens, head groups 1/4/8) through every plan mode; every row against the oracle."""
+    _say("random batches")
+    rng = np.random.default_rng(321)
+    for case in range(6):
+        seg_len = int(rng.choice([64, 128]))
+        hkv = int(rng.choice([1, 2]))
+        g = int(rng.choice([1, 4, 8]))
+        n_req = int(rng.integers(2, 6))
+        n_ids = int(rng.integers(6, 20))
+        stem = rng.permutation(n_ids)[:int(rng.integers(1, 4))].tolist()
+        lists, ntok = [], []
+        for r in range(n_req):
+            own = rng.integers(0, n_ids, size=int(rng.integers(0, 6))).tolist()
+            lists.append(([] if rng.random() < 0.2 else stem[:int(rng.integers(0, len(stem) + 1))]) + own)
+            ntok.append(int(rng.choice([0, 1, 5, 40, 150, 530 // g + 1])))
+        if sum(ntok) == 0:
+            ntok[0] = 7
+        ids = sorted(set(x for l in lists for x in l)) or [0]
+        fills = {i: int(rng.integers(1, seg_len + 1)) for i in ids}
+        b = wl.Batch(name="random%d" % case, seed=100 + case, q_heads=hkv * g, kv_heads=hkv, seg_len=seg_len, n_slots=32,
+                     req_row_ptr=np.concatenate([[0], np.cumsum(ntok)]).astype(np.int32),
+                     req_seg_ptr=np.concatenate([[0], np.cumsum([len(l) for l in lists])]).astype(np.int32),
+                     seg_ids=np.array([x for l in lists for x in l], dtype=np.uint64),
+                     pool_ids=np.array(ids, dtype=np.uint64),
+                     pool_slots=rng.permutation(32)[:len(ids)].astype(np.int32),
+                     pool_fills=np.array([fills[i] for i in ids], dtype=np.int32))
+        for kw in (dict(), dict(fuse=True), dict(flags=B.TL_PLAN_SELF_BLOCK | B.TL_PLAN_NO_SHARING, split_segments=1)):
+            run = H.run_gpu(b, **kw)
+            _check_all_requests(run)
+            run.close()
