@@ -84,6 +84,15 @@ __device__ __forceinline__ float xor32_sum(float x) {
   return r0 + r1;
 }
 
+// a packed bf16 operand held as four 32-bit words, so that a pair of elements is one register write
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+// word `pair` (0..3) of a packed operand := (a, b) rounded to bf16
+__device__ __forceinline__ void set_pair(u32x4& p, int pair, float a, float b) {
+  typedef float f32x2_t __attribute__((ext_vector_type(2)));
+  typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+  p[pair] = __builtin_bit_cast(unsigned, __builtin_convertvector(f32x2_t{a, b}, bf16x2_t));
+}
+
 __device__ __forceinline__ float max16(const f32x16& s) {
   float a = fmaxf(fmaxf(s[0], s[1]), s[2]);
   float b = fmaxf(fmaxf(s[3], s[4]), s[5]);
@@ -374,15 +383,16 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
     __syncthreads();
 
     f32x16 s0[kRG], s1[kRG];            // scores of block 0 / block 1 of a tile (then their probabilities)
-    bf16x8 p0[kRG][2], p1[kRG][2];      // packed probabilities
+    u32x4 p0[kRG][2], p1[kRG][2];       // packed probabilities (bf16 pairs)
     qk_block(lds_k, 0, s0);
     float mc[kRG];
 #pragma unroll
     for (int rg = 0; rg < kRG; ++rg) {
       if (!have_ref) m_ref[rg] = xor32_max(max16(s0[rg]));   // reference: the first block's row maximum
       mc[rg] = m_ref[rg] * c;
-      p1[rg][0] = pack_bf16x8(0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f);
+      p1[rg][0] = u32x4{0u, 0u, 0u, 0u};
       p1[rg][1] = p1[rg][0];
+      p0[rg][0] = p0[rg][1] = p1[rg][0];
     }
 
     // operand group g of an iteration (0..31): step g / 16; even = K operand (head-dim step g%16 / 2),
@@ -448,7 +458,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
           const int sp = idx >> 2, d = idx & 3;
 #pragma unroll
           for (int rg = 0; rg < kRG; ++rg)
-            o[rg][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, step == 0 ? p1[rg][sp] : p0[rg][sp], o[rg][d], 0, 0, 0);
+            o[rg][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, __builtin_bit_cast(bf16x8, step == 0 ? p1[rg][sp] : p0[rg][sp]), o[rg][d], 0, 0, 0);
         }
         // probabilities of the block whose scores are complete: kRG elements per group
 #pragma unroll
@@ -456,11 +466,16 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
           const int e = gi * kRG + j, rg = e >> 4, r = e & 15;
           f32x16& s = step == 0 ? s0[rg] : s1[rg];
           s[r] = fast_exp2(fmaf(s[r], c, -mc[rg]));
-          if ((r & 7) == 7) {
-            const int r0 = r - 7;
-            const bf16x8 pk = pack_bf16x8(s[r0], s[r0 + 1], s[r0 + 2], s[r0 + 3], s[r0 + 4], s[r0 + 5], s[r0 + 6], s[r0 + 7]);
-            if (step == 0) p0[rg][r >> 3] = pk; else p1[rg][r >> 3] = pk;
-            l_run[rg] += ((s[r0] + s[r0 + 1]) + (s[r0 + 2] + s[r0 + 3])) + ((s[r0 + 4] + s[r0 + 5]) + (s[r0 + 6] + s[r0 + 7]));
+          // The row sum and the packing to bf16 trail the exponentials by one element / one pair, so
+          // that every group carries the same few vector instructions (a burst of eight adds and
+          // four converts in one group would hold up that group's MFMA) and none of them waits
+          // for the exponential issued just before it.
+          u32x4 (&pp)[2] = step == 0 ? p0[rg] : p1[rg];
+          if (r >= 1) l_run[rg] += s[r - 1];
+          if (r >= 2 && (r & 1) == 0) set_pair(pp[(r - 2) >> 3], ((r - 2) & 7) >> 1, s[r - 2], s[r - 1]);
+          if (r == 15) {
+            l_run[rg] += s[15];
+            set_pair(pp[1], 3, s[14], s[15]);
           }
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -486,7 +501,15 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
       }
     }
     // drain: accumulate block 1 of the last tile
-    pv_block(lds_v + ((n_full - 1) % kBufs) * kVTile, 1, p1);
+    {
+      bf16x8 pl[kRG][2];
+#pragma unroll
+      for (int rg = 0; rg < kRG; ++rg) {
+        pl[rg][0] = __builtin_bit_cast(bf16x8, p1[rg][0]);
+        pl[rg][1] = __builtin_bit_cast(bf16x8, p1[rg][1]);
+      }
+      pv_block(lds_v + ((n_full - 1) % kBufs) * kVTile, 1, pl);
+    }
 
     // did the fixed reference hold?  (row sums are sums of positive terms: one huge term shows)
     bool bad = false;
