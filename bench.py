@@ -67,7 +67,7 @@ def _setup(batch, torch, B):
     return pk, pv, pool
 
 
-def run_workload(batch, steps, warmup, torch, B, split_segments=0, fuse=True, extra_flags=0):
+def run_workload(batch, steps, warmup, torch, B, split_segments=0, fuse=True, extra_flags=0, graph=False):
     """Times `steps` passes of the whole path; returns timings and the plan's work counters."""
     pk, pv, pool = _setup(batch, torch, B)
     plan_flags = B.TL_PLAN_SELF_BLOCK | (B.TL_PLAN_FUSE_ROWS if fuse else 0) | extra_flags
@@ -121,6 +121,20 @@ def run_workload(batch, steps, warmup, torch, B, split_segments=0, fuse=True, ex
         "plan_create_ms": min(t_plan),
         "checksum": float(out.float().abs().mean().item()),
     }
+    if graph:
+        # the same step captured once as a HIP graph and replayed: what the launches cost the host
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            step()
+        g.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            g.replay()
+        torch.cuda.synchronize()
+        res["graph_ms_per_step"] = (time.perf_counter() - t0) * 1e3 / steps
+        res["graph_checksum"] = float(out.float().abs().mean().item())
+        del g
     B.tl_plan_destroy(plan)
     B.tl_pool_destroy(pool)
     del pk, pv, outp, lsep, out, lse, q, kn, vn
@@ -198,6 +212,8 @@ def main():
     ap.add_argument("--three-step", action="store_true",
                     help="plan without TL_PLAN_FUSE_ROWS: every request goes through partials and the merge")
     ap.add_argument("--no-decode", action="store_true", help="skip the appended decode measurement")
+    ap.add_argument("--graph", action="store_true",
+                    help="also time the step replayed from a HIP graph (reported as graph_ms_per_step)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a 1 GiB device copy (to scale rocprofv3 FETCH_SIZE/WRITE_SIZE) and exit")
     args = ap.parse_args()
@@ -220,7 +236,7 @@ def main():
              "multiturn": lambda: wl.multiturn(turn=args.turn)}[args.workload]
     batch = maker()
     res = run_workload(batch, args.steps, args.warmup, torch, B, args.split_segments, fuse=not args.three_step,
-                       extra_flags=B.TL_PLAN_NO_SHARING if args.no_sharing else 0)
+                       extra_flags=B.TL_PLAN_NO_SHARING if args.no_sharing else 0, graph=args.graph)
     work = algorithmic_work(batch, res["info"])
     tok_s = batch.n_tokens / (res["ms_per_step"] * 1e-3)
 
@@ -266,6 +282,9 @@ def main():
         "attn_tflops": (work["flops_prefix"] + work["flops_self"]) /
                        ((res["segment_attn_ms"] + res["causal_block_ms"] + res["fused_attn_ms"]) * 1e-3) / 1e12,
     }
+    if args.graph:
+        line["hip_graph"] = {"ms_per_step": res["graph_ms_per_step"],
+                             "same_output": res["graph_checksum"] == res["checksum"]}
     if args.workload != "decode" and not args.no_decode:
         db = wl.decode()
         dres = run_workload(db, max(3, args.steps // 4), 1, torch, B, args.split_segments, fuse=not args.three_step)

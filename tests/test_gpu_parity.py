@@ -586,3 +586,36 @@ def test_random_batches_against_the_oracle():
             run = H.run_gpu(b, **kw)
             _check_all_requests(run)
             run.close()
+
+
+# ---- the step as a HIP graph ----------------------------------------------------------------------
+@pytest.mark.parametrize("fuse", [False, True])
+def test_step_replays_from_a_hip_graph(fuse):
+    """The compute calls only enqueue kernels, so a step can be captured once and replayed.
+    Every replay, with eager work and synchronisations in between, must reproduce the eager
+    result bit for bit."""
+    _say("hip graph replay fuse=%s" % fuse)
+    b = wl.prefill(seed=23, n_req=3, new_tokens=100, lo=300, hi=900, seg_len=128, n_slots=64, n_shared=2)
+    run = H.run_gpu(b, fuse=fuse)            # eager: also brings the pool's device state up to date
+    _check_all_requests(run)
+    want_o, want_l = run.out.clone(), run.lse.clone()
+
+    def step():
+        B.tl_segment_attn(run.pool, run.plan, run.q, b.scale, run.out_partial, run.lse_partial)
+        B.tl_causal_block(run.plan, run.q, run.k_new, run.v_new, b.scale, run.out_partial, run.lse_partial)
+        B.tl_merge(run.plan, run.out_partial, run.lse_partial, run.out, False, run.lse)
+        if fuse:
+            B.tl_fused_attn(run.pool, run.plan, run.q, run.k_new, run.v_new, b.scale, run.out, False, run.lse)
+
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        step()
+    for rep in range(3):
+        for t in (run.out_partial, run.lse_partial, run.out, run.lse):
+            t.fill_(float("nan"))                       # eager work between the replays
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(run.out, want_o) and torch.equal(run.lse, want_l), "replay %d differs" % rep
+    del g
+    run.close()
