@@ -16,6 +16,10 @@
  *    they must stay valid until the stream work enqueued by the call has completed.
  *  - Compute calls enqueue kernels on `stream` (a hipStream_t passed as void*, NULL = the
  *    default stream) and return without synchronising.
+ *    tl_segment_attn, tl_causal_block, tl_merge and tl_fused_attn enqueue nothing but
+ *    kernels, except that the first of them after a put / append / adopt uploads the pool's
+ *    fill table with one asynchronous copy: run one step eagerly before capturing a step
+ *    into a HIP graph.
  *  - All tensors are dense, row-major, bf16 = 16-bit brain float bit patterns.
  *  - head_dim must be 128; q_heads / kv_heads must be a power of two <= 32; seg_len must
  *    be a multiple of 64.  Anything else is TL_EINVAL.
