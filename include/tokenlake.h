@@ -21,7 +21,7 @@
  *    fill table with one asynchronous copy: run one step eagerly before capturing a step
  *    into a HIP graph.
  *  - All tensors are dense, row-major, bf16 = 16-bit brain float bit patterns.
- *  - head_dim must be 128; q_heads / kv_heads must be a power of two <= 32; seg_len must
+ *  - head_dim must be 128; q_heads must be a multiple of kv_heads, at most 32 times it; seg_len must
  *    be a multiple of 64.  Anything else is TL_EINVAL.
  *  - The normalizer is the natural-log log-sum-exp of the scaled scores.  A row with no
  *    keys has O = 0 and LSE = -inf.

@@ -39,7 +39,7 @@ struct AttnArgs {
   const int32_t* part_tile;  // (first kv row, valid tokens) of each cut-short tile
   float* out;             // [rows, q_heads, 128]
   float* lse;             // [rows, q_heads]
-  int32_t q_heads, kv_heads, log2g, seg_len, n_work;
+  int32_t q_heads, kv_heads, group, seg_len, n_work;   // group = q_heads / kv_heads
   float scale;            // softmax scale
   float scale_log2e;      // scale * log2(e)
 };

@@ -36,12 +36,12 @@ __global__ __launch_bounds__(kThreads) void splitk_unit_attn_kernel(const AttnAr
   const int wave = tid >> 6, lane = tid & 63, l16 = lane & 15, c4 = lane >> 4;
   const int g = blockIdx.y * kWaves + wave;
   const bool active = g < a.kv_heads;
-  const int G = 1 << a.log2g;
+  const int G = a.group;
   uint16_t* kt = lds + wave * kWaveElems;
   uint16_t* vt = kt + kTok * kLdsStride;
 
-  const int tok_local = l16 >> a.log2g;
-  const int j = l16 & (G - 1);
+  const int tok_local = l16 / G;
+  const int j = l16 - tok_local * G;
   const bool row_ok = active && tok_local < wk.n_tok;
   const int token = row_ok ? a.tok[wk.tok_off + tok_local] : 0;
 

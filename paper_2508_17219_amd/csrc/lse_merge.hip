@@ -55,12 +55,6 @@ __global__ __launch_bounds__(256) void lse_merge_kernel(const float* __restrict_
   }
 }
 
-int ilog2(int x) {
-  int l = 0;
-  while ((1 << l) < x) ++l;
-  return l;
-}
-
 void fill_args(AttnArgs& a, const tl_plan* plan, const void* q, float scale, float* out, float* lse) {
   a.q = (const uint16_t*)q;
   a.tok = plan->d_tok;
@@ -71,7 +65,7 @@ void fill_args(AttnArgs& a, const tl_plan* plan, const void* q, float scale, flo
   a.lse = lse;
   a.q_heads = plan->q_heads;
   a.kv_heads = plan->kv_heads;
-  a.log2g = ilog2(plan->group);
+  a.group = plan->group;
   a.scale = scale;
   a.scale_log2e = scale * 1.4426950408889634f;
   a.k2 = a.v2 = nullptr;

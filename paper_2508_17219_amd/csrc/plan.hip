@@ -22,7 +22,6 @@ struct RawItem {
   int32_t begin, end;          // list positions [begin, end)
 };
 
-bool is_pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
 
 }  // namespace
 
@@ -36,7 +35,7 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
   if (!pool || n_req < 0 || !req_row_ptr || !req_seg_ptr) TL_FAIL(TL_EINVAL, "tl_plan_create: bad argument");
   if (q_heads <= 0 || q_heads % pool->kv_heads) TL_FAIL(TL_EINVAL, "tl_plan_create: q_heads must be a multiple of kv_heads");
   const int G = q_heads / pool->kv_heads;
-  if (!is_pow2(G) || G > 32) TL_FAIL(TL_EINVAL, "tl_plan_create: q_heads/kv_heads must be a power of two <= 32");
+  if (G > 32) TL_FAIL(TL_EINVAL, "tl_plan_create: q_heads/kv_heads must be at most 32");
   if (split_segments < 0) TL_FAIL(TL_EINVAL, "tl_plan_create: negative split_segments");
   if ((flags & TL_PLAN_FUSE_ROWS) && !(flags & TL_PLAN_SELF_BLOCK))
     TL_FAIL(TL_EINVAL, "tl_plan_create: TL_PLAN_FUSE_ROWS needs TL_PLAN_SELF_BLOCK");

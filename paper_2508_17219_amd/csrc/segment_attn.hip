@@ -118,7 +118,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
   const Work wk = a.work[blockIdx.x / a.kv_heads];
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63, l32 = lane & 31, h = lane >> 5;
-  const int G = 1 << a.log2g;
+  const int G = a.group;
   const int first_token = a.tok[wk.tok_off];   // causal work: tokens of a tile are consecutive
   constexpr bool kHasPool = MODE != 1, kHasSelf = MODE != 0;
   // K/V of the new tokens: the launch's main K/V for the causal block alone, the second pair when fused
@@ -131,8 +131,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
 #pragma unroll
   for (int rg = 0; rg < kRG; ++rg) {
     const int row = wave * (32 * kRG) + 32 * rg + l32;
-    tok_local[rg] = row >> a.log2g;
-    head_j[rg] = row & (G - 1);
+    tok_local[rg] = row / G;                    // any group size: the last 256 % G rows of a tile are idle
+    head_j[rg] = row - tok_local[rg] * G;
     row_ok[rg] = tok_local[rg] < wk.n_tok;
     token[rg] = row_ok[rg] ? a.tok[wk.tok_off + tok_local[rg]] : -1;
   }

@@ -238,7 +238,9 @@ def test_plan_errors():
     with pytest.raises(B.TokenLakeError):
         B.tl_plan_create(pool, 3, b.req_row_ptr, b.req_seg_ptr, b.seg_ids)          # 3 q heads on 2 kv heads
     with pytest.raises(B.TokenLakeError):
-        B.tl_plan_create(pool, 12, b.req_row_ptr, b.req_seg_ptr, b.seg_ids)         # group of 6: not a power of two
+        B.tl_plan_create(pool, 66, b.req_row_ptr, b.req_seg_ptr, b.seg_ids)         # group of 33: above the limit of 32
+    plan = B.tl_plan_create(pool, 12, b.req_row_ptr, b.req_seg_ptr, b.seg_ids)  # group of 6: any size up to 32 will do
+    B.tl_plan_destroy(plan)
     with pytest.raises(B.TokenLakeError):
         B.tl_plan_create(pool, 8, [0, 5, 3], [0, 1, 2], b.seg_ids)                  # decreasing offsets
     with pytest.raises(B.TokenLakeError):
@@ -315,7 +317,7 @@ def test_random_batches_every_pair_once_under_every_plan_mode():
     for case in range(25):
         seg_len = int(rng.choice([64, 128, 256]))
         hkv = int(rng.choice([1, 2, 8]))
-        g = int(rng.choice([1, 4, 8]))
+        g = int(rng.choice([1, 3, 4, 7, 8]))
         n_req = int(rng.integers(1, 9))
         n_ids = int(rng.integers(4, 40))
         # lists: a common stem, then branches; some ids repeated inside a list

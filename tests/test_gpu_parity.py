@@ -506,10 +506,11 @@ def test_append_rows_grow_chains_like_the_oracle():
     B.tl_pool_destroy(pool)
 
 
-@pytest.mark.parametrize("hq,hkv", [(4, 4), (8, 4), (32, 1), (16, 16)])
+@pytest.mark.parametrize("hq,hkv", [(4, 4), (8, 4), (32, 1), (16, 16), (28, 4), (6, 2), (5, 1), (24, 2)])
 def test_head_group_sizes_from_mha_to_one_kv_head(hq, hkv):
     """The paper's own model is multi-head (one kv head per q head); the named configurations are
-    grouped-query with 4 or 8 q heads per kv head.  Every path (row tiles, one-pass rows, split-K
+    grouped-query with 4 or 8 q heads per kv head; group sizes that are no power of two (7, 3, 5,
+    12) leave the last rows of a 256-row tile or a 16-row unit idle.  Every path (row tiles, one-pass rows, split-K
     units) on both extremes, every row against the oracle."""
     _say("head groups hq=%d hkv=%d" % (hq, hkv))
     g = hq // hkv
@@ -556,13 +557,13 @@ def test_mixed_batch_of_prefill_chunks_and_decode_tokens():
 
 def test_random_batches_against_the_oracle():
     """Random small batches (shared stems, repeated segments, ragged fills, requests with no
-    prefix or no tokens, head groups 1/4/8) through every plan mode; every row against the oracle."""
+    prefix or no tokens, head groups 1/3/4/7/8) through every plan mode; every row against the oracle."""
     _say("random batches")
     rng = np.random.default_rng(321)
     for case in range(6):
         seg_len = int(rng.choice([64, 128]))
         hkv = int(rng.choice([1, 2]))
-        g = int(rng.choice([1, 4, 8]))
+        g = int(rng.choice([1, 3, 4, 7, 8]))
         n_req = int(rng.integers(2, 6))
         n_ids = int(rng.integers(6, 20))
         stem = rng.permutation(n_ids)[:int(rng.integers(1, 4))].tolist()
