@@ -142,6 +142,85 @@ def run_workload(batch, steps, warmup, torch, B, split_segments=0, fuse=True, ex
     return res
 
 
+def run_session_loop(steps, warmup, torch, B, wl, per_chain_append=False):
+    """The multi-turn workload as one closed loop on the device: for turn 0..7, plan the batch of
+    all sessions' new tokens over (shared prompt + the history appended so far), run the step,
+    then append each session's next 1024 KV rows (4 segments) to its chain (tl_pool_append_batch:
+    all 64 chains in one call; `per_chain_append`: 64 calls of tl_pool_append).
+    Returns per-turn times (HIP events; host clock for the plans) averaged over `steps` passes."""
+    import numpy as np
+    turns = [wl.multiturn(turn=t) for t in range(8)]
+    b0 = turns[0]
+    dev = "cuda"
+    shape = (b0.n_slots, b0.seg_len, b0.kv_heads, b0.head_dim)
+    pk = torch.zeros(shape, dtype=torch.bfloat16, device=dev)
+    pv = torch.zeros(shape, dtype=torch.bfloat16, device=dev)
+    b0.fill_pool(pk, pv)                                   # the shared prompt's 16 segments
+    n_s, grow = b0.n_req, 4 * b0.seg_len
+    H, D = b0.q_heads, b0.head_dim
+    qs = [(t.q(dev), t.k_new(dev), t.v_new(dev)) for t in turns]
+    # rows each session appends after a turn (its 256 new tokens + 768 filler tokens): seeded noise
+    rows_k = wl.normal_bf16_range(b0.seed, wl.STREAM_KNEW, 1 << 40, n_s * grow * b0.kv_heads * D, dev).view(n_s, grow, b0.kv_heads, D)
+    rows_v = wl.normal_bf16_range(b0.seed, wl.STREAM_VNEW, 1 << 40, n_s * grow * b0.kv_heads * D, dev).view(n_s, grow, b0.kv_heads, D)
+    out = torch.empty((b0.n_tokens, H, D), dtype=torch.bfloat16, device=dev)
+    lse = torch.empty((b0.n_tokens, H), dtype=torch.float32, device=dev)
+    flags = B.TL_PLAN_SELF_BLOCK | B.TL_PLAN_FUSE_ROWS
+    shared = [int(x) for x in b0.pool_ids]
+    row_ptr = b0.req_row_ptr
+    acc = {"attn_ms": np.zeros(8), "append_ms": np.zeros(8), "plan_ms": np.zeros(8), "flops": np.zeros(8)}
+    wall = 0.0
+    for rep in range(warmup + steps):
+        pool = B.tl_pool_create(b0.n_slots, b0.seg_len, b0.kv_heads, D, pk, pv)
+        B.tl_pool_adopt(pool, b0.pool_ids, b0.pool_slots, b0.pool_fills)
+        chains = [[] for _ in range(n_s)]
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(8)]
+        plan_ms, flops, plans = [], [], []
+        torch.cuda.synchronize()
+        t_start = time.perf_counter()
+        for t in range(8):
+            lists = [shared + c for c in chains]
+            seg_ptr = np.concatenate([[0], np.cumsum([len(l) for l in lists])]).astype(np.int32)
+            ids = np.array([i for l in lists for i in l], dtype=np.uint64)
+            t0 = time.perf_counter()
+            plan = B.tl_plan_create(pool, H, row_ptr, seg_ptr, ids, flags, 0)
+            plan_ms.append((time.perf_counter() - t0) * 1e3)
+            info = B.tl_plan_get_info(plan)
+            assert info.n_fused_tokens == b0.n_tokens      # every request takes the one-pass kernel
+            flops.append(4.0 * H * D * (info.prefix_pairs + info.self_pairs))
+            q, kn, vn = qs[t]
+            ev[t][0].record()
+            B.tl_fused_attn(pool, plan, q, kn, vn, b0.scale, out, True, lse)
+            ev[t][1].record()
+            new_ids = [[wl._private_id(s_, len(shared) + len(chains[s_]) + j) for j in range(4)] for s_ in range(n_s)]
+            if per_chain_append:
+                for s_ in range(n_s):
+                    B.tl_pool_append(pool, None, new_ids[s_], rows_k[s_], rows_v[s_], grow)
+            else:
+                B.tl_pool_append_batch(pool, [None] * n_s, new_ids, [grow] * n_s, rows_k, rows_v)
+            for s_ in range(n_s):
+                chains[s_] += new_ids[s_]
+            ev[t][2].record()
+            plans.append(plan)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t_start
+        if rep >= warmup:
+            wall += dt
+            acc["attn_ms"] += [e[0].elapsed_time(e[1]) for e in ev]
+            acc["append_ms"] += [e[1].elapsed_time(e[2]) for e in ev]
+            acc["plan_ms"] += plan_ms
+            acc["flops"] = np.array(flops)
+        for plan in plans:
+            B.tl_plan_destroy(plan)
+        B.tl_pool_destroy(pool)
+    for k in ("attn_ms", "append_ms", "plan_ms"):
+        acc[k] = acc[k] / steps
+    acc["wall_ms"] = wall * 1e3 / steps
+    acc["tokens"] = 8 * b0.n_tokens
+    acc["append_bytes_per_turn"] = 2.0 * 2 * n_s * grow * b0.kv_heads * D * 2     # K and V, read + written
+    acc["checksum"] = float(out.float().abs().mean().item())
+    return acc
+
+
 def algorithmic_work(batch, info):
     """Flops and minimum HBM bytes of one pass (what the method must do)."""
     hq, hkv, d = batch.q_heads, batch.kv_heads, batch.head_dim
@@ -212,6 +291,10 @@ def main():
     ap.add_argument("--three-step", action="store_true",
                     help="plan without TL_PLAN_FUSE_ROWS: every request goes through partials and the merge")
     ap.add_argument("--no-decode", action="store_true", help="skip the appended decode measurement")
+    ap.add_argument("--session-loop", action="store_true",
+                    help="multi-turn workload as a closed loop: 8 turns of plan + attention + tl_pool_append")
+    ap.add_argument("--per-chain-append", action="store_true",
+                    help="with --session-loop: one tl_pool_append call per session instead of one batched call per turn")
     ap.add_argument("--graph", action="store_true",
                     help="also time the step replayed from a HIP graph (reported as graph_ms_per_step)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -230,6 +313,29 @@ def main():
     B.load_library()
     if args.calibrate_copy:
         calibrate_copy(torch)
+        return
+
+    if args.session_loop:
+        r = run_session_loop(args.steps, max(args.warmup, 1), torch, B, wl, args.per_chain_append)
+        gpu_ms = float(r["attn_ms"].sum() + r["append_ms"].sum())
+        ach = float(r["flops"].sum()) / (float(r["attn_ms"].sum()) * 1e-3) / 1e12
+        print(json.dumps({
+            "metric": "merged tok/s (one layer; 8 turns of 64 sessions: plan, one-pass attention, append of the turn's KV)",
+            "value": r["tokens"] / (r["wall_ms"] * 1e-3), "unit": "tok/s", "n_gpus": 1, "steps": args.steps,
+            "warmup": max(args.warmup, 1), "ms_per_step": r["wall_ms"], "higher_is_better": True, "scaling": "weak",
+            "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": "multiturn[closed loop, turns 0-7]", "new_tokens": r["tokens"]},
+            "roofline": {"kernel": "row_tile_attn_kernel<one pass>", "bound": "mfma", "achieved": ach,
+                         "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS, "traffic": None,
+                         "algorithmic_flops": float(r["flops"].sum()), "avg_kernel_ms": float(r["attn_ms"].mean())},
+            "per_turn_ms": {"attention": [round(float(x), 4) for x in r["attn_ms"]],
+                            "append": [round(float(x), 4) for x in r["append_ms"]],
+                            "plan_host": [round(float(x), 4) for x in r["plan_ms"]]},
+            "gpu_ms_per_pass": gpu_ms,
+            "append": {"bytes_per_turn": r["append_bytes_per_turn"],
+                       "GB_per_s": r["append_bytes_per_turn"] / (float(r["append_ms"].mean()) * 1e-3) / 1e9,
+                       "launches_per_turn": 64 if args.per_chain_append else 2},
+        }))
         return
 
     maker = {"prefill": wl.prefill, "decode": wl.decode, "longctx": wl.longctx, "tiny": wl.tiny,

@@ -87,13 +87,26 @@ tl_status tl_pool_put(tl_pool* pool, uint64_t segment_id, const void* k_src_dev,
  * (its remaining tokens are zeroed).  Each new id takes the lowest-numbered free slot.
  * k_rows_dev/v_rows_dev: device, [n_rows, kv_heads, head_dim] bf16.  new_ids: host [n_new];
  * n_new must be exactly ceil(max(0, n_rows - room in the tail) / seg_len).
- * new_slots_out: host [n_new] or NULL.  One kernel launch per 48 destination slots.
+ * new_slots_out: host [n_new] or NULL.  One kernel launch per 128 destination slots.
  * The tail must hold exactly one reference (a segment somebody else also uses does not grow).
  * Nothing is written or registered on error: TL_ENOTFOUND (tail not resident), TL_EINVAL
  * (tail shared, wrong n_new, id repeated or already resident), TL_EFULL. */
 tl_status tl_pool_append(tl_pool* pool, int32_t has_tail, uint64_t tail_id, const uint64_t* new_ids, int32_t n_new,
                          const void* k_rows_dev, const void* v_rows_dev, int32_t n_rows, int32_t* new_slots_out,
                          void* stream);
+
+/* tl_pool_append for n_chains chains in one call (the sessions of a batch after a turn): chain c
+ * appends rows [row_ptr[c], row_ptr[c+1]) of k_rows_dev/v_rows_dev, first into the slot of
+ * tail_ids[c] if has_tail[c] is non-zero, then into new segments new_ids[new_ptr[c] .. new_ptr[c+1]).
+ * has_tail, tail_ids (may be NULL if no chain has a tail): host [n_chains]; new_ptr, row_ptr:
+ * host [n_chains + 1], starting at 0, non-decreasing; new_slots_out: host [new_ptr[n_chains]] or
+ * NULL.  Chains are served in order, each new id taking the lowest-numbered free slot, so the
+ * result equals that of n_chains single calls; the rows of all chains go out in one kernel
+ * launch per 128 destination slots.  Every chain is validated before anything is written or
+ * registered: errors as for tl_pool_append, and TL_EINVAL if two chains name the same tail. */
+tl_status tl_pool_append_batch(tl_pool* pool, int32_t n_chains, const int32_t* has_tail, const uint64_t* tail_ids,
+                               const int32_t* new_ptr, const uint64_t* new_ids, const int32_t* row_ptr,
+                               const void* k_rows_dev, const void* v_rows_dev, int32_t* new_slots_out, void* stream);
 
 /* Register segments whose KV the caller has already written into the pool memory
  * (no copy; the slots' tails are left as they are).  ids/slots/fills: host, [n].

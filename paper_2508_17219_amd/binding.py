@@ -46,6 +46,7 @@ _SIGNATURES = {
     "tl_pool_destroy": (_I32, [_P]),
     "tl_pool_put": (_I32, [_P, _U64, _P, _P, _I32, _I32, C.POINTER(_I32), _P]),
     "tl_pool_append": (_I32, [_P, _I32, _U64, _P, _I32, _P, _P, _I32, _P, _P]),
+    "tl_pool_append_batch": (_I32, [_P, _I32, _P, _P, _P, _P, _P, _P, _P, _P, _P]),
     "tl_pool_adopt": (_I32, [_P, _P, _P, _P, _I32, _P]),
     "tl_pool_release": (_I32, [_P, _U64]),
     "tl_pool_evict_lru": (_I32, [_P, C.POINTER(_U64)]),
@@ -141,6 +142,26 @@ def tl_pool_append(pool: int, tail_id, new_ids, k_rows, v_rows, n_rows: int, str
     _check(load_library().tl_pool_append(pool, 0 if tail_id is None else 1, 0 if tail_id is None else int(tail_id),
                                          ids.ctypes.data if len(ids) else None, len(ids), _dev(k_rows), _dev(v_rows),
                                          n_rows, slots.ctypes.data if len(ids) else None, _stream(stream)))
+    return slots
+
+
+def tl_pool_append_batch(pool: int, tail_ids, new_ids, row_counts, k_rows, v_rows, stream=None) -> np.ndarray:
+    """One call for many chains.  tail_ids: per chain an id or None; new_ids: per chain a list of
+    ids; row_counts: per chain the number of rows it takes from k_rows/v_rows (in chain order).
+    Returns the slots given to the new ids, flattened in chain order."""
+    n = len(tail_ids)
+    has_tail = np.array([0 if t is None else 1 for t in tail_ids], np.int32)
+    tails = np.array([0 if t is None else int(t) for t in tail_ids], np.uint64)
+    new_ptr = np.zeros(n + 1, np.int32)
+    new_ptr[1:] = np.cumsum([len(x) for x in new_ids])
+    ids = np.array([i for x in new_ids for i in x], np.uint64)
+    row_ptr = np.zeros(n + 1, np.int32)
+    row_ptr[1:] = np.cumsum(row_counts)
+    slots = np.full(len(ids), -1, np.int32)
+    _check(load_library().tl_pool_append_batch(pool, n, has_tail.ctypes.data, tails.ctypes.data, new_ptr.ctypes.data,
+                                               ids.ctypes.data if len(ids) else None, row_ptr.ctypes.data,
+                                               _dev(k_rows), _dev(v_rows), slots.ctypes.data if len(ids) else None,
+                                               _stream(stream)))
     return slots
 
 

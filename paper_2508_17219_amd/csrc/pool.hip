@@ -58,7 +58,7 @@ __global__ void gather_slots_kernel(uint4* __restrict__ out, const uint4* __rest
 struct AppendChunk {
   int32_t slot, tok, n, src_row, zero_to, new_fill;
 };
-constexpr int kAppendChunks = 48;
+constexpr int kAppendChunks = 128;   // 3 KB of kernel arguments
 struct AppendArgs {
   AppendChunk c[kAppendChunks];
 };
@@ -257,56 +257,78 @@ tl_status tl_pool_put(tl_pool* pool, uint64_t segment_id, const void* k_src_dev,
   return TL_OK;
 }
 
-tl_status tl_pool_append(tl_pool* pool, int32_t has_tail, uint64_t tail_id, const uint64_t* new_ids, int32_t n_new,
-                         const void* k_rows_dev, const void* v_rows_dev, int32_t n_rows, int32_t* new_slots_out,
-                         void* stream) {
-  if (!pool || n_rows < 0 || n_new < 0 || (n_new > 0 && !new_ids)) TL_FAIL(TL_EINVAL, "tl_pool_append: bad argument");
-  if (n_rows > 0 && (!k_rows_dev || !v_rows_dev)) TL_FAIL(TL_EINVAL, "tl_pool_append: null source");
-  const int32_t C = pool->seg_len;
-  // ---- validate everything first ----
-  int32_t tail_slot = -1, room = 0;
-  if (has_tail) {
-    auto it = pool->slot_of.find(tail_id);
-    if (it == pool->slot_of.end()) TL_FAIL(TL_ENOTFOUND, "tl_pool_append: tail id %llu not resident", (unsigned long long)tail_id);
-    tail_slot = it->second;
-    if (pool->refcnt[tail_slot] != 1)
-      TL_FAIL(TL_EINVAL, "tl_pool_append: tail id %llu has %d references, a shared segment does not grow",
-              (unsigned long long)tail_id, pool->refcnt[tail_slot]);
-    room = C - pool->fill[tail_slot];
+tl_status tl_pool_append_batch(tl_pool* pool, int32_t n_chains, const int32_t* has_tail, const uint64_t* tail_ids,
+                               const int32_t* new_ptr, const uint64_t* new_ids, const int32_t* row_ptr,
+                               const void* k_rows_dev, const void* v_rows_dev, int32_t* new_slots_out, void* stream) {
+  if (!pool || n_chains < 0) TL_FAIL(TL_EINVAL, "tl_pool_append: bad argument");
+  if (n_chains == 0) return TL_OK;
+  if (!has_tail || !new_ptr || !row_ptr) TL_FAIL(TL_EINVAL, "tl_pool_append: null chain arrays");
+  if (new_ptr[0] != 0 || row_ptr[0] != 0) TL_FAIL(TL_EINVAL, "tl_pool_append: offsets must start at 0");
+  for (int32_t c = 0; c < n_chains; ++c) {
+    if (new_ptr[c + 1] < new_ptr[c] || row_ptr[c + 1] < row_ptr[c]) TL_FAIL(TL_EINVAL, "tl_pool_append: offsets must not decrease");
+    if (has_tail[c] && !tail_ids) TL_FAIL(TL_EINVAL, "tl_pool_append: null tail ids");
   }
-  const int32_t rest = n_rows > room ? n_rows - room : 0;
-  const int32_t need = (rest + C - 1) / C;
-  if (n_new != need) TL_FAIL(TL_EINVAL, "tl_pool_append: %d rows need exactly %d new segments, %d given", n_rows, need, n_new);
+  const int32_t n_new_all = new_ptr[n_chains], n_rows_all = row_ptr[n_chains];
+  if (n_new_all > 0 && !new_ids) TL_FAIL(TL_EINVAL, "tl_pool_append: null new ids");
+  if (n_rows_all > 0 && (!k_rows_dev || !v_rows_dev)) TL_FAIL(TL_EINVAL, "tl_pool_append: null source");
+  const int32_t C = pool->seg_len;
+  // ---- validate every chain first ----
+  std::vector<int32_t> tail_slot(n_chains, -1), room(n_chains, 0);
   {
+    std::unordered_map<int32_t, int> tails;
+    for (int32_t c = 0; c < n_chains; ++c) {
+      const int32_t n_rows = row_ptr[c + 1] - row_ptr[c], n_new = new_ptr[c + 1] - new_ptr[c];
+      if (has_tail[c]) {
+        auto it = pool->slot_of.find(tail_ids[c]);
+        if (it == pool->slot_of.end())
+          TL_FAIL(TL_ENOTFOUND, "tl_pool_append: tail id %llu not resident", (unsigned long long)tail_ids[c]);
+        tail_slot[c] = it->second;
+        if (pool->refcnt[tail_slot[c]] != 1)
+          TL_FAIL(TL_EINVAL, "tl_pool_append: tail id %llu has %d references, a shared segment does not grow",
+                  (unsigned long long)tail_ids[c], pool->refcnt[tail_slot[c]]);
+        if (n_rows > 0 && !tails.emplace(tail_slot[c], c).second)
+          TL_FAIL(TL_EINVAL, "tl_pool_append: tail id %llu is the tail of two chains", (unsigned long long)tail_ids[c]);
+        room[c] = C - pool->fill[tail_slot[c]];
+      }
+      const int32_t rest = n_rows > room[c] ? n_rows - room[c] : 0;
+      const int32_t need = (rest + C - 1) / C;
+      if (n_new != need)
+        TL_FAIL(TL_EINVAL, "tl_pool_append: %d rows need exactly %d new segments, %d given", n_rows, need, n_new);
+    }
     std::unordered_map<uint64_t, int> seen;
-    for (int32_t i = 0; i < n_new; ++i) {
+    for (int32_t i = 0; i < n_new_all; ++i) {
       if (pool->slot_of.count(new_ids[i])) TL_FAIL(TL_EINVAL, "tl_pool_append: id %llu already resident", (unsigned long long)new_ids[i]);
       if (!seen.emplace(new_ids[i], i).second) TL_FAIL(TL_EINVAL, "tl_pool_append: id %llu listed twice", (unsigned long long)new_ids[i]);
     }
   }
-  if (pool->n_slots - pool->n_used < need) TL_FAIL(TL_EFULL, "tl_pool_append: %d free slots, %d needed", pool->n_slots - pool->n_used, need);
-  if (n_rows == 0) return TL_OK;
+  if (pool->n_slots - pool->n_used < n_new_all)
+    TL_FAIL(TL_EFULL, "tl_pool_append: %d free slots, %d needed", pool->n_slots - pool->n_used, n_new_all);
+  if (n_rows_all == 0) return TL_OK;
   hipStream_t st = (hipStream_t)stream;
   tl_status rc = pool_device_ready(pool, st);
   if (rc != TL_OK) return rc;
 
   // ---- place the rows (host state changes from here on; no failure path below but HIP's) ----
   std::vector<AppendChunk> chunks;
-  int32_t row = 0;
-  if (has_tail && room > 0) {
-    const int32_t n = n_rows < room ? n_rows : room;
-    chunks.push_back(AppendChunk{tail_slot, pool->fill[tail_slot], n, 0, 0, pool->fill[tail_slot] + n});
-    pool->fill[tail_slot] += n;
-    pool->stamp[tail_slot] = ++pool->clock;
-    row = n;
-  }
-  for (int32_t i = 0; i < n_new; ++i) {
-    const int32_t n = n_rows - row < C ? n_rows - row : C;
-    const int32_t s = take_slot(pool, -1);
-    occupy(pool, s, new_ids[i], n);
-    chunks.push_back(AppendChunk{s, 0, n, row, C, n});
-    if (new_slots_out) new_slots_out[i] = s;
-    row += n;
+  for (int32_t c = 0; c < n_chains; ++c) {
+    const int32_t n_rows = row_ptr[c + 1] - row_ptr[c];
+    int32_t row = 0;
+    if (has_tail[c] && room[c] > 0 && n_rows > 0) {
+      const int32_t ts = tail_slot[c];
+      const int32_t n = n_rows < room[c] ? n_rows : room[c];
+      chunks.push_back(AppendChunk{ts, pool->fill[ts], n, row_ptr[c], 0, pool->fill[ts] + n});
+      pool->fill[ts] += n;
+      pool->stamp[ts] = ++pool->clock;
+      row = n;
+    }
+    for (int32_t i = new_ptr[c]; i < new_ptr[c + 1]; ++i) {
+      const int32_t n = n_rows - row < C ? n_rows - row : C;
+      const int32_t s = take_slot(pool, -1);
+      occupy(pool, s, new_ids[i], n);
+      chunks.push_back(AppendChunk{s, 0, n, row_ptr[c] + row, C, n});
+      if (new_slots_out) new_slots_out[i] = s;
+      row += n;
+    }
   }
   const size_t row16 = (size_t)pool->kv_heads * pool->head_dim * 2 / 16;
   const size_t slot16 = row16 * C;
@@ -321,6 +343,16 @@ tl_status tl_pool_append(tl_pool* pool, int32_t has_tail, uint64_t tail_id, cons
   }
   TL_HIP(hipGetLastError());
   return TL_OK;
+}
+
+tl_status tl_pool_append(tl_pool* pool, int32_t has_tail, uint64_t tail_id, const uint64_t* new_ids, int32_t n_new,
+                         const void* k_rows_dev, const void* v_rows_dev, int32_t n_rows, int32_t* new_slots_out,
+                         void* stream) {
+  if (!pool || n_rows < 0 || n_new < 0 || (n_new > 0 && !new_ids)) TL_FAIL(TL_EINVAL, "tl_pool_append: bad argument");
+  const int32_t tail_flag = has_tail ? 1 : 0;
+  const int32_t new_ptr[2] = {0, n_new}, row_ptr[2] = {0, n_rows};
+  return tl_pool_append_batch(pool, 1, &tail_flag, &tail_id, new_ptr, new_ids, row_ptr, k_rows_dev, v_rows_dev,
+                              new_slots_out, stream);
 }
 
 tl_status tl_pool_adopt(tl_pool* pool, const uint64_t* ids, const int32_t* slots, const int32_t* fills, int32_t n,

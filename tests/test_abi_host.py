@@ -283,6 +283,35 @@ def test_append_refuses_bad_calls_without_changing_anything():
     B.tl_pool_destroy(pool)
 
 
+def test_batched_append_validates_every_chain_before_anything_changes():
+    pool = B.tl_pool_create(6, 64, 1, 128, FAKE_K, FAKE_V)
+    B.tl_pool_adopt(pool, [10, 11, 12], [0, 1, 2], [64, 20, 30])
+
+    def state():
+        return (B.tl_pool_used(pool), B.tl_pool_lookup(pool, [10, 11, 12, 20, 21, 22, 23]).tolist(),
+                B.tl_pool_fills(pool, list(range(6))).tolist())
+
+    before = state()
+    cases = [
+        # (tails, new ids per chain, rows per chain), status: the fault sits in the LAST chain each time
+        (([11, 12], [[], [20]], [10, 34]), B.TL_EINVAL),            # 34 rows fit chain 1's tail exactly
+        (([11, 99], [[], []], [10, 3]), B.TL_ENOTFOUND),            # unknown tail
+        (([11, 11], [[], []], [5, 5]), B.TL_EINVAL),                # two chains with one tail
+        (([None, None], [[20], [20]], [10, 10]), B.TL_EINVAL),      # id given to two chains
+        (([None, 12], [[20], [10]], [10, 40]), B.TL_EINVAL),        # id already resident
+        (([None, None], [[20, 21], [22, 23]], [100, 100]), B.TL_EFULL),   # 4 slots needed, 3 free
+    ]
+    for (tails, ids, rows), status in cases:
+        with pytest.raises(B.TokenLakeError) as e:
+            B.tl_pool_append_batch(pool, tails, ids, rows, FAKE_K, FAKE_V)
+        assert e.value.status == status, (tails, ids, rows, e.value)
+        assert state() == before
+    B.tl_pool_append_batch(pool, [], [], [], None, None)               # no chains
+    B.tl_pool_append_batch(pool, [11, None], [[], []], [0, 0], None, None)   # chains with nothing to add
+    assert state() == before
+    B.tl_pool_destroy(pool)
+
+
 def test_hot_slots_match_the_oracles_segment_loads():
     for b in (wl.multiturn(turn=3), wl.prefill(seed=9, n_req=5, new_tokens=40, lo=300, hi=900, seg_len=128, n_slots=64, n_shared=2),
               wl.longctx(n_req=2, entries=40, new_tokens=64, n_ids=25, n_slots=32)):

@@ -506,6 +506,95 @@ def test_append_rows_grow_chains_like_the_oracle():
     B.tl_pool_destroy(pool)
 
 
+def test_batched_append_equals_the_oracles_chain_by_chain_appends():
+    """tl_pool_append_batch (all chains of a turn in one call, one launch per 128 destination
+    slots) against the oracle appending chain after chain: same slots, fills and pool bytes."""
+    _say("batched append")
+    seed, hkv, C, n_slots, d = 37, 2, 64, 800, 128
+    dev = "cuda"
+    rng = np.random.default_rng(seed)
+    pk = torch.full((n_slots, C, hkv, d), float("nan"), dtype=torch.bfloat16, device=dev)
+    pv = torch.full((n_slots, C, hkv, d), float("nan"), dtype=torch.bfloat16, device=dev)
+    pool = B.tl_pool_create(n_slots, C, hkv, d, pk, pv)
+    opk = np.zeros((n_slots, C, hkv, d), np.uint16)
+    opv = np.zeros_like(opk)
+    table = orc.SlotTable(n_slots, C)
+    n_chains = 120
+    most_chunks = 0
+    chains = [[] for _ in range(n_chains)]
+    totals = [0] * n_chains
+    next_id, cursor = 1000, 0
+    per = hkv * d
+    for turn in range(3):
+        counts = [int(rng.choice([0, 1, C - 1, C, C + 1, 2 * C + 7])) for _ in range(n_chains)]
+        tails, ids = [], []
+        for c in range(n_chains):
+            tail = chains[c][-1] if chains[c] and totals[c] % C else None
+            room = C - totals[c] % C if tail is not None else 0
+            need = -(-max(0, counts[c] - room) // C)
+            tails.append(tail)
+            ids.append(list(range(next_id, next_id + need)))
+            next_id += need
+        most_chunks = max(most_chunks, sum(len(x) for x in ids) + sum(1 for c in range(n_chains) if tails[c] is not None and counts[c]))
+        n = sum(counts)
+        rows = []
+        for stream in (wl.STREAM_KNEW, wl.STREAM_VNEW):
+            rows.append(wl.normal_bf16_range(seed, stream, cursor * per, n * per, dev).view(n, hkv, d))
+            rows.append(wl.bits_u16(wl.normal_bf16_range(seed, stream, cursor * per, n * per, "cpu").view(n, hkv, d)))
+        cursor += n
+        kg, kc, vg, vc = rows
+        got = B.tl_pool_append_batch(pool, tails, ids, counts, kg, vg)
+        r0 = 0
+        for c in range(n_chains):
+            if counts[c]:
+                orc.append_rows(opk, opv, table, tails[c], ids[c], kc[r0:r0 + counts[c]], vc[r0:r0 + counts[c]])
+            r0 += counts[c]
+            chains[c] += ids[c]
+            totals[c] += counts[c]
+        flat = [i for x in ids for i in x]
+        assert got.tolist() == table.lookup(flat).tolist()
+    every = [i for ch in chains for i in ch]
+    assert most_chunks > 128                            # at least one call needed a second launch
+    slots = table.lookup(every)
+    assert np.array_equal(B.tl_pool_lookup(pool, every), slots)
+    assert np.array_equal(B.tl_pool_fills(pool, slots), table.fill(slots))
+    gk = torch.empty((len(slots), C, hkv, d), dtype=torch.bfloat16, device=dev)
+    gv = torch.empty_like(gk)
+    B.tl_pool_gather(pool, slots, gk, gv)
+    torch.cuda.synchronize()
+    gkb, gvb = wl.bits_u16(gk), wl.bits_u16(gv)
+    for i, (s_, f) in enumerate(zip(slots, table.fill(slots))):
+        assert np.array_equal(gkb[i, :f], opk[s_, :f]) and np.array_equal(gvb[i, :f], opv[s_, :f]), "slot %d" % s_
+        assert not gkb[i, f:].any() and not gvb[i, f:].any()
+    # the device's fill table is what the attention kernels mask with: a plan over every chain
+    lq = 3
+    req_ids = [ch for ch in chains if ch]
+    b_seg_ptr = np.concatenate([[0], np.cumsum([len(x) for x in req_ids])]).astype(np.int32)
+    b_row_ptr = (np.arange(len(req_ids) + 1) * lq).astype(np.int32)
+    hq = 2 * hkv
+    plan = B.tl_plan_create(pool, hq, b_row_ptr, b_seg_ptr, np.array([i for x in req_ids for i in x], np.uint64), 0)
+    info = B.tl_plan_get_info(plan)
+    T = lq * len(req_ids)
+    qg = wl.normal_bf16_range(seed, wl.STREAM_Q, 0, T * hq * d, dev).view(T, hq, d)
+    qc = wl.bits_u16(wl.normal_bf16_range(seed, wl.STREAM_Q, 0, T * hq * d, "cpu").view(T, hq, d))
+    outp = torch.full((info.n_partial_rows, hq, d), float("nan"), dtype=torch.float32, device=dev)
+    lsep = torch.full((info.n_partial_rows, hq), float("nan"), dtype=torch.float32, device=dev)
+    out = torch.full((T, hq, d), float("nan"), dtype=torch.float32, device=dev)
+    lse = torch.full((T, hq), float("nan"), dtype=torch.float32, device=dev)
+    scale = 1.0 / math.sqrt(d)
+    B.tl_segment_attn(pool, plan, qg, scale, outp, lsep)
+    B.tl_merge(plan, outp, lsep, out, False, lse)
+    torch.cuda.synchronize()
+    for r in range(0, len(req_ids), 5):
+        sl = table.lookup(req_ids[r])
+        want_o, want_l = orc.request_attention(qc[r * lq:(r + 1) * lq], opk, opv, sl, table.fill(sl), None, None, scale)
+        got_o = out[r * lq:(r + 1) * lq].double().cpu().numpy()
+        got_l = lse[r * lq:(r + 1) * lq].double().cpu().numpy()
+        assert np.abs(got_o - want_o).max() <= H.TOL_O and np.abs(got_l - want_l).max() <= H.TOL_LSE
+    B.tl_plan_destroy(plan)
+    B.tl_pool_destroy(pool)
+
+
 @pytest.mark.parametrize("hq,hkv", [(4, 4), (8, 4), (32, 1), (16, 16), (28, 4), (6, 2), (5, 1), (24, 2)])
 def test_head_group_sizes_from_mha_to_one_kv_head(hq, hkv):
     """The paper's own model is multi-head (one kv head per q head); the named configurations are
