@@ -55,6 +55,70 @@ __global__ __launch_bounds__(256) void lse_merge_kernel(const float* __restrict_
   }
 }
 
+// The same recombination for tokens with many partials (split-K decode: tens to hundreds per
+// token, and few tokens): one workgroup per (token, head), the partials dealt round-robin to
+// kMergeSlices slices of 32 lanes (a lane owns 4 channels), so that a long list is walked
+// kMergeSlices entries at a time.  The maximum is agreed on first, then every slice
+// accumulates with the same weights w_j = exp(LSE_j - M) as the kernel above, and slice 0 adds
+// the slices up in a fixed order.
+constexpr int kMergeSlices = 8;
+template <bool OUT_BF16>
+__global__ __launch_bounds__(32 * kMergeSlices) void lse_merge_sliced_kernel(
+    const float* __restrict__ part, const float* __restrict__ lse, const int32_t* __restrict__ mptr,
+    const int32_t* __restrict__ mrows, const int32_t* __restrict__ mtok, void* __restrict__ out,
+    float* __restrict__ lse_out, int q_heads) {
+  __shared__ float sh_m[kMergeSlices];
+  __shared__ float sh_w[kMergeSlices];
+  __shared__ float4 sh_acc[kMergeSlices][32];
+  const int t = mtok[blockIdx.x], hd = blockIdx.y;
+  const int b = mptr[t], e = mptr[t + 1];
+  const int sl = threadIdx.x >> 5, c4 = threadIdx.x & 31;
+  float m = -INFINITY;
+  for (int jj = b + sl; jj < e; jj += kMergeSlices) m = fmaxf(m, lse[(size_t)mrows[jj] * q_heads + hd]);
+  if (c4 == 0) sh_m[sl] = m;
+  __syncthreads();
+  float M = sh_m[0];
+#pragma unroll
+  for (int i = 1; i < kMergeSlices; ++i) M = fmaxf(M, sh_m[i]);
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  float wsum = 0.f;
+  if (M > -INFINITY) {
+    for (int jj = b + sl; jj < e; jj += kMergeSlices) {
+      const size_t row = (size_t)mrows[jj] * q_heads + hd;
+      const float w = expf(lse[row] - M);
+      const float4 v = ((const float4*)part)[row * 32 + c4];
+      acc.x += w * v.x; acc.y += w * v.y; acc.z += w * v.z; acc.w += w * v.w;
+      wsum += w;
+    }
+  }
+  sh_acc[sl][c4] = acc;
+  if (c4 == 0) sh_w[sl] = wsum;
+  __syncthreads();
+  if (sl == 0) {
+    acc = sh_acc[0][c4];
+    wsum = sh_w[0];
+#pragma unroll
+    for (int i = 1; i < kMergeSlices; ++i) {
+      const float4 v = sh_acc[i][c4];
+      acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+      wsum += sh_w[i];
+    }
+    if (M > -INFINITY) {
+      const float inv = 1.f / wsum;
+      acc.x *= inv; acc.y *= inv; acc.z *= inv; acc.w *= inv;
+    }
+    const size_t orow = (size_t)t * q_heads + hd;
+    if (OUT_BF16) {
+      typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
+      f32x4 f = {acc.x, acc.y, acc.z, acc.w};
+      ((bf16x4_t*)out)[orow * 32 + c4] = __builtin_convertvector(f, bf16x4_t);
+    } else {
+      ((float4*)out)[orow * 32 + c4] = acc;
+    }
+    if (lse_out && c4 == 0) lse_out[orow] = M > -INFINITY ? M + logf(wsum) : -INFINITY;
+  }
+}
+
 void fill_args(AttnArgs& a, const tl_plan* plan, const void* q, float scale, float* out, float* lse) {
   a.q = (const uint16_t*)q;
   a.tok = plan->d_tok;
@@ -159,6 +223,18 @@ tl_status tl_merge(tl_plan* plan, const float* out_partial, const float* lse, vo
   if (rc != TL_OK) return rc;
   if (plan->merge_tok.empty()) return TL_OK;
   hipStream_t st = (hipStream_t)stream;
+  // long merge lists (split-K): the sliced kernel, one workgroup per (token, head)
+  if (plan->merge_rows.size() >= (size_t)kMergeSlices * plan->merge_tok.size()) {
+    const dim3 grid((unsigned)plan->merge_tok.size(), (unsigned)plan->q_heads), block(32 * kMergeSlices);
+    if (out_is_bf16)
+      hipLaunchKernelGGL(lse_merge_sliced_kernel<true>, grid, block, 0, st, out_partial, lse, plan->d_merge_ptr,
+                         plan->d_merge_rows, plan->d_merge_tok, out_dev, lse_out, plan->q_heads);
+    else
+      hipLaunchKernelGGL(lse_merge_sliced_kernel<false>, grid, block, 0, st, out_partial, lse, plan->d_merge_ptr,
+                         plan->d_merge_rows, plan->d_merge_tok, out_dev, lse_out, plan->q_heads);
+    TL_HIP(hipGetLastError());
+    return TL_OK;
+  }
   const dim3 grid((unsigned)plan->merge_tok.size(), (unsigned)((plan->q_heads * 32 + 255) / 256)), block(256);
   if (out_is_bf16)
     hipLaunchKernelGGL(lse_merge_kernel<true>, grid, block, 0, st, out_partial, lse, plan->d_merge_ptr, plan->d_merge_rows,

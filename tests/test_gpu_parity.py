@@ -234,6 +234,36 @@ def test_edge_cases_empty_prefix_zero_tokens_and_no_keys():
     run.close()
 
 
+def test_merge_of_long_partial_lists():
+    """Split-K with one segment per unit gives a token tens of partials: the merge then runs as
+    one workgroup per (token, head) with the list dealt to eight slices.  A request without any
+    prefix, in a plan without the self block, has no partial at all: O = 0, LSE = -inf."""
+    _say("long merge lists")
+    d = wl.decode(seed=71, n_req=4, median=3000, sigma=0.3, cap=6000, seg_len=64, hq=16, hkv=2)
+    seg_ptr = d.req_seg_ptr
+    keep = [d.seg_ids[seg_ptr[r]:seg_ptr[r + 1]] for r in range(4)]
+    keep[2] = keep[2][:0]
+    d.seg_ids = np.concatenate(keep)
+    d.req_seg_ptr = np.concatenate([[0], np.cumsum([len(k) for k in keep])]).astype(np.int32)
+    for self_block in (True, False):
+        d.self_block = self_block
+        for bf16 in (False, True):
+            run = H.run_gpu(d, split_segments=1, out_bf16=bf16)
+            ex = B.tl_plan_export(run.plan)
+            n_lists = 4 if self_block else 3
+            assert len(ex["merge_rows"]) >= 8 * n_lists and run.info.n_units >= 100      # the sliced kernel's case
+            if not self_block:
+                assert torch.all(run.out[2] == 0) and torch.all(torch.isneginf(run.lse[2]))
+            if not bf16:
+                _check_all_requests(run, reqs=None if self_block else [0, 1, 3])
+            else:
+                want = H.run_gpu(d, split_segments=1)
+                assert (run.out.float() - want.out).abs().max().item() <= 2.0 ** -8 * max(1.0, want.out.abs().max().item())
+                assert torch.equal(run.lse, want.lse)
+                want.close()
+            run.close()
+
+
 def test_put_path_dedup_and_ragged_fill():
     _say("put path")
     b = wl.prefill(seed=14, n_req=2, new_tokens=33, lo=150, hi=400, seg_len=128, n_slots=16, n_shared=1)
