@@ -171,7 +171,7 @@ typedef struct tl_plan_info {
   int32_t self_row_base;   /* first row of the self block, -1 without TL_PLAN_SELF_BLOCK */
   int32_t n_tiles;         /* MFMA row tiles (work items with many query rows)           */
   int32_t n_units;         /* split-K units (work items with <= 16 rows per kv head)     */
-  int32_t n_causal_tiles;
+  int32_t n_causal_tiles;  /* row tiles of tl_causal_block (requests with two or more new tokens) */
   int32_t n_list_entries;  /* sum of request list lengths                                */
   int32_t n_merge_entries; /* sum over tokens of partials to merge                       */
   int64_t prefix_pairs;    /* sum over list entries of new_tokens(req) * fill(slot)      */
@@ -179,6 +179,8 @@ typedef struct tl_plan_info {
   int64_t unique_kv_tokens;/* valid tokens in the distinct slots the plan touches        */
   int32_t n_fused_tiles;   /* row tiles of tl_fused_attn (TL_PLAN_FUSE_ROWS)             */
   int32_t n_fused_tokens;  /* new tokens whose output tl_fused_attn writes               */
+  int32_t n_single_tokens; /* requests with one new token (decode): their self block is one key,
+                              written by a light kernel of tl_causal_block                */
 } tl_plan_info;
 
 /* req_row_ptr: host [n_req+1], offsets of each request's new tokens in the batch's Q

@@ -119,6 +119,29 @@ __global__ __launch_bounds__(32 * kMergeSlices) void lse_merge_sliced_kernel(
   }
 }
 
+// Self block of a request with one new token (decode): the token sees itself only, so its
+// partial is O = v, LSE = scale * <q, k>.  32 lanes per (token, head), 4 channels each.
+__global__ __launch_bounds__(256) void single_token_self_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
+                                                                const uint16_t* __restrict__ v,
+                                                                const int32_t* __restrict__ stok, int n_pairs,
+                                                                float* __restrict__ part, float* __restrict__ lse,
+                                                                int self_base, int q_heads, int group, float scale) {
+  const int pair = blockIdx.x * 8 + (threadIdx.x >> 5), c4 = threadIdx.x & 31;
+  if (pair >= n_pairs) return;              // whole 32-lane groups leave together
+  const int t = stok[pair / q_heads], hd = pair % q_heads, g = hd / group, kv_heads = q_heads / group;
+  const uint2 qb = ((const uint2*)(q + ((size_t)t * q_heads + hd) * kHeadDim))[c4];
+  const uint2 kb = ((const uint2*)(k + ((size_t)t * kv_heads + g) * kHeadDim))[c4];
+  const uint2 vb = ((const uint2*)(v + ((size_t)t * kv_heads + g) * kHeadDim))[c4];
+  auto lo = [](uint32_t w) { return __uint_as_float(w << 16); };
+  auto hi = [](uint32_t w) { return __uint_as_float(w & 0xffff0000u); };
+  float s = lo(qb.x) * lo(kb.x) + hi(qb.x) * hi(kb.x) + lo(qb.y) * lo(kb.y) + hi(qb.y) * hi(kb.y);
+#pragma unroll
+  for (int off = 16; off >= 1; off >>= 1) s += __shfl_xor(s, off, 32);
+  const size_t row = (size_t)(self_base + t) * q_heads + hd;
+  ((float4*)part)[row * 32 + c4] = make_float4(lo(vb.x), hi(vb.x), lo(vb.y), hi(vb.y));
+  if (c4 == 0) lse[row] = s * scale;
+}
+
 void fill_args(AttnArgs& a, const tl_plan* plan, const void* q, float scale, float* out, float* lse) {
   a.q = (const uint16_t*)q;
   a.tok = plan->d_tok;
@@ -185,6 +208,13 @@ tl_status tl_causal_block(tl_plan* plan, const void* q_dev, const void* k_new_de
   a.seg_len = 0;
   a.work = plan->d_ctiles;
   a.n_work = (int)plan->ctiles.size();
+  if (!plan->single_tok.empty()) {
+    const int n_pairs = (int)plan->single_tok.size() * plan->q_heads;
+    hipLaunchKernelGGL(single_token_self_kernel, dim3((unsigned)((n_pairs + 7) / 8)), dim3(256), 0, (hipStream_t)stream,
+                       (const uint16_t*)q_dev, (const uint16_t*)k_new_dev, (const uint16_t*)v_new_dev, plan->d_single_tok,
+                       n_pairs, out_partial, lse, plan->info.self_row_base, plan->q_heads, plan->group, scale);
+    TL_HIP(hipGetLastError());
+  }
   return launch_causal_row_tiles(a, a.n_work, (hipStream_t)stream);
 }
 

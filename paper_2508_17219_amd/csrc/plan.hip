@@ -261,6 +261,10 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
           n_part = (int32_t)p->part_tile.size() / 2 - part_off;
           n_fused_tokens += (int32_t)lq;
         }
+        if (!fused[r] && lq == 1) {      // a single new token sees itself only: no row tile for it
+          p->single_tok.push_back(a);
+          continue;
+        }
         for (int32_t t0 = a; t0 < b; t0 += tok_tile) {
           const int32_t n = std::min(tok_tile, b - t0);
           if (fused[r])
@@ -345,6 +349,7 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
     inf.unique_kv_tokens = uniq_tok;
     inf.n_fused_tiles = (int32_t)p->ftiles.size();
     inf.n_fused_tokens = n_fused_tokens;
+    inf.n_single_tokens = (int32_t)p->single_tok.size();
   } catch (const std::bad_alloc&) {
     rc = TL_ENOMEM;
     set_error("tl_plan_create: host allocation failed");
@@ -446,7 +451,8 @@ tl_status plan_device_ready(tl_plan* p) {
   const size_t b_part = al(sizeof(int32_t) * p->part_tile.size());
   const size_t b_ftiles = al(sizeof(Work) * p->ftiles.size());
   const size_t b_mtok = al(sizeof(int32_t) * p->merge_tok.size());
-  const size_t total = b_tiles + b_units + b_ctiles + b_tok + b_slots + b_mptr + b_mrows + b_tbase + b_part + b_ftiles + b_mtok + 256;
+  const size_t b_stok = al(sizeof(int32_t) * p->single_tok.size());
+  const size_t total = b_tiles + b_units + b_ctiles + b_tok + b_slots + b_mptr + b_mrows + b_tbase + b_part + b_ftiles + b_mtok + b_stok + 256;
   std::vector<char> host(total, 0);
   size_t off = 0;
   auto put = [&](const void* src, size_t bytes, size_t reserved) {
@@ -466,6 +472,7 @@ tl_status plan_device_ready(tl_plan* p) {
   const size_t o_part = put(p->part_tile.data(), sizeof(int32_t) * p->part_tile.size(), b_part);
   const size_t o_ftiles = put(p->ftiles.data(), sizeof(Work) * p->ftiles.size(), b_ftiles);
   const size_t o_mtok = put(p->merge_tok.data(), sizeof(int32_t) * p->merge_tok.size(), b_mtok);
+  const size_t o_stok = put(p->single_tok.data(), sizeof(int32_t) * p->single_tok.size(), b_stok);
   void* blob = nullptr;
   TL_HIP(hipMalloc(&blob, total));
   hipError_t e = hipMemcpy(blob, host.data(), total, hipMemcpyHostToDevice);
@@ -486,6 +493,7 @@ tl_status plan_device_ready(tl_plan* p) {
   p->d_part_tile = (int32_t*)(b + o_part);
   p->d_ftiles = (Work*)(b + o_ftiles);
   p->d_merge_tok = (int32_t*)(b + o_mtok);
+  p->d_single_tok = (int32_t*)(b + o_stok);
   p->on_device = true;
   return TL_OK;
 }

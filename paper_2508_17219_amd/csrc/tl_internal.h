@@ -82,6 +82,7 @@ struct tl_plan {
   std::vector<int32_t> merge_ptr, merge_rows;
   std::vector<tl::Work> tiles, units, ctiles, ftiles;   // ftiles: fused rows (pool tiles + causal block in one pass)
   std::vector<int32_t> merge_tok;  // tokens that tl_merge writes (all but the fused ones)
+  std::vector<int32_t> single_tok; // the new token of every request that has exactly one (not fused): self block = one key
   // heavy hitters, computed on first request from the resolved lists kept here
   std::vector<int32_t> list_slots, list_ptr, list_ntok;
   mutable bool hot_ready;
@@ -94,7 +95,7 @@ struct tl_plan {
   bool on_device;
   void* blob;
   tl::Work *d_tiles, *d_units, *d_ctiles, *d_ftiles;
-  int32_t *d_tok, *d_slots, *d_merge_ptr, *d_merge_rows, *d_tile_base, *d_part_tile, *d_merge_tok;
+  int32_t *d_tok, *d_slots, *d_merge_ptr, *d_merge_rows, *d_tile_base, *d_part_tile, *d_merge_tok, *d_single_tok;
 };
 
 namespace tl {

@@ -229,6 +229,24 @@ def test_shared_run_becomes_one_item_read_once():
     B.tl_pool_destroy(pool)
 
 
+def test_single_new_tokens_get_no_causal_row_tile():
+    """A request with one new token sees only itself in the self block: the plan lists it for
+    the light kernel and makes row tiles only for requests with two or more tokens."""
+    b = wl.decode(n_req=9, median=900, cap=4000, seg_len=128)
+    b.req_row_ptr = np.concatenate([[0], np.cumsum([1, 1, 2, 1, 0, 1, 5, 1, 1])]).astype(np.int32)
+    pool = _pool_for(b)
+    plan = B.tl_plan_create(pool, b.q_heads, b.req_row_ptr, b.req_seg_ptr, b.seg_ids, B.TL_PLAN_SELF_BLOCK)
+    info = B.tl_plan_get_info(plan)
+    assert info.n_single_tokens == 6 and info.n_causal_tiles == 2
+    assert info.self_pairs == 6 * 1 + 3 + 15
+    B.tl_plan_destroy(plan)
+    plan = B.tl_plan_create(pool, b.q_heads, b.req_row_ptr, b.req_seg_ptr, b.seg_ids, 0)
+    info = B.tl_plan_get_info(plan)
+    assert info.n_single_tokens == 0 and info.n_causal_tiles == 0
+    B.tl_plan_destroy(plan)
+    B.tl_pool_destroy(pool)
+
+
 def test_plan_errors():
     b = wl.tiny()
     pool = _pool_for(b)

@@ -669,7 +669,7 @@ def test_mixed_batch_of_prefill_chunks_and_decode_tokens():
     for split in (0, 2):
         run = H.run_gpu(b, fuse=True, split_segments=split)
         i = run.info
-        assert i.n_fused_tokens == 290 and i.n_units > 0 and i.n_tiles > 0 and i.n_causal_tiles == 5
+        assert i.n_fused_tokens == 290 and i.n_units > 0 and i.n_tiles > 0 and i.n_causal_tiles == 2 and i.n_single_tokens == 3
         _check_all_requests(run)
         run.close()
 
