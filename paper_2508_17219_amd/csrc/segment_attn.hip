@@ -447,28 +447,26 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
           ring[gp % (kDepth + 1)] = gp < 32 ? operand(gp, k_t, k_n, v_p, v_t) : operand(gp - 32, k_n, k_n, v_t, v_n);
         }
         const bf16x8 x = ring[gq % (kDepth + 1)];
-        if ((gi & 1) == 0) {
-          const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-          for (int rg = 0; rg < kRG; ++rg) {
-            if (step == 0) s1[rg] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, qreg[rg][idx], idx == 0 ? zero : s1[rg], 0, 0, 0);
-            else s0[rg] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, qreg[rg][idx], idx == 0 ? zero : s0[rg], 0, 0, 0);
-          }
-        } else {
-          const int sp = idx >> 2, d = idx & 3;
-#pragma unroll
-          for (int rg = 0; rg < kRG; ++rg)
-            o[rg][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, __builtin_bit_cast(bf16x8, step == 0 ? p1[rg][sp] : p0[rg][sp]), o[rg][d], 0, 0, 0);
-        }
-        // probabilities of the block whose scores are complete: kRG elements per group
+        // kRG MFMAs share the operand; each is followed by its own slice of the probabilities of
+        // the block whose scores are complete (one element), so that matrix and vector
+        // instructions alternate in the wave's instruction stream
 #pragma unroll
         for (int j = 0; j < kRG; ++j) {
+          if ((gi & 1) == 0) {
+            const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            if (step == 0) s1[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, qreg[j][idx], idx == 0 ? zero : s1[j], 0, 0, 0);
+            else s0[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, qreg[j][idx], idx == 0 ? zero : s0[j], 0, 0, 0);
+          } else {
+            const int sp = idx >> 2, d = idx & 3;
+            o[j][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, __builtin_bit_cast(bf16x8, step == 0 ? p1[j][sp] : p0[j][sp]), o[j][d], 0, 0, 0);
+          }
+          __builtin_amdgcn_sched_barrier(0);   // the MFMA first, then its slice (+0.8 % over leaving the order to the compiler)
           const int e = gi * kRG + j, rg = e >> 4, r = e & 15;
           f32x16& s = step == 0 ? s0[rg] : s1[rg];
           s[r] = fast_exp2(fmaf(s[r], c, -mc[rg]));
           // The row sum and the packing to bf16 trail the exponentials by one element / one pair, so
-          // that every group carries the same few vector instructions (a burst of eight adds and
-          // four converts in one group would hold up that group's MFMA) and none of them waits
+          // that every slice carries the same few vector instructions (a burst of eight adds and
+          // four converts in one place would hold up the MFMA behind it) and none of them waits
           // for the exponential issued just before it.
           u32x4 (&pp)[2] = step == 0 ? p0[rg] : p1[rg];
           if (r >= 1) l_run[rg] += s[r - 1];
@@ -477,8 +475,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
             l_run[rg] += s[15];
             set_pair(pp[1], 3, s[14], s[15]);
           }
+          __builtin_amdgcn_sched_barrier(0);
         }
-        __builtin_amdgcn_sched_barrier(0);
       }
       // this wave's share of K(t+2) / V(t+1) has landed; after the barrier everybody's has, and
       // everybody is done reading K(t) block 1 and V(t-1), the buffers the next loads overwrite
