@@ -142,6 +142,25 @@ def run_workload(batch, steps, warmup, torch, B, split_segments=0, fuse=True, ex
     return res
 
 
+def probe_mfma(torch, B, iters=8000, reps=5):
+    """Sustained rate of the matrix unit alone (no memory, LDS or vector work), with constant and
+    with changing operands: context for the published peak the roofline fractions are taken against."""
+    scratch = torch.zeros(16, dtype=torch.float32, device="cuda")
+    out = {}
+    for name, rnd in (("constant_operands", False), ("changing_random_operands", True)):
+        best = 0.0
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fl = B.tl_probe_mfma(rnd, iters, scratch)
+            e1.record()
+            torch.cuda.synchronize()
+            best = max(best, fl / (e0.elapsed_time(e1) * 1e-3) / 1e12)
+        out[name] = {"TFLOP/s": best, "frac_of_peak": best / PEAK_BF16_TFLOPS}
+    print(json.dumps({"probe": "mfma_f32_32x32x16_bf16 only, 1024 workgroups x 8 waves, %d x 32 instructions per wave, "
+                               "best of %d launches" % (iters, reps), "peak_TFLOP/s": PEAK_BF16_TFLOPS, **out}))
+
+
 def run_session_loop(steps, warmup, torch, B, wl, per_chain_append=False):
     """The multi-turn workload as one closed loop on the device: for turn 0..7, plan the batch of
     all sessions' new tokens over (shared prompt + the history appended so far), run the step,
@@ -297,6 +316,8 @@ def main():
                     help="with --session-loop: one tl_pool_append call per session instead of one batched call per turn")
     ap.add_argument("--graph", action="store_true",
                     help="also time the step replayed from a HIP graph (reported as graph_ms_per_step)")
+    ap.add_argument("--probe-mfma", action="store_true",
+                    help="only run the MFMA-only probe kernel (constant and changing operands) and exit")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a 1 GiB device copy (to scale rocprofv3 FETCH_SIZE/WRITE_SIZE) and exit")
     args = ap.parse_args()
@@ -311,6 +332,9 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     B.load_library()
+    if args.probe_mfma:
+        probe_mfma(torch, B)
+        return
     if args.calibrate_copy:
         calibrate_copy(torch)
         return

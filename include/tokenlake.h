@@ -289,6 +289,15 @@ tl_status tl_model_cache_load(double d, const int64_t* prefix_len, const int64_t
                               int32_t n_gpus, double mem_bw, double flops, double t_ideal, double* traffic_out,
                               double* flops_out, double* load_out);
 
+/* ------------------------------------------------------------------------------------
+ * Device probe (measurement aid, no part of the method): enqueues a kernel of nothing but bf16
+ * 32x32x16 MFMAs on 1024 workgroups of 8 waves, iters x 32 instructions per wave, with constant
+ * operands (random_operands = 0) or operands that differ from instruction to instruction.
+ * scratch_dev: device, at least 4 bytes (practically never written).  *flops_out = floating-
+ * point operations of the launch; the caller times it.  TL_EINVAL: iters outside 1..2^20.
+ * ------------------------------------------------------------------------------------ */
+tl_status tl_probe_mfma(int32_t random_operands, int32_t iters, void* scratch_dev, double* flops_out, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -46,6 +46,7 @@ _SIGNATURES = {
     "tl_pool_destroy": (_I32, [_P]),
     "tl_pool_put": (_I32, [_P, _U64, _P, _P, _I32, _I32, C.POINTER(_I32), _P]),
     "tl_pool_append": (_I32, [_P, _I32, _U64, _P, _I32, _P, _P, _I32, _P, _P]),
+    "tl_probe_mfma": (_I32, [_I32, _I32, _P, _PF64, _P]),
     "tl_pool_append_batch": (_I32, [_P, _I32, _P, _P, _P, _P, _P, _P, _P, _P, _P]),
     "tl_pool_adopt": (_I32, [_P, _P, _P, _P, _I32, _P]),
     "tl_pool_release": (_I32, [_P, _U64]),
@@ -271,6 +272,13 @@ def tl_causal_block(plan: int, q, k_new, v_new, scale: float, out_partial, lse, 
 def tl_fused_attn(pool: int, plan: int, q, k_new, v_new, scale: float, out, out_is_bf16: bool, lse_out=None, stream=None):
     _check(load_library().tl_fused_attn(pool, plan, _dev(q), _dev(k_new), _dev(v_new), scale, _dev(out),
                                         int(bool(out_is_bf16)), _dev(lse_out), _stream(stream)))
+
+
+def tl_probe_mfma(random_operands: bool, iters: int, scratch, stream=None) -> float:
+    """Enqueues the MFMA-only probe kernel; returns the floating-point operations of the launch."""
+    fl = C.c_double(0.0)
+    _check(load_library().tl_probe_mfma(int(bool(random_operands)), iters, _dev(scratch), C.byref(fl), _stream(stream)))
+    return fl.value
 
 
 def tl_merge(plan: int, out_partial, lse, out, out_is_bf16: bool, lse_out=None, stream=None):

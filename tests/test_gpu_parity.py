@@ -739,3 +739,14 @@ def test_step_replays_from_a_hip_graph(fuse):
         assert torch.equal(run.out, want_o) and torch.equal(run.lse, want_l), "replay %d differs" % rep
     del g
     run.close()
+
+
+def test_mfma_probe_runs_and_validates():
+    _say("mfma probe")
+    scratch = torch.zeros(16, dtype=torch.float32, device="cuda")
+    for rnd in (False, True):
+        assert B.tl_probe_mfma(rnd, 10, scratch) == 1024 * 8 * 10 * 32 * 32768.0
+    torch.cuda.synchronize()
+    assert torch.all(scratch == 0)
+    with pytest.raises(B.TokenLakeError):
+        B.tl_probe_mfma(True, 0, scratch)
