@@ -253,25 +253,26 @@ tl_status tl_merge(tl_plan* plan, const float* out_partial, const float* lse, vo
   if (rc != TL_OK) return rc;
   if (plan->merge_tok.empty()) return TL_OK;
   hipStream_t st = (hipStream_t)stream;
-  // long merge lists (split-K): the sliced kernel, one workgroup per (token, head)
-  if (plan->merge_rows.size() >= (size_t)kMergeSlices * plan->merge_tok.size()) {
-    const dim3 grid((unsigned)plan->merge_tok.size(), (unsigned)plan->q_heads), block(32 * kMergeSlices);
+  const int n_short = plan->n_merge_short, n_long = (int)plan->merge_tok.size() - n_short;
+  if (n_short > 0) {
+    const dim3 grid((unsigned)n_short, (unsigned)((plan->q_heads * 32 + 255) / 256)), block(256);
+    if (out_is_bf16)
+      hipLaunchKernelGGL(lse_merge_kernel<true>, grid, block, 0, st, out_partial, lse, plan->d_merge_ptr, plan->d_merge_rows,
+                         plan->d_merge_tok, out_dev, lse_out, plan->q_heads);
+    else
+      hipLaunchKernelGGL(lse_merge_kernel<false>, grid, block, 0, st, out_partial, lse, plan->d_merge_ptr, plan->d_merge_rows,
+                         plan->d_merge_tok, out_dev, lse_out, plan->q_heads);
+  }
+  if (n_long > 0) {
+    // long merge lists (split-K): the sliced kernel, one workgroup per (token, head)
+    const dim3 grid((unsigned)n_long, (unsigned)plan->q_heads), block(32 * kMergeSlices);
     if (out_is_bf16)
       hipLaunchKernelGGL(lse_merge_sliced_kernel<true>, grid, block, 0, st, out_partial, lse, plan->d_merge_ptr,
-                         plan->d_merge_rows, plan->d_merge_tok, out_dev, lse_out, plan->q_heads);
+                         plan->d_merge_rows, plan->d_merge_tok + n_short, out_dev, lse_out, plan->q_heads);
     else
       hipLaunchKernelGGL(lse_merge_sliced_kernel<false>, grid, block, 0, st, out_partial, lse, plan->d_merge_ptr,
-                         plan->d_merge_rows, plan->d_merge_tok, out_dev, lse_out, plan->q_heads);
-    TL_HIP(hipGetLastError());
-    return TL_OK;
+                         plan->d_merge_rows, plan->d_merge_tok + n_short, out_dev, lse_out, plan->q_heads);
   }
-  const dim3 grid((unsigned)plan->merge_tok.size(), (unsigned)((plan->q_heads * 32 + 255) / 256)), block(256);
-  if (out_is_bf16)
-    hipLaunchKernelGGL(lse_merge_kernel<true>, grid, block, 0, st, out_partial, lse, plan->d_merge_ptr, plan->d_merge_rows,
-                       plan->d_merge_tok, out_dev, lse_out, plan->q_heads);
-  else
-    hipLaunchKernelGGL(lse_merge_kernel<false>, grid, block, 0, st, out_partial, lse, plan->d_merge_ptr, plan->d_merge_rows,
-                       plan->d_merge_tok, out_dev, lse_out, plan->q_heads);
   TL_HIP(hipGetLastError());
   return TL_OK;
 }

@@ -302,6 +302,12 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
       for (int32_t t = 0; t < T; ++t)
         if (!tok_fused[t]) p->merge_ptr[t + 1]++;
     for (int32_t t = 0; t < T; ++t) p->merge_ptr[t + 1] += p->merge_ptr[t];
+    // tokens with long lists (split-K) last: tl_merge gives them the sliced kernel
+    {
+      auto is_short = [&](int32_t t) { return p->merge_ptr[t + 1] - p->merge_ptr[t] < kLongMergeList; };
+      auto mid = std::stable_partition(p->merge_tok.begin(), p->merge_tok.end(), is_short);
+      p->n_merge_short = (int32_t)(mid - p->merge_tok.begin());
+    }
     p->merge_rows.assign(p->merge_ptr[T], 0);
     {
       std::vector<int32_t> cur(p->merge_ptr.begin(), p->merge_ptr.end() - 1);

@@ -30,6 +30,7 @@ void set_error(const char* fmt, ...) __attribute__((format(printf, 1, 2)));
 
 constexpr int kHeadDim = 128;
 constexpr int kKvTile = 64;      // kv tokens per LDS tile of the row-tile kernel
+constexpr int kLongMergeList = 8;  // partials per token from which the merge deals the list to slices
 constexpr int kRowTile = 256;    // query rows (token x head-in-group) per workgroup
 constexpr int kUnitRows = 16;    // max rows per kv head of a split-K unit
 // A request is planned for the one-pass kernel from this many query rows per kv head: it then
@@ -81,7 +82,9 @@ struct tl_plan {
   std::vector<int32_t> item_row_base, item_tok_ptr, item_tokens, item_slot_ptr, item_slots;
   std::vector<int32_t> merge_ptr, merge_rows;
   std::vector<tl::Work> tiles, units, ctiles, ftiles;   // ftiles: fused rows (pool tiles + causal block in one pass)
-  std::vector<int32_t> merge_tok;  // tokens that tl_merge writes (all but the fused ones)
+  std::vector<int32_t> merge_tok;  // tokens that tl_merge writes (all but the fused ones): n_merge_short with short
+                                   // lists first, then those with kLongMergeList or more partials
+  int32_t n_merge_short = 0;
   std::vector<int32_t> single_tok; // the new token of every request that has exactly one (not fused): self block = one key
   // heavy hitters, computed on first request from the resolved lists kept here
   std::vector<int32_t> list_slots, list_ptr, list_ntok;
