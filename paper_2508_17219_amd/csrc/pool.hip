@@ -25,23 +25,6 @@ void set_error(const char* fmt, ...) {
 int get_option_vread() { return g_opt_vread; }
 int get_option_compute_units() { return g_opt_compute_units; }
 
-// 16 bytes per thread, grid-stride.  dst/src are 16-byte aligned (rows are 256 B).
-__global__ void copy16_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src, size_t n16) {
-  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-  size_t stride = (size_t)gridDim.x * blockDim.x;
-  for (; i < n16; i += stride) dst[i] = src[i];
-}
-
-__global__ void zero16_kernel(uint4* __restrict__ dst, size_t n16) {
-  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-  size_t stride = (size_t)gridDim.x * blockDim.x;
-  for (; i < n16; i += stride) dst[i] = make_uint4(0, 0, 0, 0);
-}
-
-__global__ void set_i32_kernel(int32_t* p, int32_t idx, int32_t v) {
-  if (threadIdx.x == 0 && blockIdx.x == 0) p[idx] = v;
-}
-
 // out[(i, :)] = pool[(slots[i], :)], slot_elems16 uint4 per slot; one block column per slot.
 __global__ void gather_slots_kernel(uint4* __restrict__ out, const uint4* __restrict__ pool,
                                     const int32_t* __restrict__ slots, size_t slot16) {
@@ -83,13 +66,6 @@ __global__ void append_rows_kernel(uint4* __restrict__ pool_k, uint4* __restrict
     pool_v[dst0 + n16 + i] = z;
   }
   if (blockIdx.x == 0 && threadIdx.x == 0) fill[c.slot] = c.new_fill;
-}
-
-static int blocks_for(size_t n16) {
-  size_t b = (n16 + 255) / 256;
-  if (b > 4096) b = 4096;
-  if (b < 1) b = 1;
-  return (int)b;
 }
 
 tl_status pool_device_ready(const tl_pool* pool, hipStream_t stream) {
@@ -239,18 +215,15 @@ tl_status tl_pool_put(tl_pool* pool, uint64_t segment_id, const void* k_src_dev,
   hipStream_t st = (hipStream_t)stream;
   tl_status rc = pool_device_ready(pool, st);
   if (rc != TL_OK) return rc;
+  // one launch: copy the fill rows, clear the rest of the slot, store the slot's fill
   const size_t row16 = (size_t)pool->kv_heads * pool->head_dim * 2 / 16;
   const size_t slot16 = row16 * pool->seg_len;
-  const size_t n16 = row16 * fill;
-  uint4* kd = (uint4*)pool->k_dev + (size_t)s * slot16;
-  uint4* vd = (uint4*)pool->v_dev + (size_t)s * slot16;
-  hipLaunchKernelGGL(copy16_kernel, dim3(blocks_for(n16)), dim3(256), 0, st, kd, (const uint4*)k_src_dev, n16);
-  hipLaunchKernelGGL(copy16_kernel, dim3(blocks_for(n16)), dim3(256), 0, st, vd, (const uint4*)v_src_dev, n16);
-  if (n16 < slot16) {
-    hipLaunchKernelGGL(zero16_kernel, dim3(blocks_for(slot16 - n16)), dim3(256), 0, st, kd + n16, slot16 - n16);
-    hipLaunchKernelGGL(zero16_kernel, dim3(blocks_for(slot16 - n16)), dim3(256), 0, st, vd + n16, slot16 - n16);
-  }
-  hipLaunchKernelGGL(set_i32_kernel, dim3(1), dim3(64), 0, st, pool->fill_dev, s, fill);
+  AppendArgs args;
+  memset(&args, 0, sizeof(args));
+  args.c[0] = AppendChunk{s, 0, fill, 0, pool->seg_len, fill};
+  const unsigned bx = (unsigned)(slot16 / 256 > 32 ? 32 : (slot16 + 255) / 256);
+  hipLaunchKernelGGL(append_rows_kernel, dim3(bx, 1), dim3(256), 0, st, (uint4*)pool->k_dev, (uint4*)pool->v_dev,
+                     (const uint4*)k_src_dev, (const uint4*)v_src_dev, pool->fill_dev, args, row16, slot16);
   TL_HIP(hipGetLastError());
   occupy(pool, s, segment_id, fill);
   if (slot_out) *slot_out = s;
