@@ -155,13 +155,17 @@ typedef struct tl_plan tl_plan;
 enum {
   TL_PLAN_SELF_BLOCK = 1, /* reserve partial rows for tl_causal_block and merge them   */
   TL_PLAN_NO_SHARING = 2, /* do not group requests: one item chain per request         */
-  TL_PLAN_FUSE_ROWS = 4   /* requests with at least 512 query rows per kv head (new
-                             tokens x q-heads per kv-head) leave the three-step path: one
-                             pass of tl_fused_attn over their whole slot list and their own
-                             new tokens writes their final output.  Such rows have a single
-                             partial, so nothing is written to out_partial for them and
-                             tl_segment_attn / tl_causal_block / tl_merge skip them.
-                             Needs TL_PLAN_SELF_BLOCK.                                   */
+  TL_PLAN_FUSE_ROWS = 4   /* requests that gain nothing from sharing a run of slots leave the
+                             three-step path: one pass of tl_fused_attn over their whole slot
+                             list and their own new tokens writes their final output.  These
+                             are the requests with more than 16 query rows per kv head (new
+                             tokens x q-heads per kv-head) that have no segment in common with
+                             another request of the batch, or at least 512 such rows -- except,
+                             in a batch of fewer row-tile workgroups than the GPU has CUs, those
+                             whose lists are long enough (> 2048 tokens) to be cut along the
+                             KV instead.  Such rows have a single partial, so nothing is
+                             written to out_partial for them and tl_segment_attn /
+                             tl_causal_block / tl_merge skip them.  Needs TL_PLAN_SELF_BLOCK. */
 };
 
 typedef struct tl_plan_info {

@@ -80,19 +80,42 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
     auto ntok_of = [&](int32_t r) { return req_row_ptr[r + 1] - req_row_ptr[r]; };
 
     // ---- group requests along shared runs ----------------------------------------------
-    // requests with enough rows of their own gain nothing from sharing a run with others (the
-    // work is bound by the matrix unit, not by KV traffic) and lose a partial per row: with TL_PLAN_FUSE_ROWS they are set aside for the one-pass kernel
+    // With TL_PLAN_FUSE_ROWS a request is set aside for the one-pass kernel if sharing a run of slots
+    // with other requests gains it nothing: it has no slot in common with another request of the
+    // batch, or it has enough rows of its own (the work is then bound by the matrix unit, not by KV
+    // traffic) -- either way it would only lose a partial per row, and a merge, on the other path.
+    // Requests with a token's worth of rows (decode) always take split-K units.
     const int tok_tile = kRowTile / G;
     const int64_t n_cu = get_option_compute_units();
+    const int32_t min_chunk_slots = std::max(1, 2048 / pool->seg_len);
     std::vector<char> fused(n_req, 0);
     if (flags & TL_PLAN_FUSE_ROWS) {
-      for (int32_t r = 0; r < n_req; ++r) fused[r] = (int64_t)ntok_of(r) * G >= kFuseRows;
-      // A one-pass row tile cannot be cut along its KV: with fewer row-tile workgroups than CUs in
-      // the whole batch (one long prompt, say) the three-step plan, which can (see below), is used
+      std::vector<int32_t> users(pool->n_slots, 0), last_user(pool->n_slots, -1);
+      for (int32_t r = 0; r < n_req; ++r) {
+        if (ntok_of(r) == 0) continue;
+        for (int32_t pos = 0; pos < len_of(r); ++pos) {
+          const int32_t sl = slot_at(r, pos);
+          if (last_user[sl] != r) {
+            last_user[sl] = r;
+            users[sl]++;
+          }
+        }
+      }
+      // A one-pass row tile cannot be cut along its KV: when the whole batch is fewer row-tile
+      // workgroups than the GPU has CUs (one long prompt, say), requests whose slot lists are long
+      // enough to be cut (see below) stay on the three-step path
       int64_t wgs = 0;
       for (int32_t r = 0; r < n_req; ++r)
         if (ntok_of(r) > 0) wgs += (int64_t)((ntok_of(r) + tok_tile - 1) / tok_tile) * pool->kv_heads;
-      if (wgs < n_cu) std::fill(fused.begin(), fused.end(), 0);
+      const bool small_batch = wgs < n_cu;
+      for (int32_t r = 0; r < n_req; ++r) {
+        const int64_t rows = (int64_t)ntok_of(r) * G;
+        if (rows <= kUnitRows) continue;
+        if (small_batch && len_of(r) > min_chunk_slots) continue;
+        bool shares = false;
+        for (int32_t pos = 0; pos < len_of(r) && !shares; ++pos) shares = users[slot_at(r, pos)] > 1;
+        fused[r] = rows >= kFuseRows || !shares;
+      }
     }
     std::vector<RawItem> raw;
     std::vector<int32_t> live;
@@ -170,7 +193,6 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
       }
       if (wgs > 0 && wgs < n_cu) tile_chunks = (int)std::min<int64_t>(16, (2 * n_cu + wgs - 1) / wgs);
     }
-    const int32_t min_chunk_slots = std::max(1, 2048 / pool->seg_len);
     int32_t row_cursor = 0;
     p->item_tok_ptr.push_back(0);
     p->item_slot_ptr.push_back(0);

@@ -161,19 +161,20 @@ def test_plan_covers_every_pair_exactly_once(maker, kw):
 
 
 def test_fused_rows_leave_the_three_step_path():
-    """With TL_PLAN_FUSE_ROWS a request with >= 512 query rows per kv head is handled by
-    tl_fused_attn alone: it is in no work item, has no causal tile and nothing to merge; the
+    """With TL_PLAN_FUSE_ROWS a request with >= 512 query rows per kv head (or one that shares no
+    segment with another request) is handled by tl_fused_attn alone: it is in no work item, has no causal tile and nothing to merge; the
     other requests of the batch are planned as before."""
     b = wl.prefill(seed=9, n_req=5, new_tokens=200, lo=300, hi=900, seg_len=128, n_slots=64, n_shared=2)
     # G = 4: 200 tokens = 800 rows (fused), 127 tokens = 508 rows (not), 128 tokens = 512 rows (fused), 3 tokens, 0 tokens
     b.req_row_ptr = np.concatenate([[0], np.cumsum([200, 127, 128, 3, 0])]).astype(np.int32)
     plan_pool[0] = _pool_for(b)
     flags = B.TL_PLAN_SELF_BLOCK | B.TL_PLAN_FUSE_ROWS
-    # this batch has 9 row tiles x 8 kv heads = 72 workgroups: on a 256-CU GPU the planner keeps
-    # the three-step plan (and cuts the slot lists, see the next test); told to fill 64 CUs it fuses
+    # this batch has 9 row tiles x 8 kv heads = 72 workgroups, fewer than the GPU has CUs, but its slot
+    # lists (at most 900 tokens) are too short to be cut along the KV, so the same requests are fused
+    # whatever the CU count; request 1 shares its first two segments with the others and stays unfused
     plan = B.tl_plan_create(plan_pool[0], b.q_heads, b.req_row_ptr, b.req_seg_ptr, b.seg_ids, flags)
-    info = _check_plan_covers(b, plan, flags)
-    assert info.n_fused_tiles == 0
+    info = _check_plan_covers(b, plan, flags, fused_req=(0, 2))
+    assert info.n_fused_tiles == 4 + 2
     B.tl_plan_destroy(plan)
     B.tl_set_option("compute_units", 64)
     plan = B.tl_plan_create(plan_pool[0], b.q_heads, b.req_row_ptr, b.req_seg_ptr, b.seg_ids, flags)
@@ -394,9 +395,19 @@ def test_random_batches_every_pair_once_under_every_plan_mode():
                 B.tl_set_option("compute_units", 256)
                 fused = ()
                 if flags & B.TL_PLAN_FUSE_ROWS:
+                    # the rule as the header states it: more than a token's worth of rows; no segment in
+                    # common with another request, or >= 512 rows; and, in a batch of fewer row-tile
+                    # workgroups than CUs, a list too short to be cut along the KV
                     wgs = sum(-(-n // tok_tile) * hkv for n in ntok if n > 0)
-                    if wgs >= cus:
-                        fused = tuple(r for r in range(n_req) if ntok[r] * g >= 512)
+                    users = {}
+                    for r in range(n_req):
+                        if ntok[r] > 0:
+                            for i in set(lists[r]):
+                                users[i] = users.get(i, 0) + 1
+                    fused = tuple(r for r in range(n_req)
+                                  if ntok[r] * g > 16
+                                  and not (wgs < cus and len(lists[r]) > max(1, 2048 // seg_len))
+                                  and (ntok[r] * g >= 512 or not any(users[i] > 1 for i in lists[r])))
                 _check_plan_covers(b, plan, flags, fused_req=fused)
                 B.tl_plan_destroy(plan)
         B.tl_pool_destroy(plan_pool[0])
