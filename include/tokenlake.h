@@ -20,6 +20,11 @@
  *    kernels, except that the first of them after a put / append / adopt uploads the pool's
  *    fill table with one asynchronous copy: run one step eagerly before capturing a step
  *    into a HIP graph.
+ *  - A pool, and the plans made from it, belong to one host thread at a time: calls on the
+ *    same pool or plan from several threads need the caller's own lock (the id table, the
+ *    use stamps and the lazily made device copies are plain host state).  Different pools
+ *    are independent.  Compute calls on one stream run in order; the same plan may be used
+ *    on several streams once its first call has returned.
  *  - All tensors are dense, row-major, bf16 = 16-bit brain float bit patterns.
  *  - head_dim must be 128; q_heads must be a multiple of kv_heads, at most 32 times it; seg_len must
  *    be a multiple of 64.  Anything else is TL_EINVAL.
