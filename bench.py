@@ -251,7 +251,7 @@ def algorithmic_work(batch, info):
     part_bytes = part_rows * hq * (d + 1) * 4.0
     # one-pass rows: K/V of the new tokens are read, the final bf16 output and fp32 LSE are written
     fused_io_bytes = info["n_fused_tokens"] * (4.0 * hkv * d + hq * (2.0 * d + 4.0))
-    return {"flops_prefix": flops_prefix, "flops_self": flops_self, "kv_bytes": kv_bytes, "q_bytes": q_bytes,
+    return {"flops_prefix": flops_prefix, "flops_self": flops_self, "flops_tiles": 4.0 * hq * d * info.get("tile_pairs", 0), "kv_bytes": kv_bytes, "q_bytes": q_bytes,
             "partial_bytes": part_bytes, "fused_io_bytes": fused_io_bytes}
 
 
@@ -387,12 +387,16 @@ def main():
                     "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS,
                     "traffic": measured_traffic("row_tile_attn_kernel<one pass>", b.name),
                     "algorithmic_flops": fl, "algorithmic_bytes": w["kv_bytes"] + w["q_bytes"] + w["fused_io_bytes"],
+                    # what the matrix unit was given: a slot that a list names m times is walked once, weighted m
+                    "executed_flops": w["flops_tiles"] + w["flops_self"],
+                    "executed_tflops": (w["flops_tiles"] + w["flops_self"]) / (r["fused_attn_ms"] * 1e-3) / 1e12,
                     "avg_kernel_ms": r["fused_attn_ms"]}
         ach = w["flops_prefix"] / seg_s / 1e12
         return {"kernel": "row_tile_attn_kernel", "bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS,
                 "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS,
                 "traffic": measured_traffic("row_tile_attn_kernel", b.name),
-                "algorithmic_flops": w["flops_prefix"], "avg_kernel_ms": r["segment_attn_ms"]}
+                "algorithmic_flops": w["flops_prefix"], "executed_flops": w["flops_tiles"],
+                "executed_tflops": w["flops_tiles"] / seg_s / 1e12, "avg_kernel_ms": r["segment_attn_ms"]}
 
     line = {
         "metric": "merged tok/s (one layer: attention over the segment pool + causal self block, partials merged)",

@@ -190,6 +190,9 @@ typedef struct tl_plan_info {
   int32_t n_fused_tokens;  /* new tokens whose output tl_fused_attn writes               */
   int32_t n_single_tokens; /* requests with one new token (decode): their self block is one key,
                               written by a light kernel of tl_causal_block                */
+  int64_t tile_pairs;      /* (query token, kv token) pairs the row-tile kernels compute: as
+                              prefix_pairs over row-tile work, each distinct slot of a work
+                              item's list counted once (see "dedupe_tiles")                */
 } tl_plan_info;
 
 /* req_row_ptr: host [n_req+1], offsets of each request's new tokens in the batch's Q
@@ -273,7 +276,10 @@ tl_status tl_merge(tl_plan* plan, const float* out_partial, const float* lse, vo
  *   "compute_units"  the number of CUs the plan builder fills (default 256, MI355X; 0..4096):
  *                    a batch with fewer row-tile workgroups than this gets KV-chunked work
  *                    items instead of one-pass rows.  0 turns that off (tests of the one-pass
- *                    kernel on small shapes use it). */
+ *                    kernel on small shapes use it);
+ *   "dedupe_tiles"   1 (default) = a row-tile work item walks a slot that its list names m
+ *                    times once, with weight m (exact: m equal keys contribute m exp(s) to the
+ *                    numerator and the denominator alike); 0 = once per occurrence. */
 tl_status tl_set_option(const char* knob, int32_t value);
 
 /* ------------------------------------------------------------------------------------

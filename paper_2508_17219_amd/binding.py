@@ -31,7 +31,7 @@ class tl_plan_info(C.Structure):
         "n_req", "n_tokens", "q_heads", "kv_heads", "n_items", "n_partial_rows", "self_row_base",
         "n_tiles", "n_units", "n_causal_tiles", "n_list_entries", "n_merge_entries")] + [
         (n, C.c_int64) for n in ("prefix_pairs", "self_pairs", "unique_kv_tokens")] + [
-        (n, C.c_int32) for n in ("n_fused_tiles", "n_fused_tokens", "n_single_tokens")]
+        (n, C.c_int32) for n in ("n_fused_tiles", "n_fused_tokens", "n_single_tokens")] + [("tile_pairs", C.c_int64)]
 
 
 _lib = None

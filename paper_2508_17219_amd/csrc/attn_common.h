@@ -37,6 +37,8 @@ struct AttnArgs {
   const int32_t* slots;   // slot lists (pool work)
   const int32_t* tile_base;  // first kv row of each full 64-token tile (pool row tiles)
   const int32_t* part_tile;  // (first kv row, valid tokens) of each cut-short tile
+  const float* tile_lm;      // log2(times the tile's slot is listed), parallel to tile_base
+  const float* part_lm;      // the same for the cut-short tiles
   float* out;             // [rows, q_heads, 128]
   float* lse;             // [rows, q_heads]
   int32_t q_heads, kv_heads, group, seg_len, n_work;   // group = q_heads / kv_heads

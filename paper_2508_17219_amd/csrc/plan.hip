@@ -164,6 +164,40 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
       }
     }
 
+    // The kv tokens of a slot list as tiles of kKvTile rows.  A slot listed several times (lists are
+    // multisets: Section 3.1 has no order or uniqueness among the segments a request attends to) is
+    // walked once; its tiles carry log2 of the multiplicity, which the kernel adds to the exponent
+    // (m equal keys weigh m exp(s) in numerator and denominator alike).  Returns the pairs computed.
+    const bool dedupe = get_option_dedupe_tiles() != 0;
+    std::vector<int32_t> mult_of(dedupe ? pool->n_slots : 0, 0);
+    auto emit_tiles = [&](auto slot_of_pos, int32_t n_pos) -> int64_t {
+      int64_t kv_tokens = 0;
+      if (dedupe)
+        for (int32_t pos = 0; pos < n_pos; ++pos) mult_of[slot_of_pos(pos)]++;
+      for (int32_t pos = 0; pos < n_pos; ++pos) {
+        const int32_t sl = slot_of_pos(pos), f = pool->fill[sl];
+        int32_t m = 1;
+        if (dedupe) {
+          m = mult_of[sl];
+          if (m == 0) continue;        // a later occurrence of a slot already emitted
+          mult_of[sl] = 0;
+        }
+        const float lm = log2f((float)m);
+        kv_tokens += f;
+        for (int32_t off = 0; off < f; off += kKvTile) {
+          if (off + kKvTile <= f) {
+            p->tile_base.push_back(sl * pool->seg_len + off);
+            p->tile_lm.push_back(lm);
+          } else {
+            p->part_tile.push_back(sl * pool->seg_len + off);
+            p->part_tile.push_back(f - off);
+            p->part_lm.push_back(lm);
+          }
+        }
+      }
+      return kv_tokens;
+    };
+
     // ---- final items, work lists ----------------------------------------------------------
     int split = split_segments;
     if (split == 0) {
@@ -196,7 +230,7 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
     int32_t row_cursor = 0;
     p->item_tok_ptr.push_back(0);
     p->item_slot_ptr.push_back(0);
-    int64_t prefix_pairs = 0;
+    int64_t prefix_pairs = 0, tile_pairs = 0;
     int32_t n_fused_tokens = 0;
     for (const RawItem& it : raw) {
       int32_t n_tok = 0;
@@ -226,17 +260,7 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
           // the item's kv tokens as tiles of kKvTile rows (shared by all its row tiles)
           const int32_t full_off = (int32_t)p->tile_base.size();
           const int32_t part_off = (int32_t)p->part_tile.size() / 2;
-          for (int32_t pos = slot_base; pos < slot_base + (c1 - c0); ++pos) {
-            const int32_t s = p->item_slots[pos], f = pool->fill[s];
-            for (int32_t off = 0; off < f; off += kKvTile) {
-              if (off + kKvTile <= f) {
-                p->tile_base.push_back(s * pool->seg_len + off);
-              } else {
-                p->part_tile.push_back(s * pool->seg_len + off);
-                p->part_tile.push_back(f - off);
-              }
-            }
-          }
+          tile_pairs += (int64_t)n_tok * emit_tiles([&](int32_t pos) { return p->item_slots[slot_base + pos]; }, c1 - c0);
           const int32_t n_full = (int32_t)p->tile_base.size() - full_off;
           const int32_t n_part = (int32_t)p->part_tile.size() / 2 - part_off;
           // row tiles never straddle two requests' token ranges unless ranges are short:
@@ -267,18 +291,8 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
           // the request's whole slot list as tiles of kKvTile rows
           full_off = (int32_t)p->tile_base.size();
           part_off = (int32_t)p->part_tile.size() / 2;
-          for (int32_t pos = 0; pos < len_of(r); ++pos) {
-            const int32_t s = slot_at(r, pos), f = pool->fill[s];
-            prefix_pairs += lq * f;
-            for (int32_t off = 0; off < f; off += kKvTile) {
-              if (off + kKvTile <= f) {
-                p->tile_base.push_back(s * pool->seg_len + off);
-              } else {
-                p->part_tile.push_back(s * pool->seg_len + off);
-                p->part_tile.push_back(f - off);
-              }
-            }
-          }
+          for (int32_t pos = 0; pos < len_of(r); ++pos) prefix_pairs += lq * pool->fill[slot_at(r, pos)];
+          tile_pairs += lq * emit_tiles([&](int32_t pos) { return slot_at(r, pos); }, len_of(r));
           n_full = (int32_t)p->tile_base.size() - full_off;
           n_part = (int32_t)p->part_tile.size() / 2 - part_off;
           n_fused_tokens += (int32_t)lq;
@@ -378,6 +392,7 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
     inf.n_fused_tiles = (int32_t)p->ftiles.size();
     inf.n_fused_tokens = n_fused_tokens;
     inf.n_single_tokens = (int32_t)p->single_tok.size();
+    inf.tile_pairs = tile_pairs;
   } catch (const std::bad_alloc&) {
     rc = TL_ENOMEM;
     set_error("tl_plan_create: host allocation failed");
@@ -480,7 +495,9 @@ tl_status plan_device_ready(tl_plan* p) {
   const size_t b_ftiles = al(sizeof(Work) * p->ftiles.size());
   const size_t b_mtok = al(sizeof(int32_t) * p->merge_tok.size());
   const size_t b_stok = al(sizeof(int32_t) * p->single_tok.size());
-  const size_t total = b_tiles + b_units + b_ctiles + b_tok + b_slots + b_mptr + b_mrows + b_tbase + b_part + b_ftiles + b_mtok + b_stok + 256;
+  const size_t b_tlm = al(sizeof(float) * p->tile_lm.size());
+  const size_t b_plm = al(sizeof(float) * p->part_lm.size());
+  const size_t total = b_tiles + b_units + b_ctiles + b_tok + b_slots + b_mptr + b_mrows + b_tbase + b_part + b_ftiles + b_mtok + b_stok + b_tlm + b_plm + 256;
   std::vector<char> host(total, 0);
   size_t off = 0;
   auto put = [&](const void* src, size_t bytes, size_t reserved) {
@@ -501,6 +518,8 @@ tl_status plan_device_ready(tl_plan* p) {
   const size_t o_ftiles = put(p->ftiles.data(), sizeof(Work) * p->ftiles.size(), b_ftiles);
   const size_t o_mtok = put(p->merge_tok.data(), sizeof(int32_t) * p->merge_tok.size(), b_mtok);
   const size_t o_stok = put(p->single_tok.data(), sizeof(int32_t) * p->single_tok.size(), b_stok);
+  const size_t o_tlm = put(p->tile_lm.data(), sizeof(float) * p->tile_lm.size(), b_tlm);
+  const size_t o_plm = put(p->part_lm.data(), sizeof(float) * p->part_lm.size(), b_plm);
   void* blob = nullptr;
   TL_HIP(hipMalloc(&blob, total));
   hipError_t e = hipMemcpy(blob, host.data(), total, hipMemcpyHostToDevice);
@@ -522,6 +541,8 @@ tl_status plan_device_ready(tl_plan* p) {
   p->d_ftiles = (Work*)(b + o_ftiles);
   p->d_merge_tok = (int32_t*)(b + o_mtok);
   p->d_single_tok = (int32_t*)(b + o_stok);
+  p->d_tile_lm = (float*)(b + o_tlm);
+  p->d_part_lm = (float*)(b + o_plm);
   p->on_device = true;
   return TL_OK;
 }

@@ -14,6 +14,7 @@ namespace tl {
 static thread_local char g_err[512] = "";
 static int g_opt_vread = 0;
 static int g_opt_compute_units = kComputeUnits;
+static int g_opt_dedupe_tiles = 1;
 
 void set_error(const char* fmt, ...) {
   va_list ap;
@@ -24,6 +25,7 @@ void set_error(const char* fmt, ...) {
 
 int get_option_vread() { return g_opt_vread; }
 int get_option_compute_units() { return g_opt_compute_units; }
+int get_option_dedupe_tiles() { return g_opt_dedupe_tiles; }
 
 // out[(i, :)] = pool[(slots[i], :)], slot_elems16 uint4 per slot; one block column per slot.
 __global__ void gather_slots_kernel(uint4* __restrict__ out, const uint4* __restrict__ pool,
@@ -113,6 +115,11 @@ tl_status tl_set_option(const char* knob, int32_t value) {
   if (!strcmp(knob, "compute_units")) {
     if (value < 0 || value > 4096) TL_FAIL(TL_EINVAL, "tl_set_option: compute_units must be 0..4096");
     g_opt_compute_units = value;
+    return TL_OK;
+  }
+  if (!strcmp(knob, "dedupe_tiles")) {
+    if (value < 0 || value > 1) TL_FAIL(TL_EINVAL, "tl_set_option: dedupe_tiles must be 0 or 1");
+    g_opt_dedupe_tiles = value;
     return TL_OK;
   }
   TL_FAIL(TL_EINVAL, "tl_set_option: unknown knob '%s'", knob);

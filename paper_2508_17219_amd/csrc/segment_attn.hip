@@ -52,7 +52,7 @@ constexpr int kKTile = kKvTile * kKS;
 constexpr int kVTile = kKvTile * kVS;
 constexpr int kIdxRing = 512;        // tile-base entries kept in LDS (ring over the work item's tile list)
 constexpr int kBufs = 3;             // LDS tile buffers: K(t+2) and V(t+1) stream in while tile t is computed
-constexpr size_t kLdsBytes = (size_t)kBufs * (kKTile + kVTile) * sizeof(uint16_t) + (kIdxRing + 4) * sizeof(int32_t);
+constexpr size_t kLdsBytes = (size_t)kBufs * (kKTile + kVTile) * sizeof(uint16_t) + (2 * kIdxRing + 4) * sizeof(int32_t);
 constexpr float kRescaleLog2 = 8.0f;             // careful path: raise the maximum when exceeded by 2^8
 constexpr float kFastPathLimit = 1.152921504606846976e18f;  // 2^60
 constexpr int kDmaPerWave = 16 / kWaves;                  // direct-load instructions per wave per K (or V) tile
@@ -112,7 +112,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
   uint16_t* lds_k = lds;                 // [kBufs][64][kKS]
   uint16_t* lds_v = lds + kBufs * kKTile;    // [kBufs][64][kVS]
   int32_t* lds_idx = (int32_t*)(lds + kBufs * (kKTile + kVTile));   // [kIdxRing]
-  int32_t* lds_flag = lds_idx + kIdxRing;
+  float* lds_lm = (float*)(lds_idx + kIdxRing);   // [kIdxRing] log2(multiplicity) of the same tiles
+  int32_t* lds_flag = lds_idx + 2 * kIdxRing;
 
   const int g = blockIdx.x % a.kv_heads;
   const Work wk = a.work[blockIdx.x / a.kv_heads];
@@ -181,7 +182,10 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
   // is arithmetic
   auto ring_fill = [&](int first, int count) __attribute__((always_inline)) {   // entries [first, first+count) of the list, clipped
     for (int i = first + tid; i < first + count && i < nf_pool; i += kThreads)
+    {
       lds_idx[i & (kIdxRing - 1)] = a.tile_base[wk.full_off + i];
+      lds_lm[i & (kIdxRing - 1)] = a.tile_lm[wk.full_off + i];
+    }
   };
 
   // ---- careful path staging (global -> registers -> LDS): kChunks chunks of 16 B per thread per
@@ -273,8 +277,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
   };
   // probabilities of a block against the reference: p = 2^(c (s - m_ref)); B operands pb[sp]
   // hold registers 8 sp .. 8 sp + 7
-  auto exp_block = [&](int rg, f32x16& s, bf16x8 (&pb)[2]) {
-    const float mc = m_ref[rg] * c;
+  auto exp_block = [&](int rg, f32x16& s, bf16x8 (&pb)[2], float lm) {
+    const float mc = m_ref[rg] * c - lm;   // lm = log2(times the tile's slot is listed): p = m 2^(c (s - m_ref))
 #pragma unroll
     for (int r = 0; r < 16; ++r) s[r] = fast_exp2(fmaf(s[r], c, -mc));
     pb[0] = pack_bf16x8(s[0], s[1], s[2], s[3], s[4], s[5], s[6], s[7]);
@@ -312,7 +316,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
     }
   };
   // careful path: one tile (rows beyond `valid` hidden; causal work also hides later tokens)
-  auto careful_tile = [&](auto SELF, const uint16_t* src_k, const uint16_t* src_v, int base, int valid) __attribute__((always_inline)) {
+  auto careful_tile = [&](auto SELF, const uint16_t* src_k, const uint16_t* src_v, int base, int valid, float lm) __attribute__((always_inline)) {
     constexpr bool CAUSAL = decltype(SELF)::value;
     {
       // rows beyond `valid` are written as zero: 0 * garbage cannot make NaN
@@ -348,7 +352,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
           pb[rg][0] = pack_bf16x8(0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f);
           pb[rg][1] = pb[rg][0];
         } else {
-          exp_block(rg, s[rg], pb[rg]);
+          exp_block(rg, s[rg], pb[rg], lm);
         }
       }
       pv_block(lds_v, hb, pb);
@@ -417,6 +421,9 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
     // first rows of the tiles that the coming iteration streams in, K(t+2) and V(t+1) (indices past
     // the end are clamped: such a value is never used for a load)
     int base_k = full_base(min(2, n_full - 1)), base_v = full_base(min(1, n_full - 1));
+    // log2 of the multiplicity of the tile whose probabilities the coming iteration forms
+    auto tile_lm = [&](int t) __attribute__((always_inline)) -> float { return CAUSAL ? 0.f : lds_lm[t & (kIdxRing - 1)]; };
+    float lm_cur = tile_lm(0);
     // one tile; kb = t % kBufs is a compile-time constant (the loop below is unrolled kBufs times),
     // so that every LDS address is a loop-invariant per-lane register plus an immediate offset
     auto tile_iteration = [&](auto KB, int t) __attribute__((always_inline)) {
@@ -434,13 +441,22 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
       if (t + 2 < n_full) dma_tile(src_k, base_k, lds_k + km1 * kKTile, dma_off_k);
       if (t + 1 < n_full) dma_tile(src_v, base_v, lds_v + km2 * kVTile, dma_off_v);
       int base_k_next = 0, base_k_next_v = 0;
+      float lm_next = 0.f;
+      float nmc[kRG];               // exponent offset of this tile's probabilities: p = m 2^(c (s - m_ref))
+#pragma unroll
+      for (int rg = 0; rg < kRG; ++rg) nmc[rg] = lm_cur - mc[rg];
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int gq = 0; gq < 32; ++gq) {
         const int step = gq >> 4, gi = gq & 15, idx = gi >> 1;
         // read early and made wave-uniform well before the next iteration's start needs it
-        if (gq == 6) base_k_next_v = full_base(min(t + 3, n_full - 1));
-        if (gq == 20) base_k_next = __builtin_amdgcn_readfirstlane(base_k_next_v);
+        if (gq == 6) {
+          base_k_next_v = full_base(min(t + 3, n_full - 1));
+          lm_next = tile_lm(min(t + 1, n_full - 1));
+        }
+        if (gq == 20) {
+          base_k_next = __builtin_amdgcn_readfirstlane(base_k_next_v);
+        }
         // fetch ahead (the first groups of the next iteration read tiles that are already resident)
         {
           const int gp = gq + kDepth;
@@ -463,7 +479,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
           __builtin_amdgcn_sched_barrier(0);   // the MFMA first, then its slice (+0.8 % over leaving the order to the compiler)
           const int e = gi * kRG + j, rg = e >> 4, r = e & 15;
           f32x16& s = step == 0 ? s0[rg] : s1[rg];
-          s[r] = fast_exp2(fmaf(s[r], c, -mc[rg]));
+          s[r] = fast_exp2(fmaf(s[r], c, nmc[rg]));
           // The row sum and the packing to bf16 trail the exponentials by one element / one pair, so
           // that every slice carries the same few vector instructions (a burst of eight adds and
           // four converts in one place would hold up the MFMA behind it) and none of them waits
@@ -486,6 +502,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
       __builtin_amdgcn_sched_barrier(0);
       base_v = base_k;
       base_k = base_k_next;
+      lm_cur = lm_next;
     };
     {
       int t = 0;
@@ -532,16 +549,17 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
         ring_fill(t + kIdxRing / 2, kIdxRing / 2);
         __syncthreads();
       }
-      careful_tile(kPoolPhase, a.k, a.v, lds_idx[t & (kIdxRing - 1)], kKvTile);
+      careful_tile(kPoolPhase, a.k, a.v, lds_idx[t & (kIdxRing - 1)], kKvTile, lds_lm[t & (kIdxRing - 1)]);
     }
   };
   auto careful_pool_part = [&]() __attribute__((always_inline)) {   // tiles cut short by a slot's fill
     for (int pt = 0; pt < np_pool; ++pt)
-      careful_tile(kPoolPhase, a.k, a.v, a.part_tile[2 * (wk.part_off + pt)], a.part_tile[2 * (wk.part_off + pt) + 1]);
+      careful_tile(kPoolPhase, a.k, a.v, a.part_tile[2 * (wk.part_off + pt)], a.part_tile[2 * (wk.part_off + pt) + 1],
+                   a.part_lm[wk.part_off + pt]);
   };
   auto careful_self = [&](int first_tile, int n_tiles) __attribute__((always_inline)) {
     for (int t = first_tile; t < first_tile + n_tiles; ++t)
-      careful_tile(kSelfPhase, self_k, self_v, wk.kv_off + kKvTile * t, min(kKvTile, wk.kv_len - kKvTile * t));
+      careful_tile(kSelfPhase, self_k, self_v, wk.kv_off + kKvTile * t, min(kKvTile, wk.kv_len - kKvTile * t), 0.f);
   };
 
   // ======================= the phases =======================

@@ -54,6 +54,7 @@ struct Work {
 
 int get_option_vread();
 int get_option_compute_units();
+int get_option_dedupe_tiles();
 
 }  // namespace tl
 
@@ -94,11 +95,13 @@ struct tl_plan {
   std::vector<int32_t> tok;      // token index array referenced by Work::tok_off
   std::vector<int32_t> tile_base;  // Work::full_off
   std::vector<int32_t> part_tile;  // Work::part_off, pairs (first kv row, valid tokens)
+  std::vector<float> tile_lm, part_lm;  // log2 of how often the tile's slot is listed (parallel to tile_base / part_tile pairs)
   // device copies (made on first use)
   bool on_device;
   void* blob;
   tl::Work *d_tiles, *d_units, *d_ctiles, *d_ftiles;
   int32_t *d_tok, *d_slots, *d_merge_ptr, *d_merge_rows, *d_tile_base, *d_part_tile, *d_merge_tok, *d_single_tok;
+  float *d_tile_lm, *d_part_lm;
 };
 
 namespace tl {

@@ -248,6 +248,33 @@ def test_single_new_tokens_get_no_causal_row_tile():
     B.tl_pool_destroy(pool)
 
 
+def test_tile_pairs_count_each_distinct_slot_of_a_work_item_once():
+    """One work item per request (no sharing), and one-pass rows (150 tokens x 4 heads >= 512 rows):
+    either way a request's whole list is one walk, so every distinct segment counts once."""
+    for flags, ntok in ((B.TL_PLAN_SELF_BLOCK | B.TL_PLAN_NO_SHARING, 50), (B.TL_PLAN_SELF_BLOCK | B.TL_PLAN_FUSE_ROWS, 150)):
+        b = wl.longctx(n_req=3, entries=40, new_tokens=ntok, seg_len=64, n_ids=10, n_slots=16)
+        pool = _pool_for(b)
+        fill_of = dict(zip(b.pool_ids.tolist(), b.pool_fills.tolist()))
+        per_entry = sum(ntok * fill_of[int(i)] for i in b.seg_ids)
+        distinct = sum(ntok * sum(fill_of[int(i)] for i in set(b.seg_ids[b.req_seg_ptr[r]:b.req_seg_ptr[r + 1]].tolist()))
+                       for r in range(3))
+        assert distinct < per_entry
+        for dedupe in (1, 0):
+            B.tl_set_option("dedupe_tiles", dedupe)
+            B.tl_set_option("compute_units", 0)
+            plan = B.tl_plan_create(pool, b.q_heads, b.req_row_ptr, b.req_seg_ptr, b.seg_ids, flags)
+            B.tl_set_option("compute_units", 256)
+            B.tl_set_option("dedupe_tiles", 1)
+            info = B.tl_plan_get_info(plan)
+            assert info.prefix_pairs == per_entry
+            assert info.tile_pairs == (distinct if dedupe else per_entry)
+            assert (info.n_fused_tokens == 3 * ntok) == bool(flags & B.TL_PLAN_FUSE_ROWS)
+            B.tl_plan_destroy(plan)
+        B.tl_pool_destroy(pool)
+    with pytest.raises(B.TokenLakeError):
+        B.tl_set_option("dedupe_tiles", 2)
+
+
 def test_plan_errors():
     b = wl.tiny()
     pool = _pool_for(b)

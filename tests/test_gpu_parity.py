@@ -349,6 +349,36 @@ def test_full_longctx_config_sampled():
     run.close()
 
 
+def test_repeated_segments_walked_once_with_their_multiplicity():
+    """Lists that name a segment several times (Zipf draws with replacement): by default a row-tile
+    work item walks each distinct slot once and weighs its keys by the multiplicity.  Every row
+    against the oracle, which concatenates the list as it stands; with the option off the kernel does
+    the same as the oracle, and the two settings agree; three-step and one-pass plans; ragged fills
+    (the repeated slots' cut-short tiles carry the weight too)."""
+    _say("repeated segments")
+    b = wl.longctx(seed=77, n_req=3, entries=60, new_tokens=150, seg_len=128, n_ids=12, n_slots=16)
+    fills = b.pool_fills.copy()
+    fills[::3] = 77                      # a third of the segments end inside their second tile
+    b.pool_fills = fills
+    counts = [np.unique(b.seg_ids[b.req_seg_ptr[r]:b.req_seg_ptr[r + 1]], return_counts=True)[1] for r in range(b.n_req)]
+    assert max(int(c.max()) for c in counts) >= 8
+    for fuse in (False, True):
+        runs = {}
+        for dedupe in (1, 0):
+            B.tl_set_option("dedupe_tiles", dedupe)
+            try:
+                runs[dedupe] = H.run_gpu(b, fuse=fuse)
+            finally:
+                B.tl_set_option("dedupe_tiles", 1)
+            _check_all_requests(runs[dedupe])
+        i1, i0 = runs[1].info, runs[0].info
+        # one-pass rows walk a request's whole list at once (12 distinct segments of 60 entries); shared runs are
+        # walked run by run, and a segment can come back in a later run
+        assert i0.tile_pairs == i0.prefix_pairs == i1.prefix_pairs and (3 if fuse else 1) * i1.tile_pairs < i1.prefix_pairs
+        assert (runs[1].out - runs[0].out).abs().max().item() <= 8e-3 and (runs[1].lse - runs[0].lse).abs().max().item() <= 1e-4
+        runs[0].close(); runs[1].close()
+
+
 @pytest.mark.parametrize("turn", [0, 7])
 def test_full_multiturn_config_sampled(turn):
     _say("full multi-turn (cfg 5) turn %d" % turn)
