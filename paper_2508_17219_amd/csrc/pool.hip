@@ -316,8 +316,14 @@ tl_status tl_pool_append_batch(tl_pool* pool, int32_t n_chains, const int32_t* h
     const size_t nc = chunks.size() - c0 < (size_t)kAppendChunks ? chunks.size() - c0 : (size_t)kAppendChunks;
     AppendArgs args;
     memset(&args, 0, sizeof(args));
-    for (size_t i = 0; i < nc; ++i) args.c[i] = chunks[c0 + i];
-    const unsigned bx = (unsigned)(slot16 / 256 > 32 ? 32 : (slot16 + 255) / 256);
+    size_t most16 = 1;     // the largest chunk of the launch (copied plus cleared 16-byte pieces) sizes the block columns
+    for (size_t i = 0; i < nc; ++i) {
+      const AppendChunk& ch = chunks[c0 + i];
+      args.c[i] = ch;
+      const size_t rows = (size_t)(ch.zero_to > ch.tok + ch.n ? ch.zero_to - ch.tok : ch.n);
+      if (rows * row16 > most16) most16 = rows * row16;
+    }
+    const unsigned bx = (unsigned)(most16 / 256 > 32 ? 32 : (most16 + 255) / 256);
     hipLaunchKernelGGL(append_rows_kernel, dim3(bx, (unsigned)nc), dim3(256), 0, st, (uint4*)pool->k_dev, (uint4*)pool->v_dev,
                        (const uint4*)k_rows_dev, (const uint4*)v_rows_dev, pool->fill_dev, args, row16, slot16);
   }
