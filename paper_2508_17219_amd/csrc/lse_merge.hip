@@ -148,8 +148,8 @@ void fill_args(AttnArgs& a, const tl_plan* plan, const void* q, float scale, flo
   a.slots = plan->d_slots;
   a.tile_base = plan->d_tile_base;
   a.part_tile = plan->d_part_tile;
-  a.tile_lm = plan->d_tile_lm;
-  a.part_lm = plan->d_part_lm;
+  a.tile_lm = plan->any_repeat ? plan->d_tile_lm : nullptr;   // null: every tile has multiplicity 1
+  a.part_lm = plan->any_repeat ? plan->d_part_lm : nullptr;
   a.out = out;
   a.lse = lse;
   a.q_heads = plan->q_heads;

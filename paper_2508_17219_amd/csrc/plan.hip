@@ -183,6 +183,7 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
           mult_of[sl] = 0;
         }
         const float lm = log2f((float)m);
+        if (m > 1) p->any_repeat = true;
         kv_tokens += f;
         for (int32_t off = 0; off < f; off += kKvTile) {
           if (off + kKvTile <= f) {

@@ -184,7 +184,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
     for (int i = first + tid; i < first + count && i < nf_pool; i += kThreads)
     {
       lds_idx[i & (kIdxRing - 1)] = a.tile_base[wk.full_off + i];
-      lds_lm[i & (kIdxRing - 1)] = a.tile_lm[wk.full_off + i];
+      if (a.tile_lm) lds_lm[i & (kIdxRing - 1)] = a.tile_lm[wk.full_off + i];
     }
   };
 
@@ -422,7 +422,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
     // the end are clamped: such a value is never used for a load)
     int base_k = full_base(min(2, n_full - 1)), base_v = full_base(min(1, n_full - 1));
     // log2 of the multiplicity of the tile whose probabilities the coming iteration forms
-    auto tile_lm = [&](int t) __attribute__((always_inline)) -> float { return CAUSAL ? 0.f : lds_lm[t & (kIdxRing - 1)]; };
+    // (a.tile_lm is null when no list of the plan names a slot twice: then nothing is read)
+    auto tile_lm = [&](int t) __attribute__((always_inline)) -> float { return CAUSAL || !a.tile_lm ? 0.f : lds_lm[t & (kIdxRing - 1)]; };
     float lm_cur = tile_lm(0);
     // one tile; kb = t % kBufs is a compile-time constant (the loop below is unrolled kBufs times),
     // so that every LDS address is a loop-invariant per-lane register plus an immediate offset
@@ -549,13 +550,13 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
         ring_fill(t + kIdxRing / 2, kIdxRing / 2);
         __syncthreads();
       }
-      careful_tile(kPoolPhase, a.k, a.v, lds_idx[t & (kIdxRing - 1)], kKvTile, lds_lm[t & (kIdxRing - 1)]);
+      careful_tile(kPoolPhase, a.k, a.v, lds_idx[t & (kIdxRing - 1)], kKvTile, a.tile_lm ? lds_lm[t & (kIdxRing - 1)] : 0.f);
     }
   };
   auto careful_pool_part = [&]() __attribute__((always_inline)) {   // tiles cut short by a slot's fill
     for (int pt = 0; pt < np_pool; ++pt)
       careful_tile(kPoolPhase, a.k, a.v, a.part_tile[2 * (wk.part_off + pt)], a.part_tile[2 * (wk.part_off + pt) + 1],
-                   a.part_lm[wk.part_off + pt]);
+                   a.part_lm ? a.part_lm[wk.part_off + pt] : 0.f);
   };
   auto careful_self = [&](int first_tile, int n_tiles) __attribute__((always_inline)) {
     for (int t = first_tile; t < first_tile + n_tiles; ++t)

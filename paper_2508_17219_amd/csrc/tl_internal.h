@@ -95,6 +95,7 @@ struct tl_plan {
   std::vector<int32_t> tok;      // token index array referenced by Work::tok_off
   std::vector<int32_t> tile_base;  // Work::full_off
   std::vector<int32_t> part_tile;  // Work::part_off, pairs (first kv row, valid tokens)
+  bool any_repeat = false;              // some work item's list names a slot more than once
   std::vector<float> tile_lm, part_lm;  // log2 of how often the tile's slot is listed (parallel to tile_base / part_tile pairs)
   // device copies (made on first use)
   bool on_device;
