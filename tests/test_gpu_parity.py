@@ -264,6 +264,47 @@ def test_merge_of_long_partial_lists():
             run.close()
 
 
+def test_merge_kernels_on_synthetic_partials():
+    """tl_merge alone, on partials that attention would rarely produce: LSEs spread over +-80,
+    partials with LSE = -inf (weight 0) mixed in, tokens whose partials are all -inf.  The plan
+    gives short lists (plain kernel) and long ones (sliced kernel) in the same call; every
+    (token, head) against the oracle's merge, fp32 and bf16 outputs."""
+    _say("merge on synthetic partials")
+    d = wl.decode(seed=72, n_req=6, median=1500, sigma=0.8, cap=6000, seg_len=64, hq=8, hkv=2)
+    pk, pv = H.device_pool(d, poison=False)
+    pool = B.tl_pool_create(d.n_slots, d.seg_len, d.kv_heads, d.head_dim, pk, pv)
+    B.tl_pool_adopt(pool, d.pool_ids, d.pool_slots, d.pool_fills)
+    plan = B.tl_plan_create(pool, d.q_heads, d.req_row_ptr, d.req_seg_ptr, d.seg_ids, B.TL_PLAN_SELF_BLOCK, 2)
+    info, ex = B.tl_plan_get_info(plan), B.tl_plan_export(plan)
+    counts = np.diff(ex["merge_ptr"])
+    assert counts.min() < 8 <= counts.max()                       # both kernels have work
+    rng = np.random.default_rng(5)
+    R, Hq, D = info.n_partial_rows, d.q_heads, d.head_dim
+    outp = rng.standard_normal((R, Hq, D)).astype(np.float32)
+    lsep = (rng.standard_normal((R, Hq)) * 30).astype(np.float32)
+    lsep[rng.random((R, Hq)) < 0.2] = -np.inf
+    dead_tok = int(np.argmax(counts))                             # every partial of the longest list: no keys
+    lsep[ex["merge_rows"][ex["merge_ptr"][dead_tok]:ex["merge_ptr"][dead_tok + 1]], 0] = -np.inf
+    g_outp, g_lsep = torch.from_numpy(outp).cuda(), torch.from_numpy(lsep).cuda()
+    for bf16 in (False, True):
+        out = torch.full((info.n_tokens, Hq, D), float("nan"), dtype=torch.bfloat16 if bf16 else torch.float32, device="cuda")
+        lse = torch.full((info.n_tokens, Hq), float("nan"), dtype=torch.float32, device="cuda")
+        B.tl_merge(plan, g_outp, g_lsep, out, bf16, lse)
+        torch.cuda.synchronize()
+        got_o, got_l = out.double().cpu().numpy(), lse.double().cpu().numpy()
+        for t in range(info.n_tokens):
+            rows = ex["merge_rows"][ex["merge_ptr"][t]:ex["merge_ptr"][t + 1]]
+            want_o, want_l = orc.merge_partials(outp[rows], lsep[rows])
+            both_inf = np.isneginf(want_l) & np.isneginf(got_l[t])
+            diff = np.abs(np.where(both_inf, 0.0, got_l[t]) - np.where(both_inf, 0.0, want_l))
+            assert np.all(diff <= 1e-4 * np.maximum(1.0, np.abs(np.where(both_inf, 0.0, want_l)))), t
+            tol = 2.0 ** -8 * max(1.0, float(np.abs(want_o).max())) if bf16 else 1e-5 * max(1.0, float(np.abs(want_o).max()))
+            assert np.abs(got_o[t] - want_o).max() <= tol, (t, bf16)
+        assert np.all(got_o[dead_tok, 0] == 0) and np.isneginf(got_l[dead_tok, 0])
+    B.tl_plan_destroy(plan)
+    B.tl_pool_destroy(pool)
+
+
 def test_put_path_dedup_and_ragged_fill():
     _say("put path")
     b = wl.prefill(seed=14, n_req=2, new_tokens=33, lo=150, hi=400, seg_len=128, n_slots=16, n_shared=1)
