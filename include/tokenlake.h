@@ -25,6 +25,8 @@
  *    use stamps and the lazily made device copies are plain host state).  Different pools
  *    are independent.  Compute calls on one stream run in order; the same plan may be used
  *    on several streams once its first call has returned.
+ *  - With a plan of zero new tokens the compute calls return TL_OK at once and look at no
+ *    other argument (empty tensors have null pointers).
  *  - All tensors are dense, row-major, bf16 = 16-bit brain float bit patterns.
  *  - head_dim must be 128; q_heads must be a multiple of kv_heads, at most 32 times it; seg_len must
  *    be a multiple of 64.  Anything else is TL_EINVAL.

@@ -172,6 +172,7 @@ extern "C" {
 
 tl_status tl_segment_attn(const tl_pool* pool, tl_plan* plan, const void* q_dev, float scale, float* out_partial,
                           float* lse, void* stream) {
+  if (plan && plan->n_tokens == 0) return TL_OK;   // a batch without new tokens: nothing to do, buffers may be empty
   if (!pool || !plan || !q_dev || !out_partial || !lse) TL_FAIL(TL_EINVAL, "tl_segment_attn: null argument");
   if (plan->pool != pool) TL_FAIL(TL_EINVAL, "tl_segment_attn: plan was built for another pool");
   if (!(scale > 0.f) || !std::isfinite(scale)) TL_FAIL(TL_EINVAL, "tl_segment_attn: scale must be positive and finite");
@@ -197,6 +198,7 @@ tl_status tl_segment_attn(const tl_pool* pool, tl_plan* plan, const void* q_dev,
 
 tl_status tl_causal_block(tl_plan* plan, const void* q_dev, const void* k_new_dev, const void* v_new_dev, float scale,
                           float* out_partial, float* lse, void* stream) {
+  if (plan && plan->n_tokens == 0) return TL_OK;   // a batch without new tokens: nothing to do, buffers may be empty
   if (!plan || !q_dev || !k_new_dev || !v_new_dev || !out_partial || !lse) TL_FAIL(TL_EINVAL, "tl_causal_block: null argument");
   if (!(plan->flags & TL_PLAN_SELF_BLOCK)) TL_FAIL(TL_EINVAL, "tl_causal_block: plan has no self block");
   if (!(scale > 0.f) || !std::isfinite(scale)) TL_FAIL(TL_EINVAL, "tl_causal_block: scale must be positive and finite");
@@ -223,6 +225,7 @@ tl_status tl_causal_block(tl_plan* plan, const void* q_dev, const void* k_new_de
 tl_status tl_fused_attn(const tl_pool* pool, tl_plan* plan, const void* q_dev, const void* k_new_dev,
                         const void* v_new_dev, float scale, void* out_dev, int32_t out_is_bf16, float* lse_out,
                         void* stream) {
+  if (plan && plan->n_tokens == 0) return TL_OK;   // a batch without new tokens: nothing to do, buffers may be empty
   if (!pool || !plan || !q_dev || !k_new_dev || !v_new_dev || !out_dev) TL_FAIL(TL_EINVAL, "tl_fused_attn: null argument");
   if (plan->pool != pool) TL_FAIL(TL_EINVAL, "tl_fused_attn: plan was built for another pool");
   if (!(scale > 0.f) || !std::isfinite(scale)) TL_FAIL(TL_EINVAL, "tl_fused_attn: scale must be positive and finite");
@@ -250,6 +253,7 @@ tl_status tl_fused_attn(const tl_pool* pool, tl_plan* plan, const void* q_dev, c
 
 tl_status tl_merge(tl_plan* plan, const float* out_partial, const float* lse, void* out_dev, int32_t out_is_bf16,
                    float* lse_out, void* stream) {
+  if (plan && plan->n_tokens == 0) return TL_OK;   // a batch without new tokens: nothing to do, buffers may be empty
   if (!plan || !out_partial || !lse || !out_dev) TL_FAIL(TL_EINVAL, "tl_merge: null argument");
   tl_status rc = plan_device_ready(plan);
   if (rc != TL_OK) return rc;

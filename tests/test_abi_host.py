@@ -116,7 +116,7 @@ def _check_plan_covers(b, plan, flags, fused_req=()):
     assert rows_seen == set(range(n_item_rows))
     self_rows = T if flags & B.TL_PLAN_SELF_BLOCK else 0
     assert info.n_partial_rows == n_item_rows + self_rows
-    assert info.self_row_base == (n_item_rows if self_rows else -1)
+    assert info.self_row_base == (n_item_rows if flags & B.TL_PLAN_SELF_BLOCK else -1)   # also for a batch with no tokens
     # merge lists: every partial row exactly once, under its own token
     mp, mr = ex["merge_ptr"], ex["merge_rows"]
     assert mp[0] == 0 and mp[-1] == len(mr) == info.n_merge_entries == info.n_partial_rows - len(fused_tok)

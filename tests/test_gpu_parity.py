@@ -232,6 +232,14 @@ def test_edge_cases_empty_prefix_zero_tokens_and_no_keys():
     assert torch.all(run.out[t0:t1] == 0) and torch.all(torch.isneginf(run.lse[t0:t1]))
     _check_all_requests(run, reqs=[0, 3])
     run.close()
+    # a batch without any new token: every call returns at once and writes nothing
+    base.self_block = True
+    base.req_row_ptr = np.zeros(5, np.int32)
+    for fuse in (False, True):
+        run = H.run_gpu(base, fuse=fuse)
+        assert run.info.n_tokens == 0 and run.info.n_partial_rows == 0 and run.info.n_items == 0
+        assert torch.isnan(run.out).all() and torch.isnan(run.out_partial).all()
+        run.close()
 
 
 def test_merge_of_long_partial_lists():
