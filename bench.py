@@ -331,6 +331,8 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
+    from paper_2508_17219_amd import build as _build
+    _build.ensure_built(verbose=False)       # builds only if no library is there
     B.load_library()
     if args.probe_mfma:
         probe_mfma(torch, B)

@@ -42,6 +42,12 @@ def build(verbose: bool = True, extra_flags=()) -> str:
     return LIB
 
 
+def ensure_built(verbose: bool = True) -> str:
+    """Build only if no library is there (tests, the smoke run and the benchmark call this; after a
+    change to a source, run the build itself)."""
+    return LIB if os.path.exists(LIB) else build(verbose)
+
+
 if __name__ == "__main__":
     build()
     sys.exit(0)

@@ -12,6 +12,12 @@ def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
 
 
+def pytest_sessionstart(session):
+    # the tests load the library that is built; if none is there (fresh checkout), build it once
+    from paper_2508_17219_amd import build as _b
+    _b.ensure_built(verbose=False)
+
+
 def _have_gpu():
     try:
         import torch
