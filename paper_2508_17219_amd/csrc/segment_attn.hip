@@ -29,6 +29,13 @@
 // Careful path (tiles cut short by a slot's fill, tiles on the causal diagonal, and the
 // redo): one tile at a time, masked, running maximum raised (and O rescaled) when a block
 // exceeds it by more than 2^8.
+// Repeated slots: a work item's list may name a slot several times (a multiset); the plan's tile
+// lists hold each distinct slot once with log2 of its multiplicity, which is added to the exponent
+// of the tile's probabilities (m equal keys weigh m exp(s) in numerator and denominator alike).
+//
+// TL_RG (compile time, default 1): 32-row groups per wave.  2 = 4 waves of 64 rows, one wave per
+// SIMD, half the LDS operand reads; measured equal in time to the default when built with
+// VGPR-form MFMAs (-mllvm -amdgpu-mfma-vgpr-form), slower without, and not used by the library.
 #include <type_traits>
 
 #include "attn_common.h"
