@@ -305,6 +305,8 @@ def main():
     ap.add_argument("--workload", default="prefill", choices=["prefill", "decode", "longctx", "multiturn", "tiny"])
     ap.add_argument("--turn", type=int, default=7, help="turn of the multi-turn workload (0..7)")
     ap.add_argument("--split-segments", type=int, default=0)
+    ap.add_argument("--n-req", type=int, default=0, help="decode workload only: number of requests (default 256)")
+    ap.add_argument("--median-prefix", type=int, default=0, help="decode workload only: median prefix length (default 16384)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sharing", action="store_true", help="plan with TL_PLAN_NO_SHARING (one item chain per request)")
     ap.add_argument("--three-step", action="store_true",
@@ -364,9 +366,16 @@ def main():
         }))
         return
 
-    maker = {"prefill": wl.prefill, "decode": wl.decode, "longctx": wl.longctx, "tiny": wl.tiny,
+    decode_kw = {}
+    if args.n_req:
+        decode_kw["n_req"] = args.n_req
+    if args.median_prefix:
+        decode_kw["median"] = args.median_prefix
+    maker = {"prefill": wl.prefill, "decode": lambda: wl.decode(**decode_kw), "longctx": wl.longctx, "tiny": wl.tiny,
              "multiturn": lambda: wl.multiturn(turn=args.turn)}[args.workload]
     batch = maker()
+    if args.workload == "decode" and decode_kw:
+        batch.name = "decode[%s]" % ", ".join("%s=%d" % kv for kv in sorted(decode_kw.items()))
     res = run_workload(batch, args.steps, args.warmup, torch, B, args.split_segments, fuse=not args.three_step,
                        extra_flags=B.TL_PLAN_NO_SHARING if args.no_sharing else 0, graph=args.graph)
     work = algorithmic_work(batch, res["info"])
