@@ -73,8 +73,16 @@ __global__ __launch_bounds__(32 * kMergeSlices) void lse_merge_sliced_kernel(
   const int t = mtok[blockIdx.x], hd = blockIdx.y;
   const int b = mptr[t], e = mptr[t + 1];
   const int sl = threadIdx.x >> 5, c4 = threadIdx.x & 31;
+  // (both walks take four entries at a time so that their loads are in flight together)
+  constexpr int kStep = 4 * kMergeSlices;
   float m = -INFINITY;
-  for (int jj = b + sl; jj < e; jj += kMergeSlices) m = fmaxf(m, lse[(size_t)mrows[jj] * q_heads + hd]);
+  int j0 = b + sl;
+  for (; j0 + 3 * kMergeSlices < e; j0 += kStep) {
+    const float l0 = lse[(size_t)mrows[j0] * q_heads + hd], l1 = lse[(size_t)mrows[j0 + kMergeSlices] * q_heads + hd];
+    const float l2 = lse[(size_t)mrows[j0 + 2 * kMergeSlices] * q_heads + hd], l3 = lse[(size_t)mrows[j0 + 3 * kMergeSlices] * q_heads + hd];
+    m = fmaxf(fmaxf(m, fmaxf(l0, l1)), fmaxf(l2, l3));
+  }
+  for (; j0 < e; j0 += kMergeSlices) m = fmaxf(m, lse[(size_t)mrows[j0] * q_heads + hd]);
   if (c4 == 0) sh_m[sl] = m;
   __syncthreads();
   float M = sh_m[0];
@@ -83,12 +91,29 @@ __global__ __launch_bounds__(32 * kMergeSlices) void lse_merge_sliced_kernel(
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
   float wsum = 0.f;
   if (M > -INFINITY) {
-    for (int jj = b + sl; jj < e; jj += kMergeSlices) {
-      const size_t row = (size_t)mrows[jj] * q_heads + hd;
-      const float w = expf(lse[row] - M);
-      const float4 v = ((const float4*)part)[row * 32 + c4];
+    auto add = [&](float l, const float4& v) {
+      const float w = expf(l - M);
       acc.x += w * v.x; acc.y += w * v.y; acc.z += w * v.z; acc.w += w * v.w;
       wsum += w;
+    };
+    int jj = b + sl;
+    for (; jj + 3 * kMergeSlices < e; jj += kStep) {
+      size_t row[4];
+      float l[4];
+      float4 v[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) row[u] = (size_t)mrows[jj + u * kMergeSlices] * q_heads + hd;
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        l[u] = lse[row[u]];
+        v[u] = ((const float4*)part)[row[u] * 32 + c4];
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) add(l[u], v[u]);       // same order as one by one
+    }
+    for (; jj < e; jj += kMergeSlices) {
+      const size_t row = (size_t)mrows[jj] * q_heads + hd;
+      add(lse[row], ((const float4*)part)[row * 32 + c4]);
     }
   }
   sh_acc[sl][c4] = acc;
