@@ -200,6 +200,19 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
     };
 
     // ---- final items, work lists ----------------------------------------------------------
+    // An item goes to split-K units if it has a token's worth of rows, or if it is a run shared by
+    // decode-type requests only (each with a token's worth of rows) that together would not fill
+    // one row tile: such a run has too little arithmetic for a row tile to matter and, as a handful
+    // of workgroups in a launch of its own, would only add its latency to the step.  Its tokens are
+    // then dealt to units of kUnitRows rows, which re-read the run through L2.
+    const int32_t tok_unit = std::max(1, kUnitRows / G);
+    auto unit_item = [&](const RawItem& it, int64_t n_tok) -> bool {
+      if (n_tok * G <= kUnitRows) return true;
+      if (n_tok * G > kRowTile) return false;
+      for (int32_t r : it.reqs)
+        if ((int64_t)ntok_of(r) * G > kUnitRows) return false;
+      return true;
+    };
     int split = split_segments;
     if (split == 0) {
       // Split-K chunk: long enough to amortise a unit's start-up (measured on the decode
@@ -209,7 +222,7 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
       for (const RawItem& it : raw) {
         int64_t n_tok = 0;
         for (int32_t r : it.reqs) n_tok += ntok_of(r);
-        if (n_tok * G <= kUnitRows) few_entries += it.end - it.begin;
+        if (unit_item(it, n_tok)) few_entries += (int64_t)(it.end - it.begin) * ((n_tok + tok_unit - 1) / tok_unit);
       }
       const int lo = std::max(1, 512 / pool->seg_len);
       split = (int)std::min<int64_t>(32, std::max<int64_t>(lo, (few_entries + 2047) / 2048));
@@ -224,7 +237,7 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
       for (const RawItem& it : raw) {
         int64_t n_tok = 0;
         for (int32_t r : it.reqs) n_tok += ntok_of(r);
-        if (n_tok * G > kUnitRows) wgs += ((n_tok + tok_tile - 1) / tok_tile) * pool->kv_heads;
+        if (!unit_item(it, n_tok)) wgs += ((n_tok + tok_tile - 1) / tok_tile) * pool->kv_heads;
       }
       if (wgs > 0 && wgs < n_cu) tile_chunks = (int)std::min<int64_t>(16, (2 * n_cu + wgs - 1) / wgs);
     }
@@ -236,7 +249,7 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
     for (const RawItem& it : raw) {
       int32_t n_tok = 0;
       for (int32_t r : it.reqs) n_tok += ntok_of(r);
-      const bool few_rows = (int64_t)n_tok * G <= kUnitRows;
+      const bool few_rows = unit_item(it, n_tok);
       const int32_t run = it.end - it.begin;
       const int32_t step = few_rows ? split
                            : tile_chunks > 1 ? std::max(min_chunk_slots, (run + tile_chunks - 1) / tile_chunks)
@@ -256,7 +269,8 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
         p->item_tok_ptr.push_back((int32_t)p->item_tokens.size());
         p->item_slot_ptr.push_back((int32_t)p->item_slots.size());
         if (few_rows) {
-          p->units.push_back(Work{tok_base, n_tok, row_cursor, slot_base, c1 - c0, 0, 0, 0, 0});
+          for (int32_t t0 = 0; t0 < n_tok; t0 += tok_unit)
+            p->units.push_back(Work{tok_base + t0, std::min(tok_unit, n_tok - t0), row_cursor + t0, slot_base, c1 - c0, 0, 0, 0, 0});
         } else {
           // the item's kv tokens as tiles of kKvTile rows (shared by all its row tiles)
           const int32_t full_off = (int32_t)p->tile_base.size();

@@ -230,6 +230,32 @@ def test_shared_run_becomes_one_item_read_once():
     B.tl_pool_destroy(pool)
 
 
+def test_run_shared_by_decode_tokens_becomes_units():
+    """64 sessions decode one token each over a shared prompt and private histories: the shared run
+    (64 tokens x 4 heads = 256 rows, one row tile's worth) is dealt to split-K units of 16 rows instead
+    of a launch of row tiles of its own; with 200 tokens per session it stays a row-tile item."""
+    b = wl.multiturn(turn=2, n_sessions=64, new_tokens=1, n_slots=2048)
+    pool = _pool_for(b)
+    plan = B.tl_plan_create(pool, b.q_heads, b.req_row_ptr, b.req_seg_ptr, b.seg_ids, B.TL_PLAN_SELF_BLOCK | B.TL_PLAN_FUSE_ROWS)
+    info = B.tl_plan_get_info(plan)
+    plan_pool[0] = pool
+    _check_plan_covers(b, plan, B.TL_PLAN_SELF_BLOCK | B.TL_PLAN_FUSE_ROWS)
+    assert info.n_tiles == 0 and info.n_fused_tiles == 0 and info.n_single_tokens == 64
+    ex = B.tl_plan_export(plan)
+    n_tok = np.diff(ex["item_tok_ptr"])
+    shared_items = int((n_tok == 64).sum())                  # chunks of the shared run, all 64 tokens each
+    assert shared_items >= 1 and info.n_units == (info.n_items - shared_items) + shared_items * 16   # 4 tokens per unit
+    B.tl_plan_destroy(plan)
+    B.tl_pool_destroy(pool)
+    b = wl.multiturn(turn=2, n_sessions=64, new_tokens=200, n_slots=2048)
+    pool = _pool_for(b)
+    plan = B.tl_plan_create(pool, b.q_heads, b.req_row_ptr, b.req_seg_ptr, b.seg_ids, B.TL_PLAN_SELF_BLOCK)
+    info = B.tl_plan_get_info(plan)
+    assert info.n_tiles > 0 and info.n_units == 0
+    B.tl_plan_destroy(plan)
+    B.tl_pool_destroy(pool)
+
+
 def test_single_new_tokens_get_no_causal_row_tile():
     """A request with one new token sees only itself in the self block: the plan lists it for
     the light kernel and makes row tiles only for requests with two or more tokens."""
