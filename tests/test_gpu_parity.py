@@ -360,6 +360,41 @@ def test_sharing_and_no_sharing_plans_agree():
     a.close(); n.close()
 
 
+def test_guard_rows_around_every_output_stay_untouched():
+    """Out-of-bounds canaries: partials, LSEs and outputs live inside larger allocations whose rows
+    before and after them hold a bit pattern that no kernel may change (three-step and one-pass plans,
+    ragged tiles, split-K units)."""
+    _say("guard rows")
+    b = wl.prefill(seed=19, n_req=4, new_tokens=70, lo=300, hi=900, seg_len=128, n_slots=64, n_shared=2)
+    lens = [70, 1, 200, 3]
+    b.req_row_ptr = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    pk, pv = H.device_pool(b)
+    pool = B.tl_pool_create(b.n_slots, b.seg_len, b.kv_heads, b.head_dim, pk, pv)
+    B.tl_pool_adopt(pool, b.pool_ids, b.pool_slots, b.pool_fills)
+    q, kn, vn = b.q("cuda"), b.k_new("cuda"), b.v_new("cuda")
+    Hq, D, T, guard = b.q_heads, b.head_dim, b.n_tokens, 8
+    canary = -7.25
+    for flags in (B.TL_PLAN_SELF_BLOCK, B.TL_PLAN_SELF_BLOCK | B.TL_PLAN_FUSE_ROWS):
+        B.tl_set_option("compute_units", 0)
+        plan = B.tl_plan_create(pool, Hq, b.req_row_ptr, b.req_seg_ptr, b.seg_ids, flags, 1)
+        B.tl_set_option("compute_units", 256)
+        R = B.tl_plan_get_info(plan).n_partial_rows
+        big = {name: torch.full((rows + 2 * guard,) + tail, canary, dtype=dt, device="cuda")
+               for name, rows, tail, dt in (("outp", R, (Hq, D), torch.float32), ("lsep", R, (Hq,), torch.float32),
+                                            ("out", T, (Hq, D), torch.bfloat16), ("lse", T, (Hq,), torch.float32))}
+        view = {k: v[guard:v.shape[0] - guard] for k, v in big.items()}
+        B.tl_segment_attn(pool, plan, q, b.scale, view["outp"], view["lsep"])
+        B.tl_causal_block(plan, q, kn, vn, b.scale, view["outp"], view["lsep"])
+        B.tl_merge(plan, view["outp"], view["lsep"], view["out"], True, view["lse"])
+        B.tl_fused_attn(pool, plan, q, kn, vn, b.scale, view["out"], True, view["lse"])
+        torch.cuda.synchronize()
+        for k, v in big.items():
+            assert torch.all(v[:guard] == canary) and torch.all(v[v.shape[0] - guard:] == canary), (k, flags)
+        assert not torch.any(view["out"] == canary) and not torch.any(view["lse"] == canary)     # and every token was written
+        B.tl_plan_destroy(plan)
+    B.tl_pool_destroy(pool)
+
+
 def test_deterministic_bits_run_to_run():
     _say("determinism")
     b = wl.prefill(seed=17, n_req=3, new_tokens=90, lo=300, hi=900, seg_len=128, n_slots=64, n_shared=2)
