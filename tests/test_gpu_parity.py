@@ -335,7 +335,7 @@ def test_put_path_dedup_and_ragged_fill():
     B.tl_causal_block(plan, q, kn, vn, b.scale, outp, lsep)
     B.tl_merge(plan, outp, lsep, out, False, lse)
     torch.cuda.synchronize()
-    run = H.GpuRun(b, pool, plan, info, q, kn, vn, None, None, outp, lsep, out, lse)
+    run = H.DeviceRun(b, pool, plan, info, q, kn, vn, None, None, outp, lsep, out, lse)
     _check_all_requests(run)
     run.close()
 

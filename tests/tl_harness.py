@@ -17,7 +17,7 @@ TOL_LSE = 1e-3    # max abs error on LSE
 
 
 @dataclass
-class GpuRun:
+class DeviceRun:
     batch: wl.Batch
     pool: int
     plan: int
@@ -53,7 +53,7 @@ def device_pool(batch: wl.Batch, device="cuda", poison: bool = True):
 
 
 def run_gpu(batch: wl.Batch, flags=None, split_segments: int = 0, out_bf16: bool = False, poison: bool = True,
-            pool_tensors=None, fuse: bool = False, fill_cus: int = 0) -> GpuRun:
+            pool_tensors=None, fuse: bool = False, fill_cus: int = 0) -> DeviceRun:
     dev = "cuda"
     pk, pv = pool_tensors if pool_tensors is not None else device_pool(batch, dev, poison)
     pool = B.tl_pool_create(batch.n_slots, batch.seg_len, batch.kv_heads, batch.head_dim, pk, pv)
@@ -84,7 +84,7 @@ def run_gpu(batch: wl.Batch, flags=None, split_segments: int = 0, out_bf16: bool
     if flags & B.TL_PLAN_FUSE_ROWS:
         B.tl_fused_attn(pool, plan, q, kn, vn, batch.scale, out, out_bf16, lse)
     torch.cuda.synchronize()
-    return GpuRun(batch, pool, plan, info, q, kn, vn, pk, pv, outp, lsep, out, lse)
+    return DeviceRun(batch, pool, plan, info, q, kn, vn, pk, pv, outp, lsep, out, lse)
 
 
 # ---- oracle side -------------------------------------------------------------------------
@@ -125,7 +125,7 @@ def oracle_request_rows(batch: wl.Batch, r: int, rows=None):
     return orc.partial_attention(qb[rows], k_all, v_all, batch.scale, n_visible=n_vis)
 
 
-def compare_rows(run: GpuRun, r: int, rows=None, tol_o=TOL_O, tol_lse=TOL_LSE):
+def compare_rows(run: DeviceRun, r: int, rows=None, tol_o=TOL_O, tol_lse=TOL_LSE):
     """Max abs errors of the merged output of request r against the oracle on `rows`."""
     b = run.batch
     t0 = int(b.req_row_ptr[r])
