@@ -224,7 +224,38 @@ def tl_plan_create(pool: int, q_heads: int, req_row_ptr, req_seg_ptr, seg_ids, f
 
 
 def tl_plan_destroy(plan: int):
+    _plan_shapes.pop(plan, None)
     _check(load_library().tl_plan_destroy(plan))
+
+
+# (n_tokens, n_partial_rows, q_heads, kv_heads) of every live plan: the compute wrappers check the
+# tensors they are handed against it -- the C ABI sees only pointers and cannot
+_plan_shapes = {}
+
+
+def _shape_of(plan: int):
+    sh = _plan_shapes.get(plan)
+    if sh is None:
+        i = tl_plan_get_info(plan)
+        sh = _plan_shapes[plan] = (i.n_tokens, i.n_partial_rows, i.q_heads, i.kv_heads)
+    return sh
+
+
+def _need(t, name: str, rows: int, heads: int, dim, kind: str):
+    """t must be a device tensor of the given element kind with at least rows x heads (x dim) elements."""
+    if t is None or rows == 0 or isinstance(t, int):
+        return
+    if not _kinds:
+        import torch
+        _kinds.update(bf16=torch.bfloat16, f32=torch.float32)
+    if t.dtype != _kinds[kind]:
+        raise TypeError("%s must be %s, is %s" % (name, kind, t.dtype))
+    n = rows * heads * (dim or 1)
+    if t.numel() < n:
+        raise ValueError("%s has %d elements, the plan needs %d" % (name, t.numel(), n))
+
+
+_kinds = {}
 
 
 def tl_plan_get_info(plan: int) -> tl_plan_info:
@@ -261,15 +292,23 @@ def tl_plan_export(plan: int) -> dict:
 
 # ---- compute ----------------------------------------------------------------------------
 def tl_segment_attn(pool: int, plan: int, q, scale: float, out_partial, lse, stream=None):
+    T, R, hq, _ = _shape_of(plan)
+    _need(q, "q", T, hq, 128, "bf16"); _need(out_partial, "out_partial", R, hq, 128, "f32"); _need(lse, "lse", R, hq, None, "f32")
     _check(load_library().tl_segment_attn(pool, plan, _dev(q), scale, _dev(out_partial), _dev(lse), _stream(stream)))
 
 
 def tl_causal_block(plan: int, q, k_new, v_new, scale: float, out_partial, lse, stream=None):
+    T, R, hq, hkv = _shape_of(plan)
+    _need(q, "q", T, hq, 128, "bf16"); _need(k_new, "k_new", T, hkv, 128, "bf16"); _need(v_new, "v_new", T, hkv, 128, "bf16")
+    _need(out_partial, "out_partial", R, hq, 128, "f32"); _need(lse, "lse", R, hq, None, "f32")
     _check(load_library().tl_causal_block(plan, _dev(q), _dev(k_new), _dev(v_new), scale, _dev(out_partial), _dev(lse),
                                           _stream(stream)))
 
 
 def tl_fused_attn(pool: int, plan: int, q, k_new, v_new, scale: float, out, out_is_bf16: bool, lse_out=None, stream=None):
+    T, _, hq, hkv = _shape_of(plan)
+    _need(q, "q", T, hq, 128, "bf16"); _need(k_new, "k_new", T, hkv, 128, "bf16"); _need(v_new, "v_new", T, hkv, 128, "bf16")
+    _need(out, "out", T, hq, 128, "bf16" if out_is_bf16 else "f32"); _need(lse_out, "lse_out", T, hq, None, "f32")
     _check(load_library().tl_fused_attn(pool, plan, _dev(q), _dev(k_new), _dev(v_new), scale, _dev(out),
                                         int(bool(out_is_bf16)), _dev(lse_out), _stream(stream)))
 
@@ -282,6 +321,9 @@ def tl_probe_mfma(random_operands: bool, iters: int, scratch, stream=None) -> fl
 
 
 def tl_merge(plan: int, out_partial, lse, out, out_is_bf16: bool, lse_out=None, stream=None):
+    T, R, hq, _ = _shape_of(plan)
+    _need(out_partial, "out_partial", R, hq, 128, "f32"); _need(lse, "lse", R, hq, None, "f32")
+    _need(out, "out", T, hq, 128, "bf16" if out_is_bf16 else "f32"); _need(lse_out, "lse_out", T, hq, None, "f32")
     _check(load_library().tl_merge(plan, _dev(out_partial), _dev(lse), _dev(out), int(bool(out_is_bf16)), _dev(lse_out),
                                    _stream(stream)))
 

@@ -464,3 +464,32 @@ def test_random_batches_every_pair_once_under_every_plan_mode():
                 _check_plan_covers(b, plan, flags, fused_req=fused)
                 B.tl_plan_destroy(plan)
         B.tl_pool_destroy(plan_pool[0])
+
+
+def test_binding_checks_tensor_sizes_and_types_against_the_plan():
+    """The C ABI takes bare pointers; the Python wrappers compare the tensors they are handed with
+    the plan (cached at its first use) before anything is enqueued.  CPU tensors stand in here: the
+    checks look at dtype and element count only and fail before any device call."""
+    import torch
+    b = wl.tiny()
+    pool = _pool_for(b)
+    plan = B.tl_plan_create(pool, b.q_heads, b.req_row_ptr, b.req_seg_ptr, b.seg_ids, B.TL_PLAN_SELF_BLOCK)
+    info = B.tl_plan_get_info(plan)
+    T, R, hq, hkv = info.n_tokens, info.n_partial_rows, b.q_heads, b.kv_heads
+    q = torch.zeros((T, hq, 128), dtype=torch.bfloat16)
+    kn = torch.zeros((T, hkv, 128), dtype=torch.bfloat16)
+    outp = torch.zeros((R, hq, 128), dtype=torch.float32)
+    lsep = torch.zeros((R, hq), dtype=torch.float32)
+    out = torch.zeros((T, hq, 128), dtype=torch.float32)
+    with pytest.raises(ValueError):
+        B.tl_segment_attn(pool, plan, q, b.scale, outp[:R - 1], lsep)             # a partial row short
+    with pytest.raises(TypeError):
+        B.tl_segment_attn(pool, plan, q.float(), b.scale, outp, lsep)             # q not bf16
+    with pytest.raises(ValueError):
+        B.tl_causal_block(plan, q, kn[:T - 1], kn, b.scale, outp, lsep)
+    with pytest.raises(TypeError):
+        B.tl_merge(plan, outp, lsep, out, True, None)                             # fp32 tensor declared bf16
+    with pytest.raises(ValueError):
+        B.tl_fused_attn(pool, plan, q, kn, kn, b.scale, out[:T - 1], False, None)
+    B.tl_plan_destroy(plan)
+    B.tl_pool_destroy(pool)
