@@ -743,6 +743,96 @@ def test_batched_append_equals_the_oracles_chain_by_chain_appends():
     B.tl_pool_destroy(pool)
 
 
+def test_multi_turn_sessions_as_a_closed_loop_on_the_device():
+    """Three turns of four sessions over a shared prompt: every turn plans the batch of new tokens
+    over (shared prompt + what the session has appended so far), runs the one-pass attention, checks
+    every row against the oracle, and appends the turn's own new-token K/V to the session's chain
+    with one tl_pool_append_batch call -- the KV a turn attends to is what earlier turns put there."""
+    _say("closed multi-turn loop")
+    seed, hq, hkv, C, n_slots, d = 83, 8, 2, 64, 64, 128
+    dev = "cuda"
+    pk = torch.full((n_slots, C, hkv, d), float("nan"), dtype=torch.bfloat16, device=dev)
+    pv = torch.full((n_slots, C, hkv, d), float("nan"), dtype=torch.bfloat16, device=dev)
+    pool = B.tl_pool_create(n_slots, C, hkv, d, pk, pv)
+    opk = np.zeros((n_slots, C, hkv, d), np.uint16)
+    opv = np.zeros_like(opk)
+    table = orc.SlotTable(n_slots, C)
+    scale = 1.0 / math.sqrt(d)
+    cursor = [0]
+
+    def gen(stream, n, heads):        # n rows of `heads` heads, same bits on both devices
+        per = heads * d
+        g = wl.normal_bf16_range(seed, stream, cursor[0] * hq * d, n * per, dev).view(n, heads, d)
+        c = wl.bits_u16(wl.normal_bf16_range(seed, stream, cursor[0] * hq * d, n * per, "cpu").view(n, heads, d))
+        return g, c
+
+    shared = [1, 2, 3]
+    for sid in shared:                 # the shared prompt: three full segments
+        kg, kc = gen(wl.STREAM_POOL_K, C, hkv)
+        vg, vc = gen(wl.STREAM_POOL_V, C, hkv)
+        cursor[0] += C
+        slot = B.tl_pool_put(pool, sid, kg, vg, C)
+        assert slot == table.put(sid, C)
+        opk[slot], opv[slot] = kc, vc
+    n_sess = 4
+    chains = [[] for _ in range(n_sess)]
+    totals = [0] * n_sess
+    next_id = 100
+    for turn, lens in enumerate([[70, 150, 40, 200], [33, 64, 130, 1], [129, 20, 65, 90]]):
+        T = sum(lens)
+        row_ptr = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+        lists = [shared + chains[s_] for s_ in range(n_sess)]
+        seg_ptr = np.concatenate([[0], np.cumsum([len(l) for l in lists])]).astype(np.int32)
+        ids = np.array([i for l in lists for i in l], np.uint64)
+        qg, qc = gen(wl.STREAM_Q, T, hq)
+        kng, knc = gen(wl.STREAM_KNEW, T, hkv)
+        vng, vnc = gen(wl.STREAM_VNEW, T, hkv)
+        cursor[0] += T
+        B.tl_set_option("compute_units", 0)
+        plan = B.tl_plan_create(pool, hq, row_ptr, seg_ptr, ids, B.TL_PLAN_SELF_BLOCK | B.TL_PLAN_FUSE_ROWS)
+        B.tl_set_option("compute_units", 256)
+        info = B.tl_plan_get_info(plan)
+        R = max(info.n_partial_rows, 1)
+        outp = torch.full((R, hq, d), float("nan"), dtype=torch.float32, device=dev)
+        lsep = torch.full((R, hq), float("nan"), dtype=torch.float32, device=dev)
+        out = torch.full((T, hq, d), float("nan"), dtype=torch.float32, device=dev)
+        lse = torch.full((T, hq), float("nan"), dtype=torch.float32, device=dev)
+        B.tl_segment_attn(pool, plan, qg, scale, outp, lsep)
+        B.tl_causal_block(plan, qg, kng, vng, scale, outp, lsep)
+        B.tl_merge(plan, outp, lsep, out, False, lse)
+        B.tl_fused_attn(pool, plan, qg, kng, vng, scale, out, False, lse)
+        torch.cuda.synchronize()
+        for s_ in range(n_sess):
+            t0, t1 = int(row_ptr[s_]), int(row_ptr[s_ + 1])
+            sl = table.lookup(lists[s_])
+            gk_, gv_ = orc.gather_segments(opk, opv, sl, table.fill(sl))
+            k_all = np.concatenate([gk_, knc[t0:t1]], axis=0)
+            v_all = np.concatenate([gv_, vnc[t0:t1]], axis=0)
+            want_o, want_l = orc.partial_attention(qc[t0:t1], k_all, v_all, scale, n_visible=gk_.shape[0] + np.arange(t1 - t0) + 1)
+            err_o = np.abs(out[t0:t1].double().cpu().numpy() - want_o).max()
+            err_l = np.abs(lse[t0:t1].double().cpu().numpy() - want_l).max()
+            assert err_o <= H.TOL_O and err_l <= H.TOL_LSE, (turn, s_, err_o, err_l)
+        B.tl_plan_destroy(plan)
+        # the turn's new tokens become prefix: one batched append for all sessions
+        tails, new_ids = [], []
+        for s_ in range(n_sess):
+            tail = chains[s_][-1] if chains[s_] and totals[s_] % C else None
+            room = C - totals[s_] % C if tail is not None else 0
+            need = -(-max(0, lens[s_] - room) // C)
+            tails.append(tail)
+            new_ids.append(list(range(next_id, next_id + need)))
+            next_id += need
+        got = B.tl_pool_append_batch(pool, tails, new_ids, lens, kng, vng)
+        for s_ in range(n_sess):
+            t0, t1 = int(row_ptr[s_]), int(row_ptr[s_ + 1])
+            orc.append_rows(opk, opv, table, tails[s_], new_ids[s_], knc[t0:t1], vnc[t0:t1])
+            chains[s_] += new_ids[s_]
+            totals[s_] += lens[s_]
+        assert got.tolist() == table.lookup([i for x in new_ids for i in x]).tolist()
+    assert all(len(ch) >= 3 for ch in chains)
+    B.tl_pool_destroy(pool)
+
+
 @pytest.mark.parametrize("hq,hkv", [(4, 4), (8, 4), (32, 1), (16, 16), (28, 4), (6, 2), (5, 1), (24, 2)])
 def test_head_group_sizes_from_mha_to_one_kv_head(hq, hkv):
     """The paper's own model is multi-head (one kv head per q head); the named configurations are
