@@ -28,16 +28,40 @@ __global__ __launch_bounds__(256) void lse_merge_kernel(const float* __restrict_
   const int idx = blockIdx.y * blockDim.x + threadIdx.x;
   if (idx < q_heads * 32) {
     const int hd = idx >> 5, c4 = idx & 31;
+    // the first kHead entries (every entry, for the short lists this kernel is given) are fetched
+    // together, LSEs first, then the partial rows, so that the loads overlap; a longer list goes on
+    // one entry at a time
+    constexpr int kHead = 8;
+    size_t row[kHead];
+    float l[kHead];
     float M = -INFINITY;
-    for (int jj = b; jj < e; ++jj) M = fmaxf(M, lse[(size_t)mrows[jj] * q_heads + hd]);
+#pragma unroll
+    for (int u = 0; u < kHead; ++u) {
+      row[u] = b + u < e ? (size_t)mrows[b + u] * q_heads + hd : 0;
+      l[u] = b + u < e ? lse[row[u]] : -INFINITY;
+      M = fmaxf(M, l[u]);
+    }
+    for (int jj = b + kHead; jj < e; ++jj) M = fmaxf(M, lse[(size_t)mrows[jj] * q_heads + hd]);
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
     float wsum = 0.f;
     if (M > -INFINITY) {
-      for (int jj = b; jj < e; ++jj) {
-        const size_t row = (size_t)mrows[jj] * q_heads + hd;
-        const float w = expf(lse[row] - M);
-        const float4 v = ((const float4*)part)[row * 32 + c4];
-        acc.x += w * v.x; acc.y += w * v.y; acc.z += w * v.z; acc.w += w * v.w;
+      float4 v[kHead];
+#pragma unroll
+      for (int u = 0; u < kHead; ++u)
+        v[u] = b + u < e ? ((const float4*)part)[row[u] * 32 + c4] : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+      for (int u = 0; u < kHead; ++u) {
+        if (b + u < e) {
+          const float w = expf(l[u] - M);
+          acc.x += w * v[u].x; acc.y += w * v[u].y; acc.z += w * v[u].z; acc.w += w * v[u].w;
+          wsum += w;
+        }
+      }
+      for (int jj = b + kHead; jj < e; ++jj) {
+        const size_t r = (size_t)mrows[jj] * q_heads + hd;
+        const float w = expf(lse[r] - M);
+        const float4 x = ((const float4*)part)[r * 32 + c4];
+        acc.x += w * x.x; acc.y += w * x.y; acc.z += w * x.z; acc.w += w * x.w;
         wsum += w;
       }
       const float inv = 1.f / wsum;
