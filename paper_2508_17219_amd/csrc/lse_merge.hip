@@ -1,6 +1,7 @@
 // Exact recombination of partial outputs by their log-sum-exp (paper Section 2.1: partial
 // outputs and normalizers are reduced into the final output; Section 4, first paragraph),
-// and the three compute entry points of the ABI.
+// the self block of single-token requests, and the four compute entry points of the ABI
+// (tl_segment_attn, tl_causal_block, tl_fused_attn, tl_merge).
 #include <cmath>
 
 #include "attn_common.h"
