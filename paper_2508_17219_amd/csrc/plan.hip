@@ -215,17 +215,29 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
     };
     int split = split_segments;
     if (split == 0) {
-      // Split-K chunk: long enough to amortise a unit's start-up (measured on the decode
-      // workload: 2 slots 5.6 TB/s, 8 slots 6.0, 16 slots 6.1), short enough to leave about
-      // 2048 units for 256 CUs; never below 512 tokens or above 32 slots.
-      int64_t few_entries = 0;
+      // Split-K chunk, in slots.  Measured on decode batches of 1 to 1024 requests: long chunks stream
+      // best (2 slots 5.6 TB/s, 8 slots 6.0, 32 slots 6.1, and fewer partials to merge), as long as
+      // there are about as many units as CUs or more; equal-sized units that overflow one round of CUs
+      // by a little leave a thin second round that cannot fill the memory system.  So: the longest
+      // chunk (at most 32 slots, at least 512 tokens) that still gives three quarters of a unit per
+      // CU, halved if the count then lands between one and one and a half rounds.
+      std::vector<std::pair<int64_t, int64_t>> runs;     // (list entries, token groups) of every unit item
       for (const RawItem& it : raw) {
         int64_t n_tok = 0;
         for (int32_t r : it.reqs) n_tok += ntok_of(r);
-        if (unit_item(it, n_tok)) few_entries += (int64_t)(it.end - it.begin) * ((n_tok + tok_unit - 1) / tok_unit);
+        if (unit_item(it, n_tok)) runs.emplace_back(it.end - it.begin, (n_tok + tok_unit - 1) / tok_unit);
       }
+      auto units_with = [&](int sp) {
+        int64_t u = 0;
+        for (const auto& r : runs) u += (r.first + sp - 1) / sp * r.second;
+        return u;
+      };
       const int lo = std::max(1, 512 / pool->seg_len);
-      split = (int)std::min<int64_t>(32, std::max<int64_t>(lo, (few_entries + 2047) / 2048));
+      const int64_t cus = n_cu > 0 ? n_cu : kComputeUnits;
+      split = 32;
+      while (split > lo && 4 * units_with(split) < 3 * cus) --split;
+      const int64_t u = units_with(split);
+      if (u > cus && 2 * u < 3 * cus && split >= 2 * lo) split /= 2;
     }
     // Row-tile items of a small batch: when all row tiles together are fewer workgroups than the
     // GPU has CUs, long slot lists are cut into chunks (each a work item with partial rows of its
