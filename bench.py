@@ -158,20 +158,51 @@ def run_workload(batch, steps, warmup, torch, B, split_segments=0, fuse=True, ex
     return res
 
 
-def probe_mfma(torch, B, iters=8000, reps=5):
-    """Sustained rate of the matrix unit alone (no memory, LDS or vector work), with constant and
-    with changing operands: context for the published peak the roofline fractions are taken against."""
+_probe_lib = None
+
+
+def _probe():
+    """libtlprobe.so: a kernel of MFMAs only.  A measurement aid of this benchmark, built beside the
+    library by paper_2508_17219_amd.build and loaded here alone (no part of the C ABI)."""
+    global _probe_lib
+    if _probe_lib is None:
+        import ctypes as C
+        from paper_2508_17219_amd import build as _build
+        if not os.path.exists(_build.PROBE_LIB):
+            _build.build_probe(verbose=False)
+        lib = C.CDLL(_build.PROBE_LIB)
+        lib.tlprobe_mfma.restype = C.c_int32
+        lib.tlprobe_mfma.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.POINTER(C.c_double), C.c_void_p]
+        _probe_lib = lib
+    return _probe_lib
+
+
+def mfma_sustained(torch, random_operands, iters=2000, reps=3):
+    """TFLOP/s of the matrix unit alone (no memory, LDS or vector work), best of `reps` launches."""
+    import ctypes as C
+    lib = _probe()
     scratch = torch.zeros(16, dtype=torch.float32, device="cuda")
+    st = torch.cuda.current_stream().cuda_stream or None
+    best = 0.0
+    for _ in range(reps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        fl = C.c_double(0.0)
+        e0.record()
+        rc = lib.tlprobe_mfma(int(bool(random_operands)), iters, scratch.data_ptr(), C.byref(fl), st)
+        e1.record()
+        torch.cuda.synchronize()
+        if rc != 0:
+            raise RuntimeError("tlprobe_mfma failed (%d)" % rc)
+        best = max(best, fl.value / (e0.elapsed_time(e1) * 1e-3) / 1e12)
+    return best
+
+
+def probe_mfma(torch, iters=8000, reps=5):
+    """Sustained rate of the matrix unit alone, with constant and with changing operands: context
+    for the published peak the roofline fractions are taken against."""
     out = {}
     for name, rnd in (("constant_operands", False), ("changing_random_operands", True)):
-        best = 0.0
-        for _ in range(reps):
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            fl = B.tl_probe_mfma(rnd, iters, scratch)
-            e1.record()
-            torch.cuda.synchronize()
-            best = max(best, fl / (e0.elapsed_time(e1) * 1e-3) / 1e12)
+        best = mfma_sustained(torch, rnd, iters, reps)
         out[name] = {"TFLOP/s": best, "frac_of_peak": best / PEAK_BF16_TFLOPS}
     print(json.dumps({"probe": "mfma_f32_32x32x16_bf16 only, 1024 workgroups x 8 waves, %d x 32 instructions per wave, "
                                "best of %d launches" % (iters, reps), "peak_TFLOP/s": PEAK_BF16_TFLOPS, **out}))
@@ -353,7 +384,7 @@ def main():
     _build.ensure_built(verbose=False)       # builds only if no library is there
     B.load_library()
     if args.probe_mfma:
-        probe_mfma(torch, B)
+        probe_mfma(torch)
         return
     if args.calibrate_copy:
         calibrate_copy(torch)

@@ -17,9 +17,10 @@
  *  - Compute calls enqueue kernels on `stream` (a hipStream_t passed as void*, NULL = the
  *    default stream) and return without synchronising.
  *    tl_segment_attn, tl_causal_block, tl_merge and tl_fused_attn enqueue nothing but
- *    kernels, except that the first of them after a put / append / adopt uploads the pool's
- *    fill table with one asynchronous copy: run one step eagerly before capturing a step
- *    into a HIP graph.
+ *    kernels, except that the first call that uses a plan makes the plan's device copy (one
+ *    hipMalloc, one asynchronous copy on `stream`) and the first tl_segment_attn after an
+ *    adopt or evict uploads the pool's fill table (one asynchronous copy): run one step
+ *    eagerly before capturing a step into a HIP graph.
  *  - A pool, and the plans made from it, belong to one host thread at a time: calls on the
  *    same pool or plan from several threads need the caller's own lock (the id table, the
  *    use stamps and the lazily made device copies are plain host state).  Different pools
@@ -27,6 +28,12 @@
  *    on several streams once its first call has returned.
  *  - With a plan of zero new tokens the compute calls return TL_OK at once and look at no
  *    other argument (empty tensors have null pointers).
+ *  - A plan holds slot numbers and fills as they were when it was built.  Any change to the
+ *    pool's slots afterwards (tl_pool_put of a new id, tl_pool_append, tl_pool_append_batch,
+ *    tl_pool_adopt, tl_pool_evict_lru) makes it stale: tl_segment_attn and tl_fused_attn then
+ *    return TL_EINVAL and enqueue nothing; build a new plan (Section 3.2: plans are made per
+ *    iteration).  tl_pool_release and a put of a resident id change no slot and keep plans valid.
+ *    A plan may outlive its pool only to be destroyed or read back (info, export, hot slots).
  *  - All tensors are dense, row-major, bf16 = 16-bit brain float bit patterns.
  *  - head_dim must be 128; q_heads must be a multiple of kv_heads, at most 32 times it; seg_len must
  *    be a multiple of 64.  Anything else is TL_EINVAL.
@@ -162,6 +169,10 @@ typedef struct tl_plan tl_plan;
 enum {
   TL_PLAN_SELF_BLOCK = 1, /* reserve partial rows for tl_causal_block and merge them   */
   TL_PLAN_NO_SHARING = 2, /* do not group requests: one item chain per request         */
+  TL_PLAN_WALK_REPEATS = 8, /* a row-tile work item walks a slot once per occurrence in its list.
+                             Default (flag absent): a slot that the list names m times is walked
+                             once with weight m (exact: m equal keys contribute m exp(s) to the
+                             numerator and the denominator alike)                          */
   TL_PLAN_FUSE_ROWS = 4   /* requests that gain nothing from sharing a run of slots leave the
                              three-step path: one pass of tl_fused_attn over their whole slot
                              list and their own new tokens writes their final output.  These
@@ -194,18 +205,22 @@ typedef struct tl_plan_info {
                               written by a light kernel of tl_causal_block                */
   int64_t tile_pairs;      /* (query token, kv token) pairs the row-tile kernels compute: as
                               prefix_pairs over row-tile work, each distinct slot of a work
-                              item's list counted once (see "dedupe_tiles")                */
+                              item's list counted once (unless TL_PLAN_WALK_REPEATS)       */
 } tl_plan_info;
 
 /* req_row_ptr: host [n_req+1], offsets of each request's new tokens in the batch's Q
  * (req_row_ptr[0] = 0, non-decreasing).  req_seg_ptr: host [n_req+1], offsets into seg_ids.
  * seg_ids: host, the ordered prefix of each request.  split_segments: list entries per
- * split-K chunk for items with few rows (0 = library default).
+ * split-K chunk for items with few rows (0 = library default).  compute_units: the number
+ * of CUs the plan fills (negative = 256, MI355X; at most 4096): a batch with fewer row-tile
+ * workgroups than this gets KV-chunked work items instead of one-pass rows, and the default
+ * split-K chunk is sized for it; 0 = never cut a row-tile item along its KV.
  * Errors: TL_ENOTFOUND if an id is not resident; TL_EINVAL on malformed arrays.
- * Makes no HIP call: device copies of the plan are made on first use. */
+ * Makes no HIP call: the device copy of the plan is made by the first compute call that uses
+ * it (one hipMalloc and one copy enqueued on that call's stream). */
 tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, int32_t n_req,
                          const int32_t* req_row_ptr, const int32_t* req_seg_ptr, const uint64_t* seg_ids,
-                         int32_t flags, int32_t split_segments);
+                         int32_t flags, int32_t split_segments, int32_t compute_units);
 tl_status tl_plan_destroy(tl_plan* plan);
 tl_status tl_plan_get_info(const tl_plan* plan, tl_plan_info* info);
 
@@ -253,10 +268,6 @@ tl_status tl_segment_attn(const tl_pool* pool, tl_plan* plan, const void* q_dev,
 tl_status tl_causal_block(tl_plan* plan, const void* q_dev, const void* k_new_dev, const void* v_new_dev,
                           float scale, float* out_partial, float* lse, void* stream);
 
-/* Exact recombination of each token's partials:
- *   M = max_j LSE_j, w_j = exp(LSE_j - M), O = sum_j w_j O_j / sum_j w_j, LSE = M + ln sum_j w_j.
- * out_dev: device [n_tokens, q_heads, 128], bf16 if out_is_bf16 else fp32.
- * lse_out: device [n_tokens, q_heads] fp32, or NULL. */
 /* The whole path in one pass for the requests that TL_PLAN_FUSE_ROWS took out of the three
  * steps (paper Section 3.3: prefix attention and the new tokens' self-attention of a request
  * need not be separate passes when one engine holds both): each row tile walks the request's
@@ -269,19 +280,18 @@ tl_status tl_fused_attn(const tl_pool* pool, tl_plan* plan, const void* q_dev, c
                         const void* v_new_dev, float scale, void* out_dev, int32_t out_is_bf16, float* lse_out,
                         void* stream);
 
+/* Exact recombination of each token's partials (Section 2.1: partial outputs and normalizers are
+ * reduced into the final output; Section 4, first paragraph):
+ *   M = max_j LSE_j, w_j = exp(LSE_j - M), O = sum_j w_j O_j / sum_j w_j, LSE = M + ln sum_j w_j.
+ * out_partial / lse: device, the rows that tl_segment_attn and tl_causal_block wrote.
+ * out_dev: device [n_tokens, q_heads, 128], bf16 if out_is_bf16 else fp32.
+ * lse_out: device [n_tokens, q_heads] fp32, or NULL.  Tokens of one-pass requests are not written. */
 tl_status tl_merge(tl_plan* plan, const float* out_partial, const float* lse, void* out_dev,
                    int32_t out_is_bf16, float* lse_out, void* stream);
 
-/* Switches for experiments and tests (process-wide).  Returns TL_EINVAL for an unknown knob
- * or a value out of range.  Knobs:
- *   "vread"          0 (default) = transposing LDS reads of V, 1 = scalar LDS reads;
- *   "compute_units"  the number of CUs the plan builder fills (default 256, MI355X; 0..4096):
- *                    a batch with fewer row-tile workgroups than this gets KV-chunked work
- *                    items instead of one-pass rows.  0 turns that off (tests of the one-pass
- *                    kernel on small shapes use it);
- *   "dedupe_tiles"   1 (default) = a row-tile work item walks a slot that its list names m
- *                    times once, with weight m (exact: m equal keys contribute m exp(s) to the
- *                    numerator and the denominator alike); 0 = once per occurrence. */
+/* Switch for tests (process-wide; both settings compute the same thing).  Returns TL_EINVAL for
+ * an unknown knob or a value out of range.  Knob:
+ *   "vread"   0 (default) = transposing LDS reads of V, 1 = scalar LDS reads. */
 tl_status tl_set_option(const char* knob, int32_t value);
 
 /* ------------------------------------------------------------------------------------
@@ -305,15 +315,6 @@ tl_status tl_model_segment_threshold(double d_q, double d_kv, double flops, doub
 tl_status tl_model_cache_load(double d, const int64_t* prefix_len, const int64_t* input_len, int32_t n,
                               int32_t n_gpus, double mem_bw, double flops, double t_ideal, double* traffic_out,
                               double* flops_out, double* load_out);
-
-/* ------------------------------------------------------------------------------------
- * Device probe (measurement aid, no part of the method): enqueues a kernel of nothing but bf16
- * 32x32x16 MFMAs on 1024 workgroups of 8 waves, iters x 32 instructions per wave, with constant
- * operands (random_operands = 0) or operands that differ from instruction to instruction.
- * scratch_dev: device, at least 4 bytes (practically never written).  *flops_out = floating-
- * point operations of the launch; the caller times it.  TL_EINVAL: iters outside 1..2^20.
- * ------------------------------------------------------------------------------------ */
-tl_status tl_probe_mfma(int32_t random_operands, int32_t iters, void* scratch_dev, double* flops_out, void* stream);
 
 #ifdef __cplusplus
 }

@@ -72,6 +72,18 @@ class SlotTable:
 
     Putting an id that is already present returns the existing slot and stores nothing.
     A new id takes `want_slot` if given (must be free), else the lowest-numbered free slot.
+
+    Life cycle (paper Section 4.3, "Replicated segment selection and eviction": eviction is
+    global LRU on the recorded last access time).  Every resident segment has a count of holders
+    and a last-access time on a logical clock that ticks once per access event:
+      put of a new id        count = 1, accessed
+      put of a resident id   count + 1, accessed
+      touch(ids)             one event for a whole batch of ids (a plan naming them): all get the same time
+      append into a tail     the tail is accessed
+      release(id)            count - 1 (the segment stays resident and usable)
+      evict_lru()            among segments with count 0, the one accessed longest ago leaves and
+                             its slot becomes free; equal times (same touch) -> the lowest slot
+    Where the paper is silent (who holds a segment, ties), this is the build's reading.
     """
 
     def __init__(self, n_slots: int, seg_len: int):
@@ -80,11 +92,59 @@ class SlotTable:
         self._slot_of = {}
         self._fill = np.zeros(self.n_slots, dtype=np.int32)
         self._used = np.zeros(self.n_slots, dtype=bool)
+        self._id_of = {}
+        self._holders = np.zeros(self.n_slots, dtype=np.int64)
+        self._accessed = np.zeros(self.n_slots, dtype=np.int64)
+        self._clock = 0
+
+    def _tick(self) -> int:
+        self._clock += 1
+        return self._clock
+
+    def touch(self, seg_ids):
+        """One access event for all the listed (resident) ids."""
+        slots = [self._slot_of[int(s)] for s in seg_ids]       # KeyError for an id that is not resident
+        now = self._tick()
+        for s in slots:
+            self._accessed[s] = now
+
+    def holders(self, seg_id: int) -> int:
+        return int(self._holders[self._slot_of[int(seg_id)]])
+
+    def n_used(self) -> int:
+        return int(self._used.sum())
+
+    def release(self, seg_id: int):
+        seg_id = int(seg_id)
+        if seg_id not in self._slot_of:
+            raise KeyError("segment not in the pool")
+        slot = self._slot_of[seg_id]
+        if self._holders[slot] <= 0:
+            raise ValueError("segment has no holder")
+        self._holders[slot] -= 1
+
+    def evict_lru(self) -> int:
+        """Removes the least recently accessed segment among those nobody holds; returns its id."""
+        best = -1
+        for slot in range(self.n_slots):
+            if self._used[slot] and self._holders[slot] == 0:
+                if best < 0 or self._accessed[slot] < self._accessed[best]:
+                    best = slot
+        if best < 0:
+            raise LookupError("no segment without holders")
+        seg_id = self._id_of.pop(best)
+        del self._slot_of[seg_id]
+        self._used[best] = False
+        self._fill[best] = 0
+        return seg_id
 
     def put(self, seg_id: int, fill: int, want_slot: int = -1) -> int:
         seg_id = int(seg_id)
         if seg_id in self._slot_of:
-            return self._slot_of[seg_id]
+            slot = self._slot_of[seg_id]
+            self._holders[slot] += 1
+            self._accessed[slot] = self._tick()
+            return slot
         if not (1 <= fill <= self.seg_len):
             raise ValueError("fill out of range")
         if want_slot >= 0:
@@ -99,6 +159,9 @@ class SlotTable:
         self._used[slot] = True
         self._fill[slot] = fill
         self._slot_of[seg_id] = slot
+        self._id_of[slot] = seg_id
+        self._holders[slot] = 1
+        self._accessed[slot] = self._tick()
         return slot
 
     def lookup(self, seg_ids) -> np.ndarray:
@@ -128,6 +191,8 @@ class SlotTable:
             tail_id = int(tail_id)
             if tail_id not in self._slot_of:
                 raise KeyError("tail segment not in the pool")
+            if self._holders[self._slot_of[tail_id]] != 1:
+                raise ValueError("a tail with other holders (or none) does not grow")
             room = self.seg_len - int(self._fill[self._slot_of[tail_id]])
         rest = max(0, n_rows - room)
         need = -(-rest // self.seg_len)
@@ -143,6 +208,7 @@ class SlotTable:
             n = min(room, n_rows)
             out.append((slot, int(self._fill[slot]), n, 0))
             self._fill[slot] += n
+            self._accessed[slot] = self._tick()
             row = n
         for sid in new_ids:
             n = min(self.seg_len, n_rows - row)

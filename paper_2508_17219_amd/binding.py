@@ -17,7 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libtokenlake.so")
 
 TL_OK, TL_EINVAL, TL_ENOMEM, TL_EFULL, TL_ENOTFOUND, TL_EHIP = 0, -1, -2, -3, -4, -5
-TL_PLAN_SELF_BLOCK, TL_PLAN_NO_SHARING, TL_PLAN_FUSE_ROWS = 1, 2, 4
+TL_PLAN_SELF_BLOCK, TL_PLAN_NO_SHARING, TL_PLAN_FUSE_ROWS, TL_PLAN_WALK_REPEATS = 1, 2, 4, 8
 
 
 class TokenLakeError(RuntimeError):
@@ -46,7 +46,6 @@ _SIGNATURES = {
     "tl_pool_destroy": (_I32, [_P]),
     "tl_pool_put": (_I32, [_P, _U64, _P, _P, _I32, _I32, C.POINTER(_I32), _P]),
     "tl_pool_append": (_I32, [_P, _I32, _U64, _P, _I32, _P, _P, _I32, _P, _P]),
-    "tl_probe_mfma": (_I32, [_I32, _I32, _P, _PF64, _P]),
     "tl_pool_append_batch": (_I32, [_P, _I32, _P, _P, _P, _P, _P, _P, _P, _P, _P]),
     "tl_pool_adopt": (_I32, [_P, _P, _P, _P, _I32, _P]),
     "tl_pool_release": (_I32, [_P, _U64]),
@@ -55,7 +54,7 @@ _SIGNATURES = {
     "tl_pool_fills": (_I32, [_P, _P, _I32, _P]),
     "tl_pool_used": (_I32, [_P, C.POINTER(_I32)]),
     "tl_pool_gather": (_I32, [_P, _P, _I32, _P, _P, _P]),
-    "tl_plan_create": (_I32, [C.POINTER(_P), _P, _I32, _I32, _P, _P, _P, _I32, _I32]),
+    "tl_plan_create": (_I32, [C.POINTER(_P), _P, _I32, _I32, _P, _P, _P, _I32, _I32, _I32]),
     "tl_plan_destroy": (_I32, [_P]),
     "tl_plan_get_info": (_I32, [_P, C.POINTER(tl_plan_info)]),
     "tl_plan_export_sizes": (_I32, [_P, C.POINTER(_I32), C.POINTER(_I32)]),
@@ -211,7 +210,7 @@ def tl_pool_gather(pool: int, slots, k_out, v_out, stream=None):
 
 # ---- plan -------------------------------------------------------------------------------
 def tl_plan_create(pool: int, q_heads: int, req_row_ptr, req_seg_ptr, seg_ids, flags: int = TL_PLAN_SELF_BLOCK,
-                   split_segments: int = 0) -> int:
+                   split_segments: int = 0, compute_units: int = -1) -> int:
     rp, sp, ids = _host(req_row_ptr, np.int32), _host(req_seg_ptr, np.int32), _host(seg_ids, np.uint64)
     if len(rp) != len(sp) or len(rp) < 1:
         raise ValueError("req_row_ptr/req_seg_ptr must both have n_req+1 entries")
@@ -219,7 +218,7 @@ def tl_plan_create(pool: int, q_heads: int, req_row_ptr, req_seg_ptr, seg_ids, f
         raise ValueError("seg_ids shorter than req_seg_ptr[-1]")
     h = _P()
     _check(load_library().tl_plan_create(C.byref(h), pool, q_heads, len(rp) - 1, rp.ctypes.data, sp.ctypes.data,
-                                         ids.ctypes.data if len(ids) else None, flags, split_segments))
+                                         ids.ctypes.data if len(ids) else None, flags, split_segments, compute_units))
     return h.value
 
 
@@ -311,13 +310,6 @@ def tl_fused_attn(pool: int, plan: int, q, k_new, v_new, scale: float, out, out_
     _need(out, "out", T, hq, 128, "bf16" if out_is_bf16 else "f32"); _need(lse_out, "lse_out", T, hq, None, "f32")
     _check(load_library().tl_fused_attn(pool, plan, _dev(q), _dev(k_new), _dev(v_new), scale, _dev(out),
                                         int(bool(out_is_bf16)), _dev(lse_out), _stream(stream)))
-
-
-def tl_probe_mfma(random_operands: bool, iters: int, scratch, stream=None) -> float:
-    """Enqueues the MFMA-only probe kernel; returns the floating-point operations of the launch."""
-    fl = C.c_double(0.0)
-    _check(load_library().tl_probe_mfma(int(bool(random_operands)), iters, _dev(scratch), C.byref(fl), _stream(stream)))
-    return fl.value
 
 
 def tl_merge(plan: int, out_partial, lse, out, out_is_bf16: bool, lse_out=None, stream=None):

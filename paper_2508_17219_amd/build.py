@@ -12,6 +12,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 LIB = os.path.join(HERE, "libtokenlake.so")
+PROBE_LIB = os.path.join(HERE, "probe", "libtlprobe.so")      # bench.py's MFMA-only probe, a library of its own
 
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "-fPIC", "-shared", "--offload-arch=gfx950",
@@ -24,12 +25,11 @@ def sources():
     return sorted(glob.glob(os.path.join(HERE, "csrc", "*.hip")))
 
 
-def build(verbose: bool = True, extra_flags=()) -> str:
-    """Compile the library (always recompiles) and return its path."""
+def _hipcc(srcs, target, verbose, extra_flags=()):
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     cmd = [hipcc] + HIPCC_FLAGS + list(extra_flags) + [
         "-I", os.path.join(ROOT, "include"), "-I", os.path.join(HERE, "csrc"),
-    ] + sources() + ["-o", LIB + ".tmp"]
+    ] + srcs + ["-o", target + ".tmp"]
     if verbose:
         print("[build]", " ".join(cmd), flush=True)
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
@@ -38,8 +38,19 @@ def build(verbose: bool = True, extra_flags=()) -> str:
         print(out, flush=True)
     if res.returncode != 0:
         raise RuntimeError("hipcc failed (%d)\n%s" % (res.returncode, out))
-    os.replace(LIB + ".tmp", LIB)
+    os.replace(target + ".tmp", target)
+    return target
+
+
+def build(verbose: bool = True, extra_flags=()) -> str:
+    """Compile the library and the benchmark's probe (always recompiles); returns the library's path."""
+    _hipcc(sources(), LIB, verbose, extra_flags)
+    build_probe(verbose)
     return LIB
+
+
+def build_probe(verbose: bool = True) -> str:
+    return _hipcc([os.path.join(HERE, "probe", "mfma_probe.hip")], PROBE_LIB, verbose)
 
 
 def ensure_built(verbose: bool = True) -> str:

@@ -56,6 +56,14 @@ __device__ __forceinline__ bf16x8 pack_bf16x8(float a0, float a1, float a2, floa
 
 __device__ __forceinline__ bf16x8 as_bf16x8(uint4 u) { return __builtin_bit_cast(bf16x8, u); }
 
+// acc + lo + hi of a packed pair of bf16 values (one v_dot2c_f32_bf16 against the pair (1, 1)):
+// the running sum of the probabilities as the matrix unit sees them, after rounding
+__device__ __forceinline__ float add_bf16_pair(float acc, unsigned pair) {
+  typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, pair), __builtin_bit_cast(bf16x2_t, 0x3f803f80u), acc,
+                                         false);
+}
+
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
 // Transposing LDS read: within each group of 16 lanes, lane j supplies the address of 4

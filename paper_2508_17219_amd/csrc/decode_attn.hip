@@ -12,11 +12,7 @@
 // Each wave stages its kv head's tiles in an LDS region of its own, and a wave's LDS
 // operations execute in program order, so no workgroup barrier is needed between the
 // wave's writes and its reads: a compiler-level ordering point is enough.
-#ifdef TL_UNIT_BLOCK_BARRIER
-#define TL_UNIT_SYNC() __syncthreads()
-#else
 #define TL_UNIT_SYNC() do { __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront"); __builtin_amdgcn_wave_barrier(); } while (0)
-#endif
 
 namespace tl {
 
@@ -60,7 +56,9 @@ __global__ __launch_bounds__(kThreads) void splitk_unit_attn_kernel(const AttnAr
   f32x4 o[8];
 #pragma unroll
   for (int d = 0; d < 8; ++d) o[d] = f32x4{0.f, 0.f, 0.f, 0.f};
-  float m_run = -INFINITY, l_run = 0.f;
+  // two row sums: the unrounded fp32 one gives the LSE, the one over the probabilities as rounded
+  // to bf16 for the second product normalises O (a convex combination of V rows whatever the rounding)
+  float m_run = -INFINITY, l_run = 0.f, lr_run = 0.f;
   const float c = a.scale_log2e;
   const size_t kv_row = (size_t)a.kv_heads * kHeadDim;
 
@@ -155,6 +153,14 @@ __global__ __launch_bounds__(kThreads) void splitk_unit_attn_kernel(const AttnAr
       l_run = l_run * alpha + lsum;
       // P^T operand: elements 0..3 = block 0 (tokens 4 c4 + r), 4..7 = block 1 (16 + 4 c4 + r)
       const bf16x8 pb = pack_bf16x8(s0[0], s0[1], s0[2], s0[3], s1[0], s1[1], s1[2], s1[3]);
+      {
+        typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+        const u32x4 w = __builtin_bit_cast(u32x4, pb);
+        float lr = lr_run * alpha;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) lr = add_bf16_pair(lr, w[i]);
+        lr_run = lr;
+      }
 #pragma unroll
       for (int d = 0; d < 8; ++d) {
         bf16x8 av;
@@ -180,8 +186,10 @@ __global__ __launch_bounds__(kThreads) void splitk_unit_attn_kernel(const AttnAr
 
   float l_tot = l_run + __shfl_xor(l_run, 16);
   l_tot += __shfl_xor(l_tot, 32);
+  float lr_tot = lr_run + __shfl_xor(lr_run, 16);
+  lr_tot += __shfl_xor(lr_tot, 32);
   if (row_ok) {
-    const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+    const float inv = lr_tot > 0.f ? 1.f / lr_tot : 0.f;
     const size_t orow = (size_t)(wk.out_row + tok_local) * a.q_heads + g * G + j;
     float* op = a.out + orow * kHeadDim;
 #pragma unroll

@@ -192,14 +192,14 @@ __global__ __launch_bounds__(256) void single_token_self_kernel(const uint16_t* 
   if (c4 == 0) lse[row] = s * scale;
 }
 
-void fill_args(AttnArgs& a, const tl_plan* plan, const void* q, float scale, float* out, float* lse) {
+void fill_args(AttnArgs& a, const tl_plan* plan, const PlanDev& d, const void* q, float scale, float* out, float* lse) {
   a.q = (const uint16_t*)q;
-  a.tok = plan->d_tok;
-  a.slots = plan->d_slots;
-  a.tile_base = plan->d_tile_base;
-  a.part_tile = plan->d_part_tile;
-  a.tile_lm = plan->any_repeat ? plan->d_tile_lm : nullptr;   // null: every tile has multiplicity 1
-  a.part_lm = plan->any_repeat ? plan->d_part_lm : nullptr;
+  a.tok = d.tok;
+  a.slots = d.slots;
+  a.tile_base = d.tile_base;
+  a.part_tile = d.part_tile;
+  a.tile_lm = plan->any_repeat ? d.tile_lm : nullptr;   // null: every tile has multiplicity 1
+  a.part_lm = plan->any_repeat ? d.part_lm : nullptr;
   a.out = out;
   a.lse = lse;
   a.q_heads = plan->q_heads;
@@ -218,30 +218,56 @@ void fill_args(AttnArgs& a, const tl_plan* plan, const void* q, float scale, flo
 
 using namespace tl;
 
+namespace {
+
+// one-pass rows of a plan whose block sits at `base` on the device
+tl_status fused_rows(const tl_pool* pool, const tl_plan* plan, const void* base, const void* q_dev, const void* k_new_dev,
+                     const void* v_new_dev, float scale, void* out_dev, int32_t out_is_bf16, float* lse_out, hipStream_t st) {
+  const PlanDev d = plan_dev(plan, base);
+  AttnArgs a;
+  fill_args(a, plan, d, q_dev, scale, nullptr, nullptr);
+  a.k = (const uint16_t*)pool->k_dev;
+  a.v = (const uint16_t*)pool->v_dev;
+  a.k2 = (const uint16_t*)k_new_dev;
+  a.v2 = (const uint16_t*)v_new_dev;
+  a.final_out = out_dev;
+  a.final_lse = lse_out;
+  a.final_is_bf16 = out_is_bf16 ? 1 : 0;
+  a.fill = nullptr;            // the row-tile kernel reads the fills that the plan baked into its tile lists
+  a.seg_len = pool->seg_len;
+  a.work = d.ftiles;
+  a.n_work = (int)plan->ftiles.size();
+  return launch_fused_row_tiles(a, a.n_work, st);
+}
+
+}  // namespace
+
 extern "C" {
 
 tl_status tl_segment_attn(const tl_pool* pool, tl_plan* plan, const void* q_dev, float scale, float* out_partial,
                           float* lse, void* stream) {
   if (plan && plan->n_tokens == 0) return TL_OK;   // a batch without new tokens: nothing to do, buffers may be empty
   if (!pool || !plan || !q_dev || !out_partial || !lse) TL_FAIL(TL_EINVAL, "tl_segment_attn: null argument");
-  if (plan->pool != pool) TL_FAIL(TL_EINVAL, "tl_segment_attn: plan was built for another pool");
+  tl_status rc = plan_is_current(plan, pool, "tl_segment_attn");
+  if (rc != TL_OK) return rc;
   if (!(scale > 0.f) || !std::isfinite(scale)) TL_FAIL(TL_EINVAL, "tl_segment_attn: scale must be positive and finite");
   hipStream_t st = (hipStream_t)stream;
-  tl_status rc = pool_device_ready(pool, st);
+  rc = pool_device_ready(pool, st);
   if (rc != TL_OK) return rc;
-  rc = plan_device_ready(plan);
+  rc = plan_device_ready(plan, st);
   if (rc != TL_OK) return rc;
+  const PlanDev d = plan_dev(plan, plan->blob_dev);
   AttnArgs a;
-  fill_args(a, plan, q_dev, scale, out_partial, lse);
+  fill_args(a, plan, d, q_dev, scale, out_partial, lse);
   a.k = (const uint16_t*)pool->k_dev;
   a.v = (const uint16_t*)pool->v_dev;
   a.fill = pool->fill_dev;
   a.seg_len = pool->seg_len;
-  a.work = plan->d_tiles;
+  a.work = d.tiles;
   a.n_work = (int)plan->tiles.size();
   rc = launch_pool_row_tiles(a, a.n_work, st);
   if (rc != TL_OK) return rc;
-  a.work = plan->d_units;
+  a.work = d.units;
   a.n_work = (int)plan->units.size();
   return launch_splitk_units(a, a.n_work, st);
 }
@@ -252,24 +278,26 @@ tl_status tl_causal_block(tl_plan* plan, const void* q_dev, const void* k_new_de
   if (!plan || !q_dev || !k_new_dev || !v_new_dev || !out_partial || !lse) TL_FAIL(TL_EINVAL, "tl_causal_block: null argument");
   if (!(plan->flags & TL_PLAN_SELF_BLOCK)) TL_FAIL(TL_EINVAL, "tl_causal_block: plan has no self block");
   if (!(scale > 0.f) || !std::isfinite(scale)) TL_FAIL(TL_EINVAL, "tl_causal_block: scale must be positive and finite");
-  tl_status rc = plan_device_ready(plan);
+  hipStream_t st = (hipStream_t)stream;
+  tl_status rc = plan_device_ready(plan, st);
   if (rc != TL_OK) return rc;
+  const PlanDev d = plan_dev(plan, plan->blob_dev);
   AttnArgs a;
-  fill_args(a, plan, q_dev, scale, out_partial, lse);
+  fill_args(a, plan, d, q_dev, scale, out_partial, lse);
   a.k = (const uint16_t*)k_new_dev;
   a.v = (const uint16_t*)v_new_dev;
   a.fill = nullptr;
   a.seg_len = 0;
-  a.work = plan->d_ctiles;
+  a.work = d.ctiles;
   a.n_work = (int)plan->ctiles.size();
   if (!plan->single_tok.empty()) {
     const int n_pairs = (int)plan->single_tok.size() * plan->q_heads;
-    hipLaunchKernelGGL(single_token_self_kernel, dim3((unsigned)((n_pairs + 7) / 8)), dim3(256), 0, (hipStream_t)stream,
-                       (const uint16_t*)q_dev, (const uint16_t*)k_new_dev, (const uint16_t*)v_new_dev, plan->d_single_tok,
+    hipLaunchKernelGGL(single_token_self_kernel, dim3((unsigned)((n_pairs + 7) / 8)), dim3(256), 0, st,
+                       (const uint16_t*)q_dev, (const uint16_t*)k_new_dev, (const uint16_t*)v_new_dev, d.single_tok,
                        n_pairs, out_partial, lse, plan->info.self_row_base, plan->q_heads, plan->group, scale);
     TL_HIP(hipGetLastError());
   }
-  return launch_causal_row_tiles(a, a.n_work, (hipStream_t)stream);
+  return launch_causal_row_tiles(a, a.n_work, st);
 }
 
 tl_status tl_fused_attn(const tl_pool* pool, tl_plan* plan, const void* q_dev, const void* k_new_dev,
@@ -277,57 +305,44 @@ tl_status tl_fused_attn(const tl_pool* pool, tl_plan* plan, const void* q_dev, c
                         void* stream) {
   if (plan && plan->n_tokens == 0) return TL_OK;   // a batch without new tokens: nothing to do, buffers may be empty
   if (!pool || !plan || !q_dev || !k_new_dev || !v_new_dev || !out_dev) TL_FAIL(TL_EINVAL, "tl_fused_attn: null argument");
-  if (plan->pool != pool) TL_FAIL(TL_EINVAL, "tl_fused_attn: plan was built for another pool");
+  tl_status rc = plan_is_current(plan, pool, "tl_fused_attn");
+  if (rc != TL_OK) return rc;
   if (!(scale > 0.f) || !std::isfinite(scale)) TL_FAIL(TL_EINVAL, "tl_fused_attn: scale must be positive and finite");
   if (plan->ftiles.empty()) return TL_OK;
   hipStream_t st = (hipStream_t)stream;
-  tl_status rc = pool_device_ready(pool, st);
+  rc = plan_device_ready(plan, st);
   if (rc != TL_OK) return rc;
-  rc = plan_device_ready(plan);
-  if (rc != TL_OK) return rc;
-  AttnArgs a;
-  fill_args(a, plan, q_dev, scale, nullptr, nullptr);
-  a.k = (const uint16_t*)pool->k_dev;
-  a.v = (const uint16_t*)pool->v_dev;
-  a.k2 = (const uint16_t*)k_new_dev;
-  a.v2 = (const uint16_t*)v_new_dev;
-  a.final_out = out_dev;
-  a.final_lse = lse_out;
-  a.final_is_bf16 = out_is_bf16 ? 1 : 0;
-  a.fill = pool->fill_dev;
-  a.seg_len = pool->seg_len;
-  a.work = plan->d_ftiles;
-  a.n_work = (int)plan->ftiles.size();
-  return launch_fused_row_tiles(a, a.n_work, st);
+  return fused_rows(pool, plan, plan->blob_dev, q_dev, k_new_dev, v_new_dev, scale, out_dev, out_is_bf16, lse_out, st);
 }
 
 tl_status tl_merge(tl_plan* plan, const float* out_partial, const float* lse, void* out_dev, int32_t out_is_bf16,
                    float* lse_out, void* stream) {
   if (plan && plan->n_tokens == 0) return TL_OK;   // a batch without new tokens: nothing to do, buffers may be empty
   if (!plan || !out_partial || !lse || !out_dev) TL_FAIL(TL_EINVAL, "tl_merge: null argument");
-  tl_status rc = plan_device_ready(plan);
+  hipStream_t st = (hipStream_t)stream;
+  tl_status rc = plan_device_ready(plan, st);
   if (rc != TL_OK) return rc;
   if (plan->merge_tok.empty()) return TL_OK;
-  hipStream_t st = (hipStream_t)stream;
+  const PlanDev d = plan_dev(plan, plan->blob_dev);
   const int n_short = plan->n_merge_short, n_long = (int)plan->merge_tok.size() - n_short;
   if (n_short > 0) {
     const dim3 grid((unsigned)n_short, (unsigned)((plan->q_heads * 32 + 255) / 256)), block(256);
     if (out_is_bf16)
-      hipLaunchKernelGGL(lse_merge_kernel<true>, grid, block, 0, st, out_partial, lse, plan->d_merge_ptr, plan->d_merge_rows,
-                         plan->d_merge_tok, out_dev, lse_out, plan->q_heads);
+      hipLaunchKernelGGL(lse_merge_kernel<true>, grid, block, 0, st, out_partial, lse, d.merge_ptr, d.merge_rows,
+                         d.merge_tok, out_dev, lse_out, plan->q_heads);
     else
-      hipLaunchKernelGGL(lse_merge_kernel<false>, grid, block, 0, st, out_partial, lse, plan->d_merge_ptr, plan->d_merge_rows,
-                         plan->d_merge_tok, out_dev, lse_out, plan->q_heads);
+      hipLaunchKernelGGL(lse_merge_kernel<false>, grid, block, 0, st, out_partial, lse, d.merge_ptr, d.merge_rows,
+                         d.merge_tok, out_dev, lse_out, plan->q_heads);
   }
   if (n_long > 0) {
     // long merge lists (split-K): the sliced kernel, one workgroup per (token, head)
     const dim3 grid((unsigned)n_long, (unsigned)plan->q_heads), block(32 * kMergeSlices);
     if (out_is_bf16)
-      hipLaunchKernelGGL(lse_merge_sliced_kernel<true>, grid, block, 0, st, out_partial, lse, plan->d_merge_ptr,
-                         plan->d_merge_rows, plan->d_merge_tok + n_short, out_dev, lse_out, plan->q_heads);
+      hipLaunchKernelGGL(lse_merge_sliced_kernel<true>, grid, block, 0, st, out_partial, lse, d.merge_ptr, d.merge_rows,
+                         d.merge_tok + n_short, out_dev, lse_out, plan->q_heads);
     else
-      hipLaunchKernelGGL(lse_merge_sliced_kernel<false>, grid, block, 0, st, out_partial, lse, plan->d_merge_ptr,
-                         plan->d_merge_rows, plan->d_merge_tok + n_short, out_dev, lse_out, plan->q_heads);
+      hipLaunchKernelGGL(lse_merge_sliced_kernel<false>, grid, block, 0, st, out_partial, lse, d.merge_ptr, d.merge_rows,
+                         d.merge_tok + n_short, out_dev, lse_out, plan->q_heads);
   }
   TL_HIP(hipGetLastError());
   return TL_OK;

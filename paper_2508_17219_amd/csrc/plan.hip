@@ -29,7 +29,7 @@ extern "C" {
 
 tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, int32_t n_req,
                          const int32_t* req_row_ptr, const int32_t* req_seg_ptr, const uint64_t* seg_ids,
-                         int32_t flags, int32_t split_segments) {
+                         int32_t flags, int32_t split_segments, int32_t compute_units) {
   if (!out) TL_FAIL(TL_EINVAL, "tl_plan_create: null out");
   *out = nullptr;
   if (!pool || n_req < 0 || !req_row_ptr || !req_seg_ptr) TL_FAIL(TL_EINVAL, "tl_plan_create: bad argument");
@@ -37,6 +37,7 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
   const int G = q_heads / pool->kv_heads;
   if (G > 32) TL_FAIL(TL_EINVAL, "tl_plan_create: q_heads/kv_heads must be at most 32");
   if (split_segments < 0) TL_FAIL(TL_EINVAL, "tl_plan_create: negative split_segments");
+  if (compute_units > 4096) TL_FAIL(TL_EINVAL, "tl_plan_create: compute_units above 4096");
   if ((flags & TL_PLAN_FUSE_ROWS) && !(flags & TL_PLAN_SELF_BLOCK))
     TL_FAIL(TL_EINVAL, "tl_plan_create: TL_PLAN_FUSE_ROWS needs TL_PLAN_SELF_BLOCK");
   if (req_row_ptr[0] != 0 || req_seg_ptr[0] != 0) TL_FAIL(TL_EINVAL, "tl_plan_create: offsets must start at 0");
@@ -58,8 +59,9 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
     p->n_req = n_req;
     p->n_tokens = T;
     p->flags = flags;
-    p->on_device = false;
-    p->blob = nullptr;
+    p->blob_dev = nullptr;
+    p->pool_generation = pool->generation;
+    p->pool_n_slots = pool->n_slots;
 
     // ---- a0: segment id -> slot ------------------------------------------------------
     std::vector<int32_t> slots(n_entries);
@@ -86,7 +88,7 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
     // traffic) -- either way it would only lose a partial per row, and a merge, on the other path.
     // Requests with a token's worth of rows (decode) always take split-K units.
     const int tok_tile = kRowTile / G;
-    const int64_t n_cu = get_option_compute_units();
+    const int64_t n_cu = compute_units < 0 ? kComputeUnits : compute_units;
     const int32_t min_chunk_slots = std::max(1, 2048 / pool->seg_len);
     std::vector<char> fused(n_req, 0);
     if (flags & TL_PLAN_FUSE_ROWS) {
@@ -168,7 +170,7 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
     // multisets: Section 3.1 has no order or uniqueness among the segments a request attends to) is
     // walked once; its tiles carry log2 of the multiplicity, which the kernel adds to the exponent
     // (m equal keys weigh m exp(s) in numerator and denominator alike).  Returns the pairs computed.
-    const bool dedupe = get_option_dedupe_tiles() != 0;
+    const bool dedupe = !(flags & TL_PLAN_WALK_REPEATS);
     std::vector<int32_t> mult_of(dedupe ? pool->n_slots : 0, 0);
     auto emit_tiles = [&](auto slot_of_pos, int32_t n_pos) -> int64_t {
       int64_t kv_tokens = 0;
@@ -420,6 +422,49 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
     inf.n_fused_tokens = n_fused_tokens;
     inf.n_single_tokens = (int32_t)p->single_tok.size();
     inf.tile_pairs = tile_pairs;
+
+    // ---- one block with everything the kernels read ---------------------------------------------
+    {
+      size_t total = 0;
+      auto reserve = [&](size_t bytes) {
+        const size_t at = total;
+        total += (bytes + 255) & ~(size_t)255;
+        return at;
+      };
+      auto& o = p->off;
+      o.tiles = reserve(sizeof(Work) * p->tiles.size());
+      o.units = reserve(sizeof(Work) * p->units.size());
+      o.ctiles = reserve(sizeof(Work) * p->ctiles.size());
+      o.ftiles = reserve(sizeof(Work) * p->ftiles.size());
+      o.tok = reserve(sizeof(int32_t) * p->tok.size());
+      o.slots = reserve(sizeof(int32_t) * p->item_slots.size());
+      o.merge_ptr = reserve(sizeof(int32_t) * p->merge_ptr.size());
+      o.merge_rows = reserve(sizeof(int32_t) * p->merge_rows.size());
+      o.tile_base = reserve(sizeof(int32_t) * p->tile_base.size());
+      o.part_tile = reserve(sizeof(int32_t) * p->part_tile.size());
+      o.merge_tok = reserve(sizeof(int32_t) * p->merge_tok.size());
+      o.single_tok = reserve(sizeof(int32_t) * p->single_tok.size());
+      o.tile_lm = reserve(sizeof(float) * p->tile_lm.size());
+      o.part_lm = reserve(sizeof(float) * p->part_lm.size());
+      p->blob_host.assign(total + 256, 0);
+      auto fill = [&](size_t at, const void* src, size_t bytes) {
+        if (bytes) memcpy(p->blob_host.data() + at, src, bytes);
+      };
+      fill(o.tiles, p->tiles.data(), sizeof(Work) * p->tiles.size());
+      fill(o.units, p->units.data(), sizeof(Work) * p->units.size());
+      fill(o.ctiles, p->ctiles.data(), sizeof(Work) * p->ctiles.size());
+      fill(o.ftiles, p->ftiles.data(), sizeof(Work) * p->ftiles.size());
+      fill(o.tok, p->tok.data(), sizeof(int32_t) * p->tok.size());
+      fill(o.slots, p->item_slots.data(), sizeof(int32_t) * p->item_slots.size());
+      fill(o.merge_ptr, p->merge_ptr.data(), sizeof(int32_t) * p->merge_ptr.size());
+      fill(o.merge_rows, p->merge_rows.data(), sizeof(int32_t) * p->merge_rows.size());
+      fill(o.tile_base, p->tile_base.data(), sizeof(int32_t) * p->tile_base.size());
+      fill(o.part_tile, p->part_tile.data(), sizeof(int32_t) * p->part_tile.size());
+      fill(o.merge_tok, p->merge_tok.data(), sizeof(int32_t) * p->merge_tok.size());
+      fill(o.single_tok, p->single_tok.data(), sizeof(int32_t) * p->single_tok.size());
+      fill(o.tile_lm, p->tile_lm.data(), sizeof(float) * p->tile_lm.size());
+      fill(o.part_lm, p->part_lm.data(), sizeof(float) * p->part_lm.size());
+    }
   } catch (const std::bad_alloc&) {
     rc = TL_ENOMEM;
     set_error("tl_plan_create: host allocation failed");
@@ -434,7 +479,7 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
 
 tl_status tl_plan_destroy(tl_plan* plan) {
   if (!plan) return TL_OK;
-  if (plan->blob) (void)hipFree(plan->blob);
+  if (plan->blob_dev) (void)hipFree(plan->blob_dev);
   delete plan;
   return TL_OK;
 }
@@ -450,8 +495,8 @@ tl_status tl_plan_hot_slots(const tl_plan* plan, int32_t max_n, int32_t* slots_o
   if (!plan->hot_ready) {
     // load of a slot = new tokens of the requests that list it
     try {
-      std::vector<int64_t> load(plan->pool->n_slots, 0);
-      std::vector<char> seen(plan->pool->n_slots, 0);
+      std::vector<int64_t> load(plan->pool_n_slots, 0);
+      std::vector<char> seen(plan->pool_n_slots, 0);
       std::vector<int32_t> order;   // first appearance, requests in order, lists front to back
       for (int32_t r = 0; r < plan->n_req; ++r)
         for (int32_t i = plan->list_ptr[r]; i < plan->list_ptr[r + 1]; ++i) {
@@ -507,70 +552,25 @@ tl_status tl_plan_export(const tl_plan* plan, int32_t* item_row_base, int32_t* i
 
 namespace tl {
 
-tl_status plan_device_ready(tl_plan* p) {
-  if (p->on_device) return TL_OK;
-  auto al = [](size_t x) { return (x + 255) & ~(size_t)255; };
-  const size_t b_tiles = al(sizeof(Work) * p->tiles.size());
-  const size_t b_units = al(sizeof(Work) * p->units.size());
-  const size_t b_ctiles = al(sizeof(Work) * p->ctiles.size());
-  const size_t b_tok = al(sizeof(int32_t) * p->tok.size());
-  const size_t b_slots = al(sizeof(int32_t) * p->item_slots.size());
-  const size_t b_mptr = al(sizeof(int32_t) * p->merge_ptr.size());
-  const size_t b_mrows = al(sizeof(int32_t) * p->merge_rows.size());
-  const size_t b_tbase = al(sizeof(int32_t) * p->tile_base.size());
-  const size_t b_part = al(sizeof(int32_t) * p->part_tile.size());
-  const size_t b_ftiles = al(sizeof(Work) * p->ftiles.size());
-  const size_t b_mtok = al(sizeof(int32_t) * p->merge_tok.size());
-  const size_t b_stok = al(sizeof(int32_t) * p->single_tok.size());
-  const size_t b_tlm = al(sizeof(float) * p->tile_lm.size());
-  const size_t b_plm = al(sizeof(float) * p->part_lm.size());
-  const size_t total = b_tiles + b_units + b_ctiles + b_tok + b_slots + b_mptr + b_mrows + b_tbase + b_part + b_ftiles + b_mtok + b_stok + b_tlm + b_plm + 256;
-  std::vector<char> host(total, 0);
-  size_t off = 0;
-  auto put = [&](const void* src, size_t bytes, size_t reserved) {
-    size_t at = off;
-    if (bytes) memcpy(host.data() + off, src, bytes);
-    off += reserved;
-    return at;
-  };
-  const size_t o_tiles = put(p->tiles.data(), sizeof(Work) * p->tiles.size(), b_tiles);
-  const size_t o_units = put(p->units.data(), sizeof(Work) * p->units.size(), b_units);
-  const size_t o_ctiles = put(p->ctiles.data(), sizeof(Work) * p->ctiles.size(), b_ctiles);
-  const size_t o_tok = put(p->tok.data(), sizeof(int32_t) * p->tok.size(), b_tok);
-  const size_t o_slots = put(p->item_slots.data(), sizeof(int32_t) * p->item_slots.size(), b_slots);
-  const size_t o_mptr = put(p->merge_ptr.data(), sizeof(int32_t) * p->merge_ptr.size(), b_mptr);
-  const size_t o_mrows = put(p->merge_rows.data(), sizeof(int32_t) * p->merge_rows.size(), b_mrows);
-  const size_t o_tbase = put(p->tile_base.data(), sizeof(int32_t) * p->tile_base.size(), b_tbase);
-  const size_t o_part = put(p->part_tile.data(), sizeof(int32_t) * p->part_tile.size(), b_part);
-  const size_t o_ftiles = put(p->ftiles.data(), sizeof(Work) * p->ftiles.size(), b_ftiles);
-  const size_t o_mtok = put(p->merge_tok.data(), sizeof(int32_t) * p->merge_tok.size(), b_mtok);
-  const size_t o_stok = put(p->single_tok.data(), sizeof(int32_t) * p->single_tok.size(), b_stok);
-  const size_t o_tlm = put(p->tile_lm.data(), sizeof(float) * p->tile_lm.size(), b_tlm);
-  const size_t o_plm = put(p->part_lm.data(), sizeof(float) * p->part_lm.size(), b_plm);
+tl_status plan_device_ready(tl_plan* p, hipStream_t stream) {
+  if (p->blob_dev) return TL_OK;
   void* blob = nullptr;
-  TL_HIP(hipMalloc(&blob, total));
-  hipError_t e = hipMemcpy(blob, host.data(), total, hipMemcpyHostToDevice);
+  TL_HIP(hipMalloc(&blob, p->blob_host.size()));
+  // on the caller's stream, in order with the kernels that read it; the host block belongs to the
+  // plan, which the caller keeps alive until the stream work of its calls has completed
+  hipError_t e = hipMemcpyAsync(blob, p->blob_host.data(), p->blob_host.size(), hipMemcpyHostToDevice, stream);
   if (e != hipSuccess) {
     (void)hipFree(blob);
     TL_FAIL(TL_EHIP, "plan upload failed: %s", hipGetErrorString(e));
   }
-  char* b = (char*)blob;
-  p->blob = blob;
-  p->d_tiles = (Work*)(b + o_tiles);
-  p->d_units = (Work*)(b + o_units);
-  p->d_ctiles = (Work*)(b + o_ctiles);
-  p->d_tok = (int32_t*)(b + o_tok);
-  p->d_slots = (int32_t*)(b + o_slots);
-  p->d_merge_ptr = (int32_t*)(b + o_mptr);
-  p->d_merge_rows = (int32_t*)(b + o_mrows);
-  p->d_tile_base = (int32_t*)(b + o_tbase);
-  p->d_part_tile = (int32_t*)(b + o_part);
-  p->d_ftiles = (Work*)(b + o_ftiles);
-  p->d_merge_tok = (int32_t*)(b + o_mtok);
-  p->d_single_tok = (int32_t*)(b + o_stok);
-  p->d_tile_lm = (float*)(b + o_tlm);
-  p->d_part_lm = (float*)(b + o_plm);
-  p->on_device = true;
+  p->blob_dev = blob;
+  return TL_OK;
+}
+
+tl_status plan_is_current(const tl_plan* plan, const tl_pool* pool, const char* who) {
+  if (plan->pool != pool) TL_FAIL(TL_EINVAL, "%s: plan was built for another pool", who);
+  if (plan->pool_generation != pool->generation)
+    TL_FAIL(TL_EINVAL, "%s: the pool has changed since the plan was built (put, append, adopt or evict): build a new plan", who);
   return TL_OK;
 }
 

@@ -13,8 +13,6 @@ namespace tl {
 
 static thread_local char g_err[512] = "";
 static int g_opt_vread = 0;
-static int g_opt_compute_units = kComputeUnits;
-static int g_opt_dedupe_tiles = 1;
 
 void set_error(const char* fmt, ...) {
   va_list ap;
@@ -24,8 +22,6 @@ void set_error(const char* fmt, ...) {
 }
 
 int get_option_vread() { return g_opt_vread; }
-int get_option_compute_units() { return g_opt_compute_units; }
-int get_option_dedupe_tiles() { return g_opt_dedupe_tiles; }
 
 // out[(i, :)] = pool[(slots[i], :)], slot_elems16 uint4 per slot; one block column per slot.
 __global__ void gather_slots_kernel(uint4* __restrict__ out, const uint4* __restrict__ pool,
@@ -112,16 +108,6 @@ tl_status tl_set_option(const char* knob, int32_t value) {
     g_opt_vread = value;
     return TL_OK;
   }
-  if (!strcmp(knob, "compute_units")) {
-    if (value < 0 || value > 4096) TL_FAIL(TL_EINVAL, "tl_set_option: compute_units must be 0..4096");
-    g_opt_compute_units = value;
-    return TL_OK;
-  }
-  if (!strcmp(knob, "dedupe_tiles")) {
-    if (value < 0 || value > 1) TL_FAIL(TL_EINVAL, "tl_set_option: dedupe_tiles must be 0 or 1");
-    g_opt_dedupe_tiles = value;
-    return TL_OK;
-  }
   TL_FAIL(TL_EINVAL, "tl_set_option: unknown knob '%s'", knob);
 }
 
@@ -147,6 +133,7 @@ tl_status tl_pool_create(tl_pool** out, int32_t n_slots, int32_t seg_len, int32_
   p->clock = 0;
   p->n_used = 0;
   p->free_hint = 0;
+  p->generation = 0;
   p->fill_dev = nullptr;
   p->fill_dirty = true;
   try {
@@ -200,6 +187,7 @@ static void occupy(tl_pool* p, int32_t slot, uint64_t id, int32_t fill) {
   p->refcnt[slot] = 1;
   p->stamp[slot] = ++p->clock;
   p->n_used++;
+  p->generation++;
 }
 
 tl_status tl_pool_put(tl_pool* pool, uint64_t segment_id, const void* k_src_dev, const void* v_src_dev, int32_t fill,
@@ -299,6 +287,7 @@ tl_status tl_pool_append_batch(tl_pool* pool, int32_t n_chains, const int32_t* h
       chunks.push_back(AppendChunk{ts, pool->fill[ts], n, row_ptr[c], 0, pool->fill[ts] + n});
       pool->fill[ts] += n;
       pool->stamp[ts] = ++pool->clock;
+      pool->generation++;
       row = n;
     }
     for (int32_t i = new_ptr[c]; i < new_ptr[c + 1]; ++i) {
@@ -380,6 +369,7 @@ tl_status tl_pool_evict_lru(tl_pool* pool, uint64_t* evicted_id) {
   pool->slot_of.erase(pool->id_of[best]);
   pool->fill[best] = 0;
   pool->n_used--;
+  pool->generation++;
   if (best < pool->free_hint) pool->free_hint = best;
   pool->fill_dirty = true;
   return TL_OK;

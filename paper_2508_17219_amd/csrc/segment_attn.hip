@@ -33,22 +33,20 @@
 // lists hold each distinct slot once with log2 of its multiplicity, which is added to the exponent
 // of the tile's probabilities (m equal keys weigh m exp(s) in numerator and denominator alike).
 //
-// TL_RG (compile time, default 1): 32-row groups per wave.  2 = 4 waves of 64 rows, one wave per
-// SIMD, half the LDS operand reads; measured equal in time to the default when built with
-// VGPR-form MFMAs (-mllvm -amdgpu-mfma-vgpr-form), slower without, and not used by the library.
+// Two row sums are kept.  The probabilities enter the second product rounded to bf16, so the
+// output is normalised by the sum of the ROUNDED values (one v_dot2c_f32_bf16 per packed pair):
+// O is then a convex combination of the V rows whatever the rounding did to the weights, and a
+// row dominated by one key returns that key's V exactly.  The normalizer that leaves the kernel
+// (LSE) comes from the sum of the unrounded fp32 values.
 #include <type_traits>
 
 #include "attn_common.h"
-
-#ifndef TL_RG
-#define TL_RG 1
-#endif
 
 namespace tl {
 
 namespace {
 
-constexpr int kRG = TL_RG;                                    // 32-row groups per wave
+constexpr int kRG = 1;                                    // 32-row groups per wave
 constexpr int kWaves = kRowTile / (32 * kRG);             // 8
 constexpr int kThreads = 64 * kWaves;                     // 512
 constexpr int kChunks = kKvTile * 16 / kThreads;          // 16-byte chunks per thread per K (or V) tile: 2
@@ -162,7 +160,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
   // O^T accumulators: o[rg][d][r] = channel 32 d + 8 (r/4) + 4 h + r%4 of the lane's row in group rg
   f32x16 o[kRG][4];
   float m_ref[kRG];   // reference point of the exponent (raw score units), -inf before any key
-  float l_run[kRG];   // this lane's share of sum exp(s - m_ref)
+  float l_run[kRG];   // this lane's share of sum exp(s - m_ref), unrounded (-> LSE)
+  float lr_run[kRG];  // the same sum over the values as rounded to bf16 for the second product (-> O)
   auto reset_state = [&]() __attribute__((always_inline)) {
 #pragma unroll
     for (int rg = 0; rg < kRG; ++rg) {
@@ -172,6 +171,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
         for (int r = 0; r < 16; ++r) o[rg][d][r] = 0.f;
       m_ref[rg] = -INFINITY;
       l_run[rg] = 0.f;
+      lr_run[rg] = 0.f;
     }
   };
   reset_state();
@@ -229,14 +229,23 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
   // in front of the LDS reads that follow; dma_wait() before the iteration's barrier is the wait)
   const unsigned lds_base_addr = __builtin_amdgcn_readfirstlane((unsigned)(size_t)(__attribute__((address_space(3))) void*)lds);
   const unsigned dma_wave_off = __builtin_amdgcn_readfirstlane(wave) * (4 * kHeadDim * 2);
+  static_assert(kDmaPerWave == 2, "dma_tile issues exactly two direct loads per wave");
   auto dma_tile = [&](const uint16_t* src, int base, uint16_t* tile, const unsigned (&off)[kDmaPerWave]) {
     const char* trow = (const char*)src + (size_t)__builtin_amdgcn_readfirstlane(base) * (kv_row * 2);
-#pragma unroll
-    for (int u = 0; u < kDmaPerWave; ++u) {
-      const unsigned dst = lds_base_addr + (unsigned)((tile - lds) + kWaves * u * 4 * kHeadDim) * 2u + dma_wave_off;
-      // address = wave-uniform 64-bit tile base (scalar registers) + this lane's constant 32-bit offset
-      asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %2" ::"v"(off[u]), "s"(dst), "s"(trow) : "memory");
-    }
+    const unsigned dst0 = lds_base_addr + (unsigned)(tile - lds) * 2u + dma_wave_off;
+    const unsigned dst1 = dst0 + (unsigned)(kWaves * 4 * kHeadDim) * 2u;
+    // address = wave-uniform 64-bit tile base (scalar registers) + this lane's constant 32-bit offset;
+    // the LDS destination travels in M0, which the compiler does not accept as a clobber: its value
+    // is put back before the statement ends
+    unsigned saved_m0;
+    asm volatile(
+        "s_mov_b32 %[sv], m0\n\t"
+        "s_mov_b32 m0, %[d0]\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %[o0], %[b]\n\t"
+        "s_mov_b32 m0, %[d1]\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %[o1], %[b]\n\t"
+        "s_mov_b32 m0, %[sv]"
+        : [sv] "=&s"(saved_m0)
+        : [o0] "v"(off[0]), [o1] "v"(off[1]), [d0] "s"(dst0), [d1] "s"(dst1), [b] "s"(trow)
+        : "memory");
   };
   // wait for all of this wave's direct loads (vmcnt(0); the other counters are left alone so that
   // LDS operand reads already in flight stay in flight)
@@ -290,11 +299,20 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
     for (int r = 0; r < 16; ++r) s[r] = fast_exp2(fmaf(s[r], c, -mc));
     pb[0] = pack_bf16x8(s[0], s[1], s[2], s[3], s[4], s[5], s[6], s[7]);
     pb[1] = pack_bf16x8(s[8], s[9], s[10], s[11], s[12], s[13], s[14], s[15]);
-    // the normaliser sums the probabilities before their rounding to bf16, in fp32
+    // the normalizer (LSE) sums the probabilities before their rounding to bf16, in fp32 ...
     float lsum = 0.f;
 #pragma unroll
     for (int r = 0; r < 16; ++r) lsum += s[r];
     l_run[rg] += lsum;
+    // ... and O is divided by the sum of what the matrix unit is given
+    float lr = lr_run[rg];
+#pragma unroll
+    for (int sp = 0; sp < 2; ++sp) {
+      const u32x4 w = __builtin_bit_cast(u32x4, pb[sp]);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) lr = add_bf16_pair(lr, w[i]);
+    }
+    lr_run[rg] = lr;
   };
   auto pv_block = [&](const uint16_t* vt, int hb, const bf16x8 (&pb)[kRG][2]) {
 #pragma unroll
@@ -316,6 +334,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
       const float alpha = (m_new == -INFINITY) ? 1.f : fast_exp2((m_ref[rg] - m_new) * c);
       m_ref[rg] = m_new;
       l_run[rg] *= alpha;
+      lr_run[rg] *= alpha;
 #pragma unroll
       for (int d = 0; d < 4; ++d)
 #pragma unroll
@@ -495,6 +514,11 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
           u32x4 (&pp)[2] = step == 0 ? p0[rg] : p1[rg];
           if (r >= 1) l_run[rg] += s[r - 1];
           if (r >= 2 && (r & 1) == 0) set_pair(pp[(r - 2) >> 3], ((r - 2) & 7) >> 1, s[r - 2], s[r - 1]);
+          // the rounded sum trails the packing by one slice; the last pair of a block is added in
+          // slice 1 of the next block (the first one adds the zeros that p1 starts with, the drain
+          // below adds the last block's)
+          if (r >= 3 && (r & 1) == 1) lr_run[rg] = add_bf16_pair(lr_run[rg], pp[(r - 3) >> 3][((r - 3) & 7) >> 1]);
+          if (r == 1) lr_run[rg] = add_bf16_pair(lr_run[rg], (step == 0 ? p1[rg] : p0[rg])[1][3]);
           if (r == 15) {
             l_run[rg] += s[15];
             set_pair(pp[1], 3, s[14], s[15]);
@@ -530,6 +554,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
       for (int rg = 0; rg < kRG; ++rg) {
         pl[rg][0] = __builtin_bit_cast(bf16x8, p1[rg][0]);
         pl[rg][1] = __builtin_bit_cast(bf16x8, p1[rg][1]);
+        lr_run[rg] = add_bf16_pair(lr_run[rg], p1[rg][1][3]);
       }
       pv_block(lds_v + ((n_full - 1) % kBufs) * kVTile, 1, pl);
     }
@@ -597,8 +622,9 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
 #pragma unroll
   for (int rg = 0; rg < kRG; ++rg) {
     const float l_tot = xor32_sum(l_run[rg]);
+    const float lr_tot = xor32_sum(lr_run[rg]);
     if (row_ok[rg]) {
-      const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+      const float inv = lr_tot > 0.f ? 1.f / lr_tot : 0.f;
       const int head = g * G + head_j[rg];
       const float lse_val = l_tot > 0.f ? m_ref[rg] * a.scale + __logf(l_tot) : -INFINITY;
       if (MODE == 2) {

@@ -38,7 +38,7 @@ constexpr int kUnitRows = 16;    // max rows per kv head of a split-K unit
 // about twice the machine balance of the measured rooflines (1.2 PFLOP/s : 6 TB/s = 200), so
 // that giving up the sharing of hot segments between requests cannot make it bandwidth-bound.
 constexpr int kFuseRows = 2 * kRowTile;
-constexpr int kComputeUnits = 256;   // MI355X (default of the "compute_units" option; the plan builder makes no HIP call)
+constexpr int kComputeUnits = 256;   // MI355X (tl_plan_create's default; the plan builder makes no HIP call)
 
 // One unit of kernel work.  Its query tokens are tok[tok_off .. tok_off+n_tok) (batch token
 // indices), its partial rows out_row .. out_row+n_tok-1.
@@ -53,8 +53,6 @@ struct Work {
 };
 
 int get_option_vread();
-int get_option_compute_units();
-int get_option_dedupe_tiles();
 
 }  // namespace tl
 
@@ -71,13 +69,15 @@ struct tl_pool {
   mutable uint64_t clock;
   int32_t n_used;
   int32_t free_hint;             // no free slot below this index
+  uint64_t generation;           // goes up whenever a slot's content, fill or owner changes (put of a new id,
+                                 // append, adopt, evict): a plan is valid for the generation it was built in
   // device mirror of fill[]
   mutable int32_t* fill_dev;
   mutable bool fill_dirty;
 };
 
 struct tl_plan {
-  const tl_pool* pool;
+  const tl_pool* pool;           // identity only after creation (never dereferenced: the pool may be gone)
   int32_t q_heads, kv_heads, group, n_req, n_tokens, flags;
   tl_plan_info info;
   std::vector<int32_t> item_row_base, item_tok_ptr, item_tokens, item_slot_ptr, item_slots;
@@ -97,15 +97,49 @@ struct tl_plan {
   std::vector<int32_t> part_tile;  // Work::part_off, pairs (first kv row, valid tokens)
   bool any_repeat = false;              // some work item's list names a slot more than once
   std::vector<float> tile_lm, part_lm;  // log2 of how often the tile's slot is listed (parallel to tile_base / part_tile pairs)
-  // device copies (made on first use)
-  bool on_device;
-  void* blob;
-  tl::Work *d_tiles, *d_units, *d_ctiles, *d_ftiles;
-  int32_t *d_tok, *d_slots, *d_merge_ptr, *d_merge_rows, *d_tile_base, *d_part_tile, *d_merge_tok, *d_single_tok;
-  float *d_tile_lm, *d_part_lm;
+  uint64_t pool_generation;      // the pool's generation when the plan was built
+  int32_t pool_n_slots;
+  // Everything the kernels read, laid out once at creation as one block of host memory (each array
+  // starts on a 256-byte boundary); the device copy is made on first use, in one transfer.
+  std::vector<char> blob_host;
+  struct {
+    size_t tiles, units, ctiles, ftiles, tok, slots, merge_ptr, merge_rows, tile_base, part_tile, merge_tok, single_tok,
+        tile_lm, part_lm;
+  } off;
+  void* blob_dev;                // hipMalloc'd copy of blob_host, or null
 };
 
 namespace tl {
+
+// Device addresses of a plan's arrays inside a copy of its block that starts at `base`.
+struct PlanDev {
+  const Work *tiles, *units, *ctiles, *ftiles;
+  const int32_t *tok, *slots, *merge_ptr, *merge_rows, *tile_base, *part_tile, *merge_tok, *single_tok;
+  const float *tile_lm, *part_lm;
+};
+inline PlanDev plan_dev(const tl_plan* p, const void* base) {
+  const char* b = (const char*)base;
+  PlanDev d;
+  d.tiles = (const Work*)(b + p->off.tiles);
+  d.units = (const Work*)(b + p->off.units);
+  d.ctiles = (const Work*)(b + p->off.ctiles);
+  d.ftiles = (const Work*)(b + p->off.ftiles);
+  d.tok = (const int32_t*)(b + p->off.tok);
+  d.slots = (const int32_t*)(b + p->off.slots);
+  d.merge_ptr = (const int32_t*)(b + p->off.merge_ptr);
+  d.merge_rows = (const int32_t*)(b + p->off.merge_rows);
+  d.tile_base = (const int32_t*)(b + p->off.tile_base);
+  d.part_tile = (const int32_t*)(b + p->off.part_tile);
+  d.merge_tok = (const int32_t*)(b + p->off.merge_tok);
+  d.single_tok = (const int32_t*)(b + p->off.single_tok);
+  d.tile_lm = (const float*)(b + p->off.tile_lm);
+  d.part_lm = (const float*)(b + p->off.part_lm);
+  return d;
+}
+
 tl_status pool_device_ready(const tl_pool* pool, hipStream_t stream);
-tl_status plan_device_ready(tl_plan* plan);
+// Makes the plan's device copy if there is none yet: one hipMalloc and one copy enqueued on `stream`.
+tl_status plan_device_ready(tl_plan* plan, hipStream_t stream);
+// TL_EINVAL if the pool has changed since the plan was built.
+tl_status plan_is_current(const tl_plan* plan, const tl_pool* pool, const char* who);
 }  // namespace tl

@@ -4,11 +4,13 @@
 // change with every instruction (pseudo-random signs and mantissas, magnitudes 2^-3..2^1, like
 // the N(0,1) inputs of the attention workloads).  The second draws far more power and the GPU
 // lowers its clock under it: the roofline discussion needs both numbers.
+//
+// A measurement aid for the benchmark, no part of the method and no part of libtokenlake.so: it
+// is built into a small library of its own (libtlprobe.so) that only bench.py loads.
 #include <hip/hip_runtime.h>
 
-#include "tl_internal.h"
+#include <cstdint>
 
-namespace tl {
 namespace {
 
 typedef __bf16 probe_bf16x8 __attribute__((ext_vector_type(8)));
@@ -53,20 +55,20 @@ __global__ __launch_bounds__(512) void mfma_probe_kernel(float* out, int iters) 
 }
 
 }  // namespace
-}  // namespace tl
 
-using namespace tl;
-
-extern "C" tl_status tl_probe_mfma(int32_t random_operands, int32_t iters, void* scratch_dev, double* flops_out,
-                                   void* stream) {
-  if (iters <= 0 || iters > (1 << 20) || !scratch_dev || !flops_out) TL_FAIL(TL_EINVAL, "tl_probe_mfma: bad argument");
+// Enqueues the probe on `stream`: 1024 workgroups of 8 waves, iters x 32 MFMAs per wave, with constant
+// operands (random_operands = 0) or operands that differ from instruction to instruction.
+// scratch_dev: device, at least 4 bytes (practically never written).  *flops_out = floating-point
+// operations of the launch; the caller times it.  Returns 0, -1 for a bad argument, -5 for a HIP error.
+extern "C" int32_t tlprobe_mfma(int32_t random_operands, int32_t iters, void* scratch_dev, double* flops_out, void* stream) {
+  if (iters <= 0 || iters > (1 << 20) || !scratch_dev || !flops_out) return -1;
   const int wgs = 1024, threads = 512;
   hipStream_t st = (hipStream_t)stream;
   if (random_operands)
     hipLaunchKernelGGL(mfma_probe_kernel<1>, dim3(wgs), dim3(threads), 0, st, (float*)scratch_dev, iters);
   else
     hipLaunchKernelGGL(mfma_probe_kernel<0>, dim3(wgs), dim3(threads), 0, st, (float*)scratch_dev, iters);
-  TL_HIP(hipGetLastError());
+  if (hipGetLastError() != hipSuccess) return -5;
   *flops_out = (double)wgs * (threads / 64) * (double)iters * 32.0 * 32768.0;
-  return TL_OK;
+  return 0;
 }

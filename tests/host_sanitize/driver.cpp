@@ -69,11 +69,10 @@ int main() {
     for (int flags : flag_sets)
       for (int cus : {0, 8, 256})
         for (int dedupe : {0, 1}) {
-          CHECK(tl_set_option("compute_units", cus) == TL_OK);
-          CHECK(tl_set_option("dedupe_tiles", dedupe) == TL_OK);
           tl_plan* plan = nullptr;
           CHECK(tl_plan_create(&plan, pool, kv_heads * group, n_req, row_ptr.data(), seg_ptr.data(),
-                               seg_ids.empty() ? nullptr : seg_ids.data(), flags, pick(0, 3)) == TL_OK);
+                               seg_ids.empty() ? nullptr : seg_ids.data(), flags | (dedupe ? 0 : TL_PLAN_WALK_REPEATS),
+                               pick(0, 3), cus) == TL_OK);
           tl_plan_info info;
           CHECK(tl_plan_get_info(plan, &info) == TL_OK);
           CHECK(info.n_tokens == row_ptr.back() && info.n_req == n_req);
@@ -93,11 +92,10 @@ int main() {
           CHECK(tl_plan_destroy(plan) == TL_OK);
           ++n_plans;
         }
-    CHECK(tl_set_option("compute_units", 256) == TL_OK && tl_set_option("dedupe_tiles", 1) == TL_OK);
     tl_plan* bad = nullptr;
     uint64_t unknown = 3;
     int32_t one_row[2] = {0, 1}, one_seg[2] = {0, 1};
-    CHECK(tl_plan_create(&bad, pool, kv_heads * group, 1, one_row, one_seg, &unknown, 0, 0) == TL_ENOTFOUND && bad == nullptr);
+    CHECK(tl_plan_create(&bad, pool, kv_heads * group, 1, one_row, one_seg, &unknown, 0, 0, -1) == TL_ENOTFOUND && bad == nullptr);
 
     // append validation (refused before any device work), release, eviction
     uint64_t new_id = 999999;

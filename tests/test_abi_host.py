@@ -89,6 +89,91 @@ def test_release_and_lru_eviction():
     B.tl_pool_destroy(pool)
 
 
+def test_pool_life_cycle_matches_the_oracle_on_random_sequences():
+    """adopt / put of a resident id / plan use / release / evict_lru: the library's table against
+    the oracle's SlotTable after every operation (slots, fills, which id an eviction removes)."""
+    rng = np.random.default_rng(29)
+    for trial in range(10):
+        n_slots, C = int(rng.integers(3, 10)), 64
+        pool = B.tl_pool_create(n_slots, C, 1, 128, FAKE_K, FAKE_V)
+        table = orc.SlotTable(n_slots, C)
+        universe = list(range(100, 116))
+        for step in range(150):
+            resident = [i for i in universe if table.lookup([i])[0] >= 0]
+            op = rng.choice(["new", "again", "plan", "release", "evict"], p=[0.3, 0.1, 0.2, 0.25, 0.15])
+            if op == "new":
+                absent = [i for i in universe if i not in resident]
+                if not absent:
+                    continue
+                sid, fill = int(rng.choice(absent)), int(rng.integers(1, C + 1))
+                if len(resident) == n_slots:
+                    continue
+                free = [s for s in range(n_slots) if s not in set(table.lookup(resident).tolist())]
+                slot = int(rng.choice(free))
+                B.tl_pool_adopt(pool, [sid], [slot], [fill])
+                assert table.put(sid, fill, slot) == slot
+            elif op == "again" and resident:
+                sid = int(rng.choice(resident))                        # dedup hit: no copy, one more holder
+                assert B.tl_pool_put(pool, sid, FAKE_K, FAKE_V, C, -1, stream=0) == table.put(sid, C)
+            elif op == "plan" and resident:
+                ids = rng.choice(resident, size=int(rng.integers(1, len(resident) + 1)), replace=True).astype(np.uint64)
+                plan = B.tl_plan_create(pool, 1, [0, 1], [0, len(ids)], ids, 0, 0)
+                B.tl_plan_destroy(plan)
+                table.touch(ids.tolist())
+            elif op == "release" and resident:
+                sid = int(rng.choice(resident))
+                if table.holders(sid) == 0:
+                    with pytest.raises(B.TokenLakeError):
+                        B.tl_pool_release(pool, sid)
+                else:
+                    B.tl_pool_release(pool, sid)
+                    table.release(sid)
+            elif op == "evict":
+                try:
+                    want = table.evict_lru()
+                except LookupError:
+                    with pytest.raises(B.TokenLakeError) as e:
+                        B.tl_pool_evict_lru(pool)
+                    assert e.value.status == B.TL_ENOTFOUND
+                else:
+                    assert B.tl_pool_evict_lru(pool) == want
+            assert np.array_equal(B.tl_pool_lookup(pool, universe), table.lookup(universe))
+            assert np.array_equal(B.tl_pool_fills(pool, np.arange(n_slots)), table.fill(np.arange(n_slots)))
+            assert B.tl_pool_used(pool) == table.n_used()
+        B.tl_pool_destroy(pool)
+
+
+def test_a_plan_goes_stale_when_the_pool_changes():
+    """A plan holds slots and fills as they were when it was built: after an adopt or an eviction the
+    compute calls that read the pool refuse it (before any device work), a release or a put of a
+    resident id leaves it valid as far as this check goes, and a fresh plan is accepted again."""
+    pool = B.tl_pool_create(4, 64, 1, 128, FAKE_K, FAKE_V)
+    B.tl_pool_adopt(pool, [10, 11], [0, 1], [64, 20])
+    lib = B.load_library()
+
+    def refused(plan):
+        # fake, never dereferenced pointers; a current plan would get as far as the device, so only
+        # the stale answer is asked for here
+        rc = lib.tl_segment_attn(pool, plan, FAKE_K, 0.1, FAKE_K, FAKE_V, None)
+        rc2 = lib.tl_fused_attn(pool, plan, FAKE_K, FAKE_K, FAKE_V, 0.1, FAKE_K, 0, None, None)
+        assert rc == rc2 or rc2 == B.TL_OK
+        return rc == B.TL_EINVAL and b"pool has changed" in lib.tl_last_error()
+
+    plan = B.tl_plan_create(pool, 1, [0, 3], [0, 2], np.array([10, 11], np.uint64), B.TL_PLAN_SELF_BLOCK)
+    B.tl_pool_release(pool, 11)
+    B.tl_pool_put(pool, 10, FAKE_K, FAKE_V, 64, -1, stream=0)
+    B.tl_pool_adopt(pool, [12], [2], [5])
+    assert refused(plan)
+    B.tl_plan_destroy(plan)
+    plan = B.tl_plan_create(pool, 1, [0, 3], [0, 2], np.array([10, 11], np.uint64), B.TL_PLAN_SELF_BLOCK)
+    assert B.tl_pool_evict_lru(pool) == 11
+    assert refused(plan)
+    # the plan outlives its pool for reading back and destruction
+    B.tl_pool_destroy(pool)
+    assert B.tl_plan_get_info(plan).n_tokens == 3 and len(B.tl_plan_hot_slots(plan, 4)[0]) == 2
+    B.tl_plan_destroy(plan)
+
+
 def _check_plan_covers(b, plan, flags, fused_req=()):
     info = B.tl_plan_get_info(plan)
     fused_tok = set(t for r in fused_req for t in range(b.req_row_ptr[r], b.req_row_ptr[r + 1]))
@@ -176,9 +261,7 @@ def test_fused_rows_leave_the_three_step_path():
     info = _check_plan_covers(b, plan, flags, fused_req=(0, 2))
     assert info.n_fused_tiles == 4 + 2
     B.tl_plan_destroy(plan)
-    B.tl_set_option("compute_units", 64)
-    plan = B.tl_plan_create(plan_pool[0], b.q_heads, b.req_row_ptr, b.req_seg_ptr, b.seg_ids, flags)
-    B.tl_set_option("compute_units", 256)
+    plan = B.tl_plan_create(plan_pool[0], b.q_heads, b.req_row_ptr, b.req_seg_ptr, b.seg_ids, flags, 0, 64)
     info = _check_plan_covers(b, plan, flags, fused_req=(0, 2))
     assert info.n_fused_tiles == 4 + 2 and info.n_fused_tokens == 328       # row tiles of 64 tokens
     assert info.n_causal_tiles == 2 + 1                                      # requests 1 and 3 only
@@ -207,9 +290,8 @@ def test_small_batch_of_row_tiles_is_cut_along_its_kv():
         ex = B.tl_plan_export(plan)
         assert np.diff(ex["item_slot_ptr"]).min() >= 8                                 # >= 2048 tokens per chunk
         B.tl_plan_destroy(plan)
-    B.tl_set_option("compute_units", 0)                                                  # switched off: one item
-    plan = B.tl_plan_create(plan_pool[0], b.q_heads, b.req_row_ptr, b.req_seg_ptr, b.seg_ids, B.TL_PLAN_SELF_BLOCK)
-    B.tl_set_option("compute_units", 256)
+    plan = B.tl_plan_create(plan_pool[0], b.q_heads, b.req_row_ptr, b.req_seg_ptr, b.seg_ids, B.TL_PLAN_SELF_BLOCK,
+                            0, 0)                                                        # switched off: one item
     assert B.tl_plan_get_info(plan).n_items == 1
     B.tl_plan_destroy(plan)
     B.tl_pool_destroy(plan_pool[0])
@@ -286,11 +368,8 @@ def test_tile_pairs_count_each_distinct_slot_of_a_work_item_once():
                        for r in range(3))
         assert distinct < per_entry
         for dedupe in (1, 0):
-            B.tl_set_option("dedupe_tiles", dedupe)
-            B.tl_set_option("compute_units", 0)
-            plan = B.tl_plan_create(pool, b.q_heads, b.req_row_ptr, b.req_seg_ptr, b.seg_ids, flags)
-            B.tl_set_option("compute_units", 256)
-            B.tl_set_option("dedupe_tiles", 1)
+            plan = B.tl_plan_create(pool, b.q_heads, b.req_row_ptr, b.req_seg_ptr, b.seg_ids,
+                                    flags | (0 if dedupe else B.TL_PLAN_WALK_REPEATS), 0, 0)
             info = B.tl_plan_get_info(plan)
             assert info.prefix_pairs == per_entry
             assert info.tile_pairs == (distinct if dedupe else per_entry)
@@ -298,7 +377,7 @@ def test_tile_pairs_count_each_distinct_slot_of_a_work_item_once():
             B.tl_plan_destroy(plan)
         B.tl_pool_destroy(pool)
     with pytest.raises(B.TokenLakeError):
-        B.tl_set_option("dedupe_tiles", 2)
+        B.tl_plan_create(pool, b.q_heads, b.req_row_ptr, b.req_seg_ptr, b.seg_ids, flags, 0, 5000)   # compute_units above 4096
 
 
 def test_plan_errors():
@@ -442,10 +521,8 @@ def test_random_batches_every_pair_once_under_every_plan_mode():
         for flags in (0, B.TL_PLAN_SELF_BLOCK, B.TL_PLAN_SELF_BLOCK | B.TL_PLAN_NO_SHARING,
                       B.TL_PLAN_SELF_BLOCK | B.TL_PLAN_FUSE_ROWS):
             for cus in (0, 8, 256):
-                B.tl_set_option("compute_units", cus)
                 plan = B.tl_plan_create(plan_pool[0], b.q_heads, b.req_row_ptr, b.req_seg_ptr, b.seg_ids, flags,
-                                        int(rng.choice([0, 1, 3])))
-                B.tl_set_option("compute_units", 256)
+                                        int(rng.choice([0, 1, 3])), cus)
                 fused = ()
                 if flags & B.TL_PLAN_FUSE_ROWS:
                     # the rule as the header states it: more than a token's worth of rows; no segment in

@@ -42,6 +42,33 @@ def _check_all_requests(run, rows_per_req=None, seed=0, reqs=None):
     return worst
 
 
+def _check_every_request(run, rows_per_req, seed, full_heads=(), kv_per_req=2):
+    """Every request of a full-size batch: its first, last and tile-boundary rows plus
+    rows_per_req random ones (None: all rows), O and LSE, against the oracle on inputs copied back
+    from the device tensors that the generator wrote.  Requests in `full_heads` are checked on all
+    kv heads, the others on kv_per_req kv heads that rotate with the request index, so that every
+    head is covered many times over the batch."""
+    b = run.batch
+    rng = np.random.default_rng(seed)
+    worst = {"err_o": 0.0, "err_lse": 0.0, "rel_o": 0.0}
+    n_checked = 0
+    for r in range(b.n_req):
+        lq = int(b.req_row_ptr[r + 1] - b.req_row_ptr[r])
+        if lq == 0:
+            continue
+        rows = None if rows_per_req is None else H.sample_rows(lq, rows_per_req, rng)
+        kv_sel = None if r in full_heads else sorted({(r * 3 + 5 * i) % b.kv_heads for i in range(kv_per_req)})
+        res = H.compare_rows_device(run, r, rows, kv_sel)
+        n_checked += 1
+        for k in worst:
+            worst[k] = max(worst[k], res[k])
+        assert res["err_o"] <= H.TOL_O, "request %d: O max-abs error %.3e" % (r, res["err_o"])
+        assert res["err_lse"] <= H.TOL_LSE, "request %d: LSE max-abs error %.3e" % (r, res["err_lse"])
+        assert res["rel_o"] <= REL_O, "request %d: O error %.3e relative to max|O*| %.3e" % (r, res["err_o"], res["ref_o"])
+    _say("%s: %d requests, worst err_o=%.2e err_lse=%.2e rel_o=%.2e" % (b.name, n_checked, worst["err_o"], worst["err_lse"], worst["rel_o"]))
+    return worst
+
+
 # ---- integer / byte work -------------------------------------------------------------------
 def test_generator_bits_identical_on_device():
     _say("generator cpu vs gpu")
@@ -186,7 +213,7 @@ def test_peaked_and_offset_variants_are_discriminating():
     _say("peaked / offset variants")
     for maker, kw in [(wl.prefill, dict(n_req=3, new_tokens=100, lo=300, hi=900, seg_len=128, n_slots=64, n_shared=2)),
                       (wl.decode, dict(n_req=6, median=700, cap=3000, seg_len=128))]:
-        b = maker(seed=21, k_gain=4.0, v_offset_mod=3, **kw)
+        b = maker(seed=21, k_gain=4.0, v_offset_mod=7, **kw)
         run = H.run_gpu(b)
         w = _check_all_requests(run)
         # on these inputs |O| is O(1): an all-zero or segment-dropping result cannot pass 2e-2
@@ -203,7 +230,7 @@ def test_scores_far_from_the_first_blocks_range():
     _say("late / early score peaks")
     for boost in [(2, 1 << 30, 32.0), (0, 1, 32.0), (3, 4, 32.0)]:
         b = wl.prefill(seed=23, n_req=2, new_tokens=96, lo=700, hi=1100, seg_len=128, n_slots=32, n_shared=1,
-                       k_boost=boost, v_offset_mod=3)
+                       k_boost=boost, v_offset_mod=7)
         run = H.run_gpu(b)
         assert run.info.n_tiles > 0
         w = _check_all_requests(run)
@@ -375,9 +402,7 @@ def test_guard_rows_around_every_output_stay_untouched():
     Hq, D, T, guard = b.q_heads, b.head_dim, b.n_tokens, 8
     canary = -7.25
     for flags in (B.TL_PLAN_SELF_BLOCK, B.TL_PLAN_SELF_BLOCK | B.TL_PLAN_FUSE_ROWS):
-        B.tl_set_option("compute_units", 0)
-        plan = B.tl_plan_create(pool, Hq, b.req_row_ptr, b.req_seg_ptr, b.seg_ids, flags, 1)
-        B.tl_set_option("compute_units", 256)
+        plan = B.tl_plan_create(pool, Hq, b.req_row_ptr, b.req_seg_ptr, b.seg_ids, flags, 1, 0)
         R = B.tl_plan_get_info(plan).n_partial_rows
         big = {name: torch.full((rows + 2 * guard,) + tail, canary, dtype=dt, device="cuda")
                for name, rows, tail, dt in (("outp", R, (Hq, D), torch.float32), ("lsep", R, (Hq,), torch.float32),
@@ -403,40 +428,70 @@ def test_deterministic_bits_run_to_run():
     r1.close(); r2.close()
 
 
-# ---- the named configurations at full size, sampled rows ------------------------------------------
-def test_full_prefill_config_sampled():
-    _say("full prefill (cfg 2)")
-    b = wl.prefill()
+# ---- the named configurations at full size: every request -------------------------------------------
+def test_device_copies_of_oracle_inputs_equal_the_host_generator():
+    """The full-size checks below copy the oracle's inputs back from the device tensors that the
+    seeded generator filled (regenerating 26 GB on the host would take minutes).  Here: the two
+    sources agree bit for bit on a case small enough for both."""
+    _say("oracle inputs: device copy vs host generator")
+    b = wl.prefill(seed=18, n_req=3, new_tokens=40, lo=300, hi=900, seg_len=128, n_slots=64, n_shared=2)
     run = H.run_gpu(b)
-    L = b.prefix_tokens()
-    reqs = sorted({int(np.argmin(L)), int(np.argmax(L)), 0})
-    _check_all_requests(run, rows_per_req=6, seed=1, reqs=reqs)
+    for r in range(b.n_req):
+        host = H.host_request_inputs(b, r)
+        dev = H.device_request_inputs(run, r)
+        for i in (0, 3, 4, 5, 6):                 # q, slot positions, fills, new K, new V
+            assert np.array_equal(host[i], dev[i])
+        fills = host[4]
+        # the pool: every valid token (beyond a slot's fill the device pool holds its poison)
+        for x, y in zip(orc.gather_segments(host[1], host[2], host[3], fills), orc.gather_segments(dev[1], dev[2], dev[3], fills)):
+            assert np.array_equal(x, y)
+        sub = H.device_request_inputs(run, r, kv_sel=[3, 6])
+        gk_h, gv_h = orc.gather_segments(host[1], host[2], host[3], fills)
+        gk_d, gv_d = orc.gather_segments(sub[1], sub[2], sub[3], sub[4])
+        assert np.array_equal(gk_h[:, [3, 6]], gk_d) and np.array_equal(gv_h[:, [3, 6]], gv_d)
+        assert sub[7] == [12, 13, 14, 15, 24, 25, 26, 27] and np.array_equal(host[0][:, sub[7]], sub[0])
     run.close()
 
 
-def test_full_decode_config_sampled():
+def test_full_prefill_config_every_request():
+    _say("full prefill (cfg 2)")
+    b = wl.prefill()
+    L = b.prefix_tokens()
+    full = {int(np.argmin(L)), int(np.argmax(L)), 0}
+    for fuse in (False, True):
+        run = H.run_gpu(b, fuse=fuse)
+        assert (run.info.n_fused_tokens == b.n_tokens) == fuse
+        _check_every_request(run, rows_per_req=6, seed=1, full_heads=full if not fuse else {5})
+        run.close()
+
+
+def test_full_decode_config_every_request():
+    """All 256 tokens of the decode batch: 16 of the 64 q heads each (two kv heads, rotating), all
+    64 heads for the shortest, the longest, the median and two more requests."""
     _say("full decode (cfg 3)")
     b = wl.decode()
     run = H.run_gpu(b, poison=False)
-    L = b.prefix_tokens()
-    order = np.argsort(L)
-    reqs = sorted({int(order[0]), int(order[-1]), int(order[len(order) // 2]), 7, 100})
-    _check_all_requests(run, reqs=reqs)
+    order = np.argsort(b.prefix_tokens())
+    full = {int(order[0]), int(order[-1]), int(order[len(order) // 2]), 7, 100}
+    _check_every_request(run, rows_per_req=None, seed=2, full_heads=full)
     run.close()
 
 
-def test_full_longctx_config_sampled():
-    _say("full long context (cfg 4)")
-    b = wl.longctx()
-    run = H.run_gpu(b)
-    _check_all_requests(run, rows_per_req=4, seed=3, reqs=[2])
-    run.close()
+@pytest.mark.parametrize("seed", [3, 33])
+def test_full_longctx_config_every_request(seed):
+    _say("full long context (cfg 4) seed %d" % seed)
+    b = wl.longctx(seed=seed)
+    for fuse in (False, True):
+        run = H.run_gpu(b, fuse=fuse)
+        assert (run.info.n_fused_tokens == b.n_tokens) == fuse
+        _check_every_request(run, rows_per_req=3, seed=3, full_heads={2} if (seed == 3 and not fuse) else ())
+        run.close()
 
 
 def test_repeated_segments_walked_once_with_their_multiplicity():
     """Lists that name a segment several times (Zipf draws with replacement): by default a row-tile
     work item walks each distinct slot once and weighs its keys by the multiplicity.  Every row
-    against the oracle, which concatenates the list as it stands; with the option off the kernel does
+    against the oracle, which concatenates the list as it stands; with TL_PLAN_WALK_REPEATS the kernel does
     the same as the oracle, and the two settings agree; three-step and one-pass plans; ragged fills
     (the repeated slots' cut-short tiles carry the weight too)."""
     _say("repeated segments")
@@ -449,11 +504,8 @@ def test_repeated_segments_walked_once_with_their_multiplicity():
     for fuse in (False, True):
         runs = {}
         for dedupe in (1, 0):
-            B.tl_set_option("dedupe_tiles", dedupe)
-            try:
-                runs[dedupe] = H.run_gpu(b, fuse=fuse)
-            finally:
-                B.tl_set_option("dedupe_tiles", 1)
+            flags = B.TL_PLAN_SELF_BLOCK | (0 if dedupe else B.TL_PLAN_WALK_REPEATS)
+            runs[dedupe] = H.run_gpu(b, flags=flags, fuse=fuse)
             _check_all_requests(runs[dedupe])
         i1, i0 = runs[1].info, runs[0].info
         # one-pass rows walk a request's whole list at once (12 distinct segments of 60 entries); shared runs are
@@ -463,13 +515,39 @@ def test_repeated_segments_walked_once_with_their_multiplicity():
         runs[0].close(); runs[1].close()
 
 
-@pytest.mark.parametrize("turn", [0, 7])
-def test_full_multiturn_config_sampled(turn):
+@pytest.mark.parametrize("turn", range(8))
+def test_full_multiturn_config_every_session(turn):
+    """Every session of every turn, three-step plan (the shared prompt as one work item read once
+    against all 16384 query tokens, private histories, causal block, merge) and one-pass plan."""
     _say("full multi-turn (cfg 5) turn %d" % turn)
     b = wl.multiturn(turn=turn)
-    run = H.run_gpu(b)
-    _check_all_requests(run, rows_per_req=5, seed=4, reqs=[0, 37, 63])
-    run.close()
+    for fuse in (False, True):
+        if fuse and turn not in (0, 3, 7):
+            continue
+        run = H.run_gpu(b, fuse=fuse)
+        assert (run.info.n_fused_tokens == b.n_tokens) == fuse
+        if not fuse:
+            assert run.info.n_items == (65 if turn else 1)
+        _check_every_request(run, rows_per_req=2, seed=4 + turn, full_heads={0, 37, 63} if (turn in (0, 7) and not fuse) else ())
+        run.close()
+
+
+def test_tile_list_longer_than_its_lds_ring_every_row():
+    """A work item with more than 512 full tiles: the row-tile kernel keeps a ring of 512 tile
+    entries in LDS and refills half of it every 256 tiles.  Every row against the oracle, as
+    pool work item (three steps) and as one-pass rows, with a ragged last tile."""
+    _say("tile-list ring wrap")
+    for fuse, n_new, n_shared in ((False, 70, 3), (True, 130, 3), (True, 70, 0)):
+        b = wl.prefill(seed=91, n_req=2, new_tokens=n_new, lo=600 * 64 - 40, hi=600 * 64 - 1, seg_len=64, n_slots=1400,
+                       n_shared=n_shared, hq=8, hkv=2)
+        run = H.run_gpu(b, fuse=fuse, compute_units=0)
+        if fuse:
+            assert run.info.n_fused_tokens == b.n_tokens
+        else:
+            ex = B.tl_plan_export(run.plan)
+            assert run.info.n_tiles > 0 and np.diff(ex["item_slot_ptr"]).max() >= 590
+        _check_every_request(run, rows_per_req=None, seed=5, full_heads={0, 1})
+        run.close()
 
 
 # ---- one-pass (fused) rows ----------------------------------------------------------------------
@@ -521,24 +599,12 @@ def test_only_short_segments_no_full_tile_anywhere():
 
 def test_fused_rows_peaked_and_far_scores():
     _say("fused rows, peaked / far scores")
-    for kw in [dict(k_gain=4.0, v_offset_mod=3), dict(k_boost=(2, 1 << 30, 32.0), v_offset_mod=3),
-               dict(k_boost=(0, 1, 32.0), v_offset_mod=3)]:
+    for kw in [dict(k_gain=4.0, v_offset_mod=7), dict(k_boost=(2, 1 << 30, 32.0), v_offset_mod=7),
+               dict(k_boost=(0, 1, 32.0), v_offset_mod=7)]:
         b = wl.prefill(seed=23, n_req=2, new_tokens=160, lo=700, hi=1100, seg_len=128, n_slots=32, n_shared=1, **kw)
         run = H.run_gpu(b, fuse=True)
         assert run.info.n_fused_tokens == 320 and run.info.n_tiles == 0
         _check_all_requests(run)
-        run.close()
-
-
-def test_fused_and_three_step_paths_agree_on_full_configs():
-    _say("fused rows, full prefill / multi-turn / long context")
-    for b, reqs, rows in [(wl.prefill(), None, 6), (wl.multiturn(turn=7), [0, 37, 63], 5), (wl.longctx(), [2], 4)]:
-        run = H.run_gpu(b, fuse=True)
-        assert run.info.n_fused_tokens == b.n_tokens and run.info.n_merge_entries == 0
-        if reqs is None:
-            L = b.prefix_tokens()
-            reqs = sorted({int(np.argmin(L)), int(np.argmax(L)), 0})
-        _check_all_requests(run, rows_per_req=rows, seed=1, reqs=reqs)
         run.close()
 
 
@@ -788,9 +854,7 @@ def test_multi_turn_sessions_as_a_closed_loop_on_the_device():
         kng, knc = gen(wl.STREAM_KNEW, T, hkv)
         vng, vnc = gen(wl.STREAM_VNEW, T, hkv)
         cursor[0] += T
-        B.tl_set_option("compute_units", 0)
-        plan = B.tl_plan_create(pool, hq, row_ptr, seg_ptr, ids, B.TL_PLAN_SELF_BLOCK | B.TL_PLAN_FUSE_ROWS)
-        B.tl_set_option("compute_units", 256)
+        plan = B.tl_plan_create(pool, hq, row_ptr, seg_ptr, ids, B.TL_PLAN_SELF_BLOCK | B.TL_PLAN_FUSE_ROWS, 0, 0)
         info = B.tl_plan_get_info(plan)
         R = max(info.n_partial_rows, 1)
         outp = torch.full((R, hq, d), float("nan"), dtype=torch.float32, device=dev)
@@ -830,6 +894,140 @@ def test_multi_turn_sessions_as_a_closed_loop_on_the_device():
             totals[s_] += lens[s_]
         assert got.tolist() == table.lookup([i for x in new_ids for i in x]).tolist()
     assert all(len(ch) >= 3 for ch in chains)
+    B.tl_pool_destroy(pool)
+
+
+def test_evicted_slots_are_reused_and_attended_over():
+    """Pool life cycle on the device (paper Section 4.3: eviction by last access time): a full pool,
+    releases, a plan that refreshes two segments, LRU evictions (same victims as the oracle), then
+    tl_pool_append and tl_pool_put into the freed slots, the stale plan refused, and attention over
+    lists that mix old segments with the ones now living in reused slots -- row tiles, one-pass rows
+    and split-K units (which read the live fill table) -- against the oracle's own table and pool."""
+    _say("evict, reuse, attend")
+    seed, hq, hkv, C, n_slots, d = 97, 8, 2, 64, 12, 128
+    dev = "cuda"
+    pk = torch.full((n_slots, C, hkv, d), float("nan"), dtype=torch.bfloat16, device=dev)
+    pv = torch.full((n_slots, C, hkv, d), float("nan"), dtype=torch.bfloat16, device=dev)
+    pool = B.tl_pool_create(n_slots, C, hkv, d, pk, pv)
+    opk = np.zeros((n_slots, C, hkv, d), np.uint16)
+    opv = np.zeros_like(opk)
+    table = orc.SlotTable(n_slots, C)
+    scale = 1.0 / math.sqrt(d)
+    cursor = [0]
+
+    def gen(stream, n, heads):
+        per = heads * d
+        g = wl.normal_bf16_range(seed, stream, cursor[0] * hq * d, n * per, dev).view(n, heads, d)
+        c = wl.bits_u16(wl.normal_bf16_range(seed, stream, cursor[0] * hq * d, n * per, "cpu").view(n, heads, d))
+        return g, c
+
+    def put(sid, fill):
+        kg, kc = gen(wl.STREAM_POOL_K, fill, hkv)
+        vg, vc = gen(wl.STREAM_POOL_V, fill, hkv)
+        cursor[0] += fill
+        slot = B.tl_pool_put(pool, sid, kg, vg, fill)
+        assert slot == table.put(sid, fill)
+        opk[slot, :fill], opv[slot, :fill] = kc, vc
+        opk[slot, fill:], opv[slot, fill:] = 0, 0
+        return slot
+
+    fills = [C, C, 40, C, 17, C, C, 64, 33, C, C, 5]
+    for i, f in enumerate(fills):
+        assert put(1 + i, f) == i
+    with pytest.raises(B.TokenLakeError) as e:
+        B.tl_pool_put(pool, 500, pk[0], pv[0], C)
+    assert e.value.status == B.TL_EFULL
+
+    def attend(lists, lens, fuse):
+        row_ptr = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+        seg_ptr = np.concatenate([[0], np.cumsum([len(l) for l in lists])]).astype(np.int32)
+        ids = np.array([i for l in lists for i in l], np.uint64)
+        T = int(row_ptr[-1])
+        qg, qc = gen(wl.STREAM_Q, T, hq)
+        kng, knc = gen(wl.STREAM_KNEW, T, hkv)
+        vng, vnc = gen(wl.STREAM_VNEW, T, hkv)
+        cursor[0] += T
+        flags = B.TL_PLAN_SELF_BLOCK | (B.TL_PLAN_FUSE_ROWS if fuse else 0)
+        plan = B.tl_plan_create(pool, hq, row_ptr, seg_ptr, ids, flags, 1, 0)
+        table.touch(ids.tolist())
+        info = B.tl_plan_get_info(plan)
+        R = max(info.n_partial_rows, 1)
+        outp = torch.full((R, hq, d), float("nan"), dtype=torch.float32, device=dev)
+        lsep = torch.full((R, hq), float("nan"), dtype=torch.float32, device=dev)
+        out = torch.full((T, hq, d), float("nan"), dtype=torch.float32, device=dev)
+        lse = torch.full((T, hq), float("nan"), dtype=torch.float32, device=dev)
+        B.tl_segment_attn(pool, plan, qg, scale, outp, lsep)
+        B.tl_causal_block(plan, qg, kng, vng, scale, outp, lsep)
+        B.tl_merge(plan, outp, lsep, out, False, lse)
+        B.tl_fused_attn(pool, plan, qg, kng, vng, scale, out, False, lse)
+        torch.cuda.synchronize()
+        for r, l in enumerate(lists):
+            t0, t1 = int(row_ptr[r]), int(row_ptr[r + 1])
+            sl = table.lookup(l)
+            assert (sl >= 0).all()
+            gk_, gv_ = orc.gather_segments(opk, opv, sl, table.fill(sl))
+            k_all = np.concatenate([gk_, knc[t0:t1]], axis=0)
+            v_all = np.concatenate([gv_, vnc[t0:t1]], axis=0)
+            want_o, want_l = orc.partial_attention(qc[t0:t1], k_all, v_all, scale, n_visible=gk_.shape[0] + np.arange(t1 - t0) + 1)
+            err_o = np.abs(out[t0:t1].double().cpu().numpy() - want_o).max()
+            err_l = np.abs(lse[t0:t1].double().cpu().numpy() - want_l).max()
+            assert err_o <= H.TOL_O and err_l <= H.TOL_LSE, (fuse, r, err_o, err_l)
+        return plan, info, (qg, outp, lsep)
+
+    old_plan, info, (qg, outp, lsep) = attend([[1, 2, 3, 4], [1, 2, 9, 10, 11, 12], [5, 6, 7, 8]], [70, 1, 150], fuse=False)
+    assert info.n_units > 0 and info.n_tiles > 0
+    # releases; a plan that names 5 and 6 makes them the most recently used of the idle segments
+    for sid in (4, 5, 6, 7, 8, 9):
+        B.tl_pool_release(pool, sid)
+        table.release(sid)
+    p2 = B.tl_plan_create(pool, hq, [0, 1], [0, 2], np.array([5, 6], np.uint64), 0)
+    B.tl_plan_destroy(p2)
+    table.touch([5, 6])
+    victims = [B.tl_pool_evict_lru(pool) for _ in range(4)]
+    assert victims == [table.evict_lru() for _ in range(4)] and set(victims).isdisjoint({5, 6})
+    assert B.tl_pool_used(pool) == 8 == table.n_used()
+    # the plan made before the evictions is refused
+    with pytest.raises(B.TokenLakeError) as e:
+        B.tl_segment_attn(pool, old_plan, qg, scale, outp, lsep)
+    assert e.value.status == B.TL_EINVAL
+    B.tl_plan_destroy(old_plan)
+    # a chain of 2 C + 10 rows takes three of the freed slots, a put the fourth
+    n_rows = 2 * C + 10
+    kg, kc = gen(wl.STREAM_POOL_K, n_rows, hkv)
+    vg, vc = gen(wl.STREAM_POOL_V, n_rows, hkv)
+    cursor[0] += n_rows
+    new_slots = B.tl_pool_append(pool, None, [100, 101, 102], kg, vg, n_rows)
+    orc.append_rows(opk, opv, table, None, [100, 101, 102], kc, vc)
+    assert new_slots.tolist() == table.lookup([100, 101, 102]).tolist()
+    freed = sorted(i - 1 for i in victims)                     # segment id i lived in slot i - 1
+    assert new_slots.tolist() == freed[:3]
+    assert put(200, 23) == freed[3]
+    # grow the chain's tail (10 of 64 tokens so far) past its end
+    kg, kc = gen(wl.STREAM_POOL_K, C, hkv)
+    vg, vc = gen(wl.STREAM_POOL_V, C, hkv)
+    cursor[0] += C
+    with pytest.raises(B.TokenLakeError) as e:
+        B.tl_pool_append(pool, 102, [300], kg, vg, C)         # the pool is full again
+    assert e.value.status == B.TL_EFULL
+    B.tl_pool_append(pool, 102, [], kg, vg, 30)
+    orc.append_rows(opk, opv, table, 102, [], kc[:30], vc[:30])
+    every = [1, 2, 3, 5, 6, 10, 11, 12, 100, 101, 102, 200]
+    slots = table.lookup(every)
+    assert np.array_equal(B.tl_pool_lookup(pool, every + victims), table.lookup(every + victims))
+    assert np.array_equal(B.tl_pool_fills(pool, np.arange(n_slots)), table.fill(np.arange(n_slots)))
+    gk = torch.empty((len(slots), C, hkv, d), dtype=torch.bfloat16, device=dev)
+    gv = torch.empty_like(gk)
+    B.tl_pool_gather(pool, slots, gk, gv)
+    torch.cuda.synchronize()
+    gkb, gvb = wl.bits_u16(gk), wl.bits_u16(gv)
+    for i, (s_, f) in enumerate(zip(slots, table.fill(slots))):
+        assert np.array_equal(gkb[i, :f], opk[s_, :f]) and np.array_equal(gvb[i, :f], opv[s_, :f]), "slot %d" % s_
+        assert not gkb[i, f:].any() and not gvb[i, f:].any()      # tails of put / appended slots are cleared
+    for fuse in (False, True):
+        plan, info, _ = attend([[1, 2, 100, 101, 102], [5, 6, 200, 100], [200, 3, 101, 102, 12], [1, 2, 10]],
+                               [70, 1, 150, 3], fuse=fuse)
+        assert info.n_units > 0 and (info.n_fused_tiles > 0) == fuse
+        B.tl_plan_destroy(plan)
     B.tl_pool_destroy(pool)
 
 
@@ -947,14 +1145,3 @@ def test_step_replays_from_a_hip_graph(fuse):
         assert torch.equal(run.out, want_o) and torch.equal(run.lse, want_l), "replay %d differs" % rep
     del g
     run.close()
-
-
-def test_mfma_probe_runs_and_validates():
-    _say("mfma probe")
-    scratch = torch.zeros(16, dtype=torch.float32, device="cuda")
-    for rnd in (False, True):
-        assert B.tl_probe_mfma(rnd, 10, scratch) == 1024 * 8 * 10 * 32 * 32768.0
-    torch.cuda.synchronize()
-    assert torch.all(scratch == 0)
-    with pytest.raises(B.TokenLakeError):
-        B.tl_probe_mfma(True, 0, scratch)

@@ -409,3 +409,107 @@ def test_segment_loads_hand_case_and_invariants():
     assert set(i for i, _ in got) == set(x for ids in lists for x in ids)
     for sid, l in got:                                                                    # brute force per id
         assert l == sum(ids.count(sid) * n for ids, n in zip(lists, ntok))
+
+
+def test_release_and_lru_eviction_hand_case_and_independent_model():
+    """Pin for SlotTable.release / touch / evict_lru (paper Section 4.3: global LRU on the
+    recorded last access time).  First a case worked by hand, then random operation sequences
+    against a model of a different shape (a plain list of records scanned with min())."""
+    t = orc.SlotTable(4, 8)
+    assert [t.put(10, 8), t.put(11, 8), t.put(12, 3)] == [0, 1, 2]        # access times 1, 2, 3
+    t.touch([10])                                                          # 10 accessed at 4
+    with pytest.raises(LookupError):
+        t.evict_lru()                                                      # everybody is held
+    t.release(11)
+    t.release(12)
+    assert t.evict_lru() == 11                                             # time 2 is older than time 3
+    assert t.lookup([10, 11, 12]).tolist() == [0, -1, 2] and t.fill([1]).tolist() == [0]
+    assert t.put(13, 5) == 1                                               # the freed slot is the lowest free one
+    t.release(10)
+    assert t.evict_lru() == 12                                             # 12 (time 3) before 10 (time 4)
+    assert t.evict_lru() == 10
+    with pytest.raises(LookupError):
+        t.evict_lru()                                                      # 13 is still held
+    assert t.n_used() == 1
+    # a second put of a resident id adds a holder: one release is not enough
+    assert t.put(13, 5) == 1 and t.holders(13) == 2
+    t.release(13)
+    with pytest.raises(LookupError):
+        t.evict_lru()
+    t.release(13)
+    with pytest.raises(ValueError):
+        t.release(13)                                                      # nobody left to release
+    with pytest.raises(KeyError):
+        t.release(99)
+    # one touch gives equal times: the lower slot goes first; a later touch of one id saves it
+    a, b = t.put(20, 8), t.put(21, 8)                                      # slots 0 and 2
+    assert (a, b) == (0, 2)
+    for i in (20, 21):
+        t.release(i)
+    t.touch([21, 20, 13])
+    assert t.evict_lru() == 20 and t.evict_lru() == 13 and t.evict_lru() == 21
+    # a tail that somebody else also holds does not grow; neither does one nobody holds
+    t = orc.SlotTable(4, 8)
+    t.put(1, 3)
+    t.put(1, 3)
+    with pytest.raises(ValueError):
+        t.append(1, [], 2)
+    t.release(1)
+    assert t.append(1, [], 2) == [(0, 3, 2, 0)]
+    t.release(1)
+    with pytest.raises(ValueError):
+        t.append(1, [], 1)
+
+    # random sequences against an independent model
+    rng = np.random.default_rng(17)
+    for trial in range(20):
+        n_slots = int(rng.integers(2, 9))
+        t = orc.SlotTable(n_slots, 8)
+        model = []                      # records [id, slot, holders, time]
+        clock = 0
+        for step in range(200):
+            op = rng.choice(["put", "touch", "release", "evict"], p=[0.35, 0.2, 0.3, 0.15])
+            ids_in = [m[0] for m in model]
+            if op == "put":
+                sid = int(rng.integers(0, 12))
+                rec = next((m for m in model if m[0] == sid), None)
+                if rec is None and len(model) == n_slots:
+                    with pytest.raises(MemoryError):
+                        t.put(sid, 8)
+                    continue
+                clock += 1
+                if rec is None:
+                    slot = min(set(range(n_slots)) - {m[1] for m in model})
+                    model.append([sid, slot, 1, clock])
+                else:
+                    slot = rec[1]
+                    rec[2] += 1
+                    rec[3] = clock
+                assert t.put(sid, 8) == slot
+            elif op == "touch" and ids_in:
+                pick = rng.choice(ids_in, size=int(rng.integers(1, len(ids_in) + 1)), replace=False).tolist()
+                clock += 1
+                for m in model:
+                    if m[0] in pick:
+                        m[3] = clock
+                t.touch(pick)
+            elif op == "release" and ids_in:
+                sid = int(rng.choice(ids_in))
+                rec = next(m for m in model if m[0] == sid)
+                if rec[2] == 0:
+                    with pytest.raises(ValueError):
+                        t.release(sid)
+                else:
+                    rec[2] -= 1
+                    t.release(sid)
+            elif op == "evict":
+                idle = [m for m in model if m[2] == 0]
+                if not idle:
+                    with pytest.raises(LookupError):
+                        t.evict_lru()
+                else:
+                    victim = min(idle, key=lambda m: (m[3], m[1]))
+                    assert t.evict_lru() == victim[0]
+                    model.remove(victim)
+            assert t.n_used() == len(model)
+            assert t.lookup(list(range(12))).tolist() == [next((m[1] for m in model if m[0] == i), -1) for i in range(12)]
