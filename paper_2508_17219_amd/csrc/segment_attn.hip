@@ -33,11 +33,19 @@
 // lists hold each distinct slot once with log2 of its multiplicity, which is added to the exponent
 // of the tile's probabilities (m equal keys weigh m exp(s) in numerator and denominator alike).
 //
-// Two row sums are kept.  The probabilities enter the second product rounded to bf16, so the
-// output is normalised by the sum of the ROUNDED values (one v_dot2c_f32_bf16 per packed pair):
-// O is then a convex combination of the V rows whatever the rounding did to the weights, and a
-// row dominated by one key returns that key's V exactly.  The normalizer that leaves the kernel
-// (LSE) comes from the sum of the unrounded fp32 values.
+// Normalisation.  The probabilities enter the second product rounded to bf16, so O should be
+// divided by the sum of the ROUNDED values -- it is then a convex combination of V rows whatever
+// the rounding did to the weights -- while the normalizer that leaves the kernel (LSE) needs the
+// sum of the unrounded fp32 values.  The kernel keeps the fp32 sum l and, beside it, a
+// correction d ~= sum(rounded) - sum(unrounded); O is divided by l + d, LSE = m + ln l.
+//  * careful path: d is exact (v_dot2c_f32_bf16 sums each packed pair as the matrix unit sees it);
+//  * fast path: a second exact sum would cost 7 % of the kernel's time (the dot instructions share
+//    the matrix pipeline), so each lane tracks the largest probability it has formed (one v_max3
+//    per pair, 2 %) and d takes that value's rounding error: with a fixed exponent reference the
+//    largest probability is a rounded number like any other (with a running maximum it would be
+//    exactly 1), and its rounding is what the error of a peaked row consists of.  What remains is
+//    the error of the other terms, sum_j w_j e_j (v_j - O) with |e_j| <= 2^-8: the same bound as a
+//    kernel that keeps a running maximum.
 #include <type_traits>
 
 #include "attn_common.h"
@@ -161,7 +169,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
   f32x16 o[kRG][4];
   float m_ref[kRG];   // reference point of the exponent (raw score units), -inf before any key
   float l_run[kRG];   // this lane's share of sum exp(s - m_ref), unrounded (-> LSE)
-  float lr_run[kRG];  // the same sum over the values as rounded to bf16 for the second product (-> O)
+  float lr_run[kRG];  // correction: (sum of the values as rounded to bf16 for the second product) - (unrounded sum)
   auto reset_state = [&]() __attribute__((always_inline)) {
 #pragma unroll
     for (int rg = 0; rg < kRG; ++rg) {
@@ -304,15 +312,15 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
 #pragma unroll
     for (int r = 0; r < 16; ++r) lsum += s[r];
     l_run[rg] += lsum;
-    // ... and O is divided by the sum of what the matrix unit is given
-    float lr = lr_run[rg];
+    // ... and O is divided by the sum of what the matrix unit is given: lr = that sum, exactly
+    float lr = 0.f;
 #pragma unroll
     for (int sp = 0; sp < 2; ++sp) {
       const u32x4 w = __builtin_bit_cast(u32x4, pb[sp]);
 #pragma unroll
       for (int i = 0; i < 4; ++i) lr = add_bf16_pair(lr, w[i]);
     }
-    lr_run[rg] = lr;
+    lr_run[rg] += lr - lsum;
   };
   auto pv_block = [&](const uint16_t* vt, int hb, const bf16x8 (&pb)[kRG][2]) {
 #pragma unroll
@@ -412,6 +420,9 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
     dma_wait();
     __syncthreads();
 
+    float pm[kRG];                      // largest probability this lane has formed in this phase
+#pragma unroll
+    for (int rg = 0; rg < kRG; ++rg) pm[rg] = 0.f;
     f32x16 s0[kRG], s1[kRG];            // scores of block 0 / block 1 of a tile (then their probabilities)
     u32x4 p0[kRG][2], p1[kRG][2];       // packed probabilities (bf16 pairs)
     qk_block(lds_k, 0, s0);
@@ -514,11 +525,10 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
           u32x4 (&pp)[2] = step == 0 ? p0[rg] : p1[rg];
           if (r >= 1) l_run[rg] += s[r - 1];
           if (r >= 2 && (r & 1) == 0) set_pair(pp[(r - 2) >> 3], ((r - 2) & 7) >> 1, s[r - 2], s[r - 1]);
-          // the rounded sum trails the packing by one slice; the last pair of a block is added in
-          // slice 1 of the next block (the first one adds the zeros that p1 starts with, the drain
-          // below adds the last block's)
-          if (r >= 3 && (r & 1) == 1) lr_run[rg] = add_bf16_pair(lr_run[rg], pp[(r - 3) >> 3][((r - 3) & 7) >> 1]);
-          if (r == 1) lr_run[rg] = add_bf16_pair(lr_run[rg], (step == 0 ? p1[rg] : p0[rg])[1][3]);
+          // the lane's largest probability, two elements per v_max3, in the slices without a convert
+          if (r == 1) pm[rg] = fmaxf(pm[rg], s[0]);
+          if (r >= 3 && (r & 1) == 1) pm[rg] = __builtin_fmaxf(__builtin_fmaxf(pm[rg], s[r - 2]), s[r - 1]);
+          if (r == 15) pm[rg] = fmaxf(pm[rg], s[15]);
           if (r == 15) {
             l_run[rg] += s[15];
             set_pair(pp[1], 3, s[14], s[15]);
@@ -554,11 +564,18 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
       for (int rg = 0; rg < kRG; ++rg) {
         pl[rg][0] = __builtin_bit_cast(bf16x8, p1[rg][0]);
         pl[rg][1] = __builtin_bit_cast(bf16x8, p1[rg][1]);
-        lr_run[rg] = add_bf16_pair(lr_run[rg], p1[rg][1][3]);
       }
       pv_block(lds_v + ((n_full - 1) % kBufs) * kVTile, 1, pl);
     }
 
+    // what rounding did to the lane's largest probability goes into the correction of the row sum
+#pragma unroll
+    for (int rg = 0; rg < kRG; ++rg) {
+      typedef float f32x2_t __attribute__((ext_vector_type(2)));
+      typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+      const unsigned w = __builtin_bit_cast(unsigned, __builtin_convertvector(f32x2_t{pm[rg], 0.f}, bf16x2_t));
+      lr_run[rg] += __uint_as_float(w << 16) - pm[rg];
+    }
     // did the fixed reference hold?  (row sums are sums of positive terms: one huge term shows)
     bool bad = false;
 #pragma unroll
@@ -622,7 +639,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
 #pragma unroll
   for (int rg = 0; rg < kRG; ++rg) {
     const float l_tot = xor32_sum(l_run[rg]);
-    const float lr_tot = xor32_sum(lr_run[rg]);
+    const float lr_tot = l_tot + xor32_sum(lr_run[rg]);
     if (row_ok[rg]) {
       const float inv = lr_tot > 0.f ? 1.f / lr_tot : 0.f;
       const int head = g * G + head_j[rg];
