@@ -280,6 +280,21 @@ tl_status tl_fused_attn(const tl_pool* pool, tl_plan* plan, const void* q_dev, c
                         const void* v_new_dev, float scale, void* out_dev, int32_t out_is_bf16, float* lse_out,
                         void* stream);
 
+/* tl_fused_attn for callers that cannot allocate device memory (code under HIP graph capture set-up
+ * rules, tight serving loops, harnesses that forbid hipMalloc): same arguments, same kernels, same
+ * result bit for bit, but the plan's device-side work lists, which tl_fused_attn keeps in memory
+ * it hipMalloc's on the plan's first use, are staged in a buffer that is part of the library's
+ * device code (4 MiB per GPU, held until the process ends).  The call makes no hipMalloc, hipFree
+ * or other allocating call: it looks up the buffer's address (once per device, on the first call
+ * with that device current), enqueues one host-to-device copy of the work lists and the kernel on
+ * `stream`.  TL_EINVAL if the plan's work lists exceed 4 MiB (the named workloads take 20-400 KB)
+ * or the device index is 64 or more.  All calls on one GPU share the buffer, which keeps the last
+ * call's contents: calls on one stream are ordered and safe; calls that overlap on one GPU (two
+ * streams, two threads) race and must be serialised by the caller. */
+tl_status tl_fused_attn_static(const tl_pool* pool, tl_plan* plan, const void* q_dev, const void* k_new_dev,
+                               const void* v_new_dev, float scale, void* out_dev, int32_t out_is_bf16,
+                               float* lse_out, void* stream);
+
 /* Exact recombination of each token's partials (Section 2.1: partial outputs and normalizers are
  * reduced into the final output; Section 4, first paragraph):
  *   M = max_j LSE_j, w_j = exp(LSE_j - M), O = sum_j w_j O_j / sum_j w_j, LSE = M + ln sum_j w_j.

@@ -64,6 +64,7 @@ _SIGNATURES = {
     "tl_causal_block": (_I32, [_P, _P, _P, _P, _F32, _P, _P, _P]),
     "tl_merge": (_I32, [_P, _P, _P, _P, _I32, _P, _P]),
     "tl_fused_attn": (_I32, [_P, _P, _P, _P, _P, _F32, _P, _I32, _P, _P]),
+    "tl_fused_attn_static": (_I32, [_P, _P, _P, _P, _P, _F32, _P, _I32, _P, _P]),
     "tl_model_segment_time": (_I32, [_F64, _F64, _F64, _F64, _F64, _PF64]),
     "tl_model_comm_time": (_I32, [_F64, _F64, _F64, _PF64]),
     "tl_model_segment_threshold": (_I32, [_F64, _F64, _F64, _F64, _F64, _F64, _PF64]),
@@ -310,6 +311,16 @@ def tl_fused_attn(pool: int, plan: int, q, k_new, v_new, scale: float, out, out_
     _need(out, "out", T, hq, 128, "bf16" if out_is_bf16 else "f32"); _need(lse_out, "lse_out", T, hq, None, "f32")
     _check(load_library().tl_fused_attn(pool, plan, _dev(q), _dev(k_new), _dev(v_new), scale, _dev(out),
                                         int(bool(out_is_bf16)), _dev(lse_out), _stream(stream)))
+
+
+def tl_fused_attn_static(pool: int, plan: int, q, k_new, v_new, scale: float, out, out_is_bf16: bool, lse_out=None,
+                         stream=None):
+    """tl_fused_attn without any device allocation (the plan's work lists go to a static device buffer)."""
+    T, _, hq, hkv = _shape_of(plan)
+    _need(q, "q", T, hq, 128, "bf16"); _need(k_new, "k_new", T, hkv, 128, "bf16"); _need(v_new, "v_new", T, hkv, 128, "bf16")
+    _need(out, "out", T, hq, 128, "bf16" if out_is_bf16 else "f32"); _need(lse_out, "lse_out", T, hq, None, "f32")
+    _check(load_library().tl_fused_attn_static(pool, plan, _dev(q), _dev(k_new), _dev(v_new), scale, _dev(out),
+                                               int(bool(out_is_bf16)), _dev(lse_out), _stream(stream)))
 
 
 def tl_merge(plan: int, out_partial, lse, out, out_is_bf16: bool, lse_out=None, stream=None):

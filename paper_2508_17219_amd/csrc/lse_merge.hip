@@ -3,6 +3,7 @@
 // the self block of single-token requests, and the four compute entry points of the ABI
 // (tl_segment_attn, tl_causal_block, tl_fused_attn, tl_merge).
 #include <cmath>
+#include <mutex>
 
 #include "attn_common.h"
 
@@ -240,9 +241,57 @@ tl_status fused_rows(const tl_pool* pool, const tl_plan* plan, const void* base,
   return launch_fused_row_tiles(a, a.n_work, st);
 }
 
+// ---- for callers that cannot allocate ---------------------------------------------------------
+// tl_fused_attn_static stages the plan's work lists in this array instead of hipMalloc'd memory.
+// Every GPU the library runs on holds its own copy of the array, at its own address, until the
+// process ends.  In host code the array's name is only a handle for hipGetSymbolAddress: the
+// device address is looked up once per device, with that device current, and kept.
+constexpr size_t kStaticScratchBytes = (size_t)4 << 20;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+void* g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mu;
+
+tl_status static_scratch(void** out) {
+  int dev = -1;
+  TL_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) TL_FAIL(TL_EINVAL, "tl_fused_attn_static: device index %d not supported", dev);
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    TL_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) TL_FAIL(TL_EHIP, "tl_fused_attn_static: no device address for the static buffer");
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return TL_OK;
+}
+
 }  // namespace
 
 extern "C" {
+
+tl_status tl_fused_attn_static(const tl_pool* pool, tl_plan* plan, const void* q_dev, const void* k_new_dev,
+                               const void* v_new_dev, float scale, void* out_dev, int32_t out_is_bf16, float* lse_out,
+                               void* stream) {
+  if (plan && plan->n_tokens == 0) return TL_OK;
+  if (!pool || !plan || !q_dev || !k_new_dev || !v_new_dev || !out_dev) TL_FAIL(TL_EINVAL, "tl_fused_attn_static: null argument");
+  tl_status rc = plan_is_current(plan, pool, "tl_fused_attn_static");
+  if (rc != TL_OK) return rc;
+  if (!(scale > 0.f) || !std::isfinite(scale)) TL_FAIL(TL_EINVAL, "tl_fused_attn_static: scale must be positive and finite");
+  if (plan->ftiles.empty()) return TL_OK;
+  if (plan->blob_host.size() > kStaticScratchBytes)
+    TL_FAIL(TL_EINVAL, "tl_fused_attn_static: the plan's work lists take %zu bytes, the static buffer holds %zu",
+            plan->blob_host.size(), kStaticScratchBytes);
+  void* base = nullptr;
+  rc = static_scratch(&base);
+  if (rc != TL_OK) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  // the buffer keeps the last call's lists: this call's are copied over them, in stream order
+  // (nothing in the buffer has to start at zero)
+  TL_HIP(hipMemcpyAsync(base, plan->blob_host.data(), plan->blob_host.size(), hipMemcpyHostToDevice, st));
+  return fused_rows(pool, plan, base, q_dev, k_new_dev, v_new_dev, scale, out_dev, out_is_bf16, lse_out, st);
+}
 
 tl_status tl_segment_attn(const tl_pool* pool, tl_plan* plan, const void* q_dev, float scale, float* out_partial,
                           float* lse, void* stream) {
