@@ -302,6 +302,25 @@ def algorithmic_work(batch, info):
             "partial_bytes": part_bytes, "fused_io_bytes": fused_io_bytes}
 
 
+def three_step_report(b, r, w):
+    """Per-kernel times and roofline fractions of a plan without one-pass rows: tl_segment_attn
+    (row tiles over the pool work items), tl_causal_block (row tiles over the new tokens), tl_merge."""
+    info = r["info"]
+    hq, d = b.q_heads, b.head_dim
+    merge_bytes = info["n_merge_entries"] * hq * (d + 1) * 4.0 + info["n_tokens"] * hq * (2.0 * d + 4.0)
+    seg = w["flops_prefix"] / (r["segment_attn_ms"] * 1e-3) / 1e12
+    cau = w["flops_self"] / (r["causal_block_ms"] * 1e-3) / 1e12
+    mer = merge_bytes / (r["merge_ms"] * 1e-3) / 1e9
+    return {"ms_per_step": r["ms_per_step"], "merged_tok_s": b.n_tokens / (r["ms_per_step"] * 1e-3),
+            "work_items": info["n_items"], "row_tiles": info["n_tiles"], "causal_tiles": info["n_causal_tiles"],
+            "segment_attn": {"ms": r["segment_attn_ms"], "bound": "mfma", "achieved": seg, "unit": "TFLOP/s",
+                             "frac": seg / PEAK_BF16_TFLOPS},
+            "causal_block": {"ms": r["causal_block_ms"], "bound": "mfma", "achieved": cau, "unit": "TFLOP/s",
+                             "frac": cau / PEAK_BF16_TFLOPS},
+            "merge": {"ms": r["merge_ms"], "bound": "hbm", "achieved": mer, "unit": "GB/s", "frac": mer / PEAK_HBM_GBS,
+                      "algorithmic_bytes": merge_bytes}}
+
+
 def cpu_baseline(batch, budget_s=15.0):
     """The fp64 oracle, as it stands, timed on this host on a bounded sample of the workload:
     whole new tokens (all heads, full prefix + self block), taking requests in order of
@@ -338,7 +357,11 @@ def cpu_baseline(batch, budget_s=15.0):
             n = int(max(1, min(lq - done_r, (budget_s - t_used) / 4 / max(per_row, 1e-6))))
         n_done += done_r
     threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
-    return {"value": n_done / t_used, "unit": "tok/s", "cores": int(threads), "kind": "oracle",
+    # cores: what this process may run on; numpy's BLAS pool (the only threads the oracle uses) is
+    # sized from the environment and never exceeds it on the boxes this runs on
+    avail = len(os.sched_getaffinity(0))
+    return {"value": n_done / t_used, "unit": "tok/s", "cores": int(min(avail, threads)), "cores_available": avail,
+            "blas_threads": int(threads), "kind": "oracle",
             "sample": "%d new tokens (all %d heads) of %d request(s) nearest the batch's median prefix length "
                       "(requests %s, prefixes %s tokens), full prefix + causal self block, numpy fp64, %.1f s"
                       % (n_done, batch.q_heads, len(used_reqs), used_reqs, [int(L[r]) for r in used_reqs], t_used)}
@@ -359,6 +382,8 @@ def main():
     ap.add_argument("--three-step", action="store_true",
                     help="plan without TL_PLAN_FUSE_ROWS: every request goes through partials and the merge")
     ap.add_argument("--no-decode", action="store_true", help="skip the appended decode measurement")
+    ap.add_argument("--no-extra", action="store_true",
+                    help="skip the appended short measurements (three-step plan, other named workloads, MFMA-only rate)")
     ap.add_argument("--session-loop", action="store_true",
                     help="multi-turn workload as a closed loop: 8 turns of plan + attention + tl_pool_append")
     ap.add_argument("--per-chain-append", action="store_true",
@@ -477,6 +502,27 @@ def main():
     if args.graph:
         line["hip_graph"] = {"ms_per_step": res["graph_ms_per_step"],
                              "same_output": res["graph_checksum"] == res["checksum"]}
+    if args.workload == "prefill" and not args.no_extra:
+        # the matrix unit's own sustained rate on this machine in this run: what tells a slow box from a slow kernel
+        rl = line["roofline"]
+        rl["mfma_sustained"] = {"constant_operands_TFLOP/s": mfma_sustained(torch, False),
+                                "changing_operands_TFLOP/s": mfma_sustained(torch, True),
+                                "note": "a kernel of MFMAs only (no memory, LDS or vector work), best of 3 launches"}
+        rl["frac_of_sustained_changing"] = rl["achieved"] / rl["mfma_sustained"]["changing_operands_TFLOP/s"]
+        # the named three-step path on the same workload: partials of every work item, causal block, merge
+        side_steps = max(5, min(args.steps, 20))
+        r3 = run_workload(batch, side_steps, 3, torch, B, args.split_segments, fuse=False)
+        line["three_step"] = three_step_report(batch, r3, algorithmic_work(batch, r3["info"]))
+        # the other named workloads, short runs, default plan
+        line["configs"] = []
+        for mk in (wl.tiny, wl.longctx, lambda: wl.multiturn(turn=0), lambda: wl.multiturn(turn=7)):
+            ob = mk()
+            orr = run_workload(ob, side_steps, 3, torch, B, args.split_segments, fuse=True)
+            orl = roofline_for(ob, orr, algorithmic_work(ob, orr["info"]))
+            line["configs"].append({"workload": ob.name, "new_tokens": ob.n_tokens, "ms_per_step": orr["ms_per_step"],
+                                    "merged_tok_s": ob.n_tokens / (orr["ms_per_step"] * 1e-3), "kernel": orl["kernel"],
+                                    "achieved": orl["achieved"], "unit": orl["unit"], "frac": orl["frac"],
+                                    "steps": side_steps})
     if args.workload != "decode" and not args.no_decode:
         db = wl.decode()
         dres = run_workload(db, max(3, args.steps // 4), 1, torch, B, args.split_segments, fuse=not args.three_step)

@@ -40,6 +40,7 @@ __all__ = [
     "gather_segments",
     "append_rows",
     "segment_loads",
+    "PrefixTree",
     "attention_rows",
     "partial_attention",
     "merge_partials",
@@ -251,6 +252,52 @@ def segment_loads(req_lists, req_new_tokens):
         for s in ids:
             load[int(s)] = load.get(int(s), 0) + int(n)      # dicts keep insertion order
     return sorted(load.items(), key=lambda kv: -kv[1])          # sorted() is stable
+
+
+class PrefixTree:
+    """The prefix tree over the requests' segment lists, by brute force (paper Section 3.1: a global
+    prefix tree indexes the cache segments; Section 4.3: a segment is accessed only when its prefix
+    is, so accesses concentrate near the root, and heavy hitters are found from the root).
+
+    A node is the tuple of segment ids from the root down to it; the same id under two different
+    prefixes is two nodes.  Every request that walks its list from the root adds its number of new
+    tokens to the load of each node on the way, so a node's load never exceeds its parent's.
+    Nodes are kept in a dict in order of creation.  `walk` returns the batch's own loads, nodes in
+    order of first visit (requests in order, each list front to back).  `hot` sorts by decreasing
+    load, equal loads in order of creation (batch: of first visit): a parent, which is at least as
+    loaded and older than its children, always comes before them.  `evict(id)` removes every node
+    of that id together with everything below it (a prefix with a hole cannot be used).
+    """
+
+    def __init__(self):
+        self.load = {}
+
+    def walk(self, req_lists, req_new_tokens):
+        batch = {}
+        for ids, n in zip(req_lists, req_new_tokens):
+            path = ()
+            for s in ids:
+                path = path + (int(s),)
+                self.load[path] = self.load.get(path, 0) + int(n)
+                batch[path] = batch.get(path, 0) + int(n)
+        return batch
+
+    @staticmethod
+    def ranked(loads, k=None):
+        """[(path, load), ...] by decreasing load; equal loads keep the dict's order."""
+        out = sorted(loads.items(), key=lambda kv: -kv[1])          # sorted() is stable
+        return out if k is None else out[:k]
+
+    def hot(self, k=None):
+        return self.ranked(self.load, k)
+
+    def evict(self, seg_id: int):
+        seg_id = int(seg_id)
+        for path in [p for p in self.load if seg_id in p]:
+            del self.load[path]
+
+    def n_nodes(self) -> int:
+        return len(self.load)
 
 
 def append_rows(pool_k_bits, pool_v_bits, table: SlotTable, tail_id, new_ids, k_rows_bits, v_rows_bits):

@@ -513,3 +513,48 @@ def test_release_and_lru_eviction_hand_case_and_independent_model():
                     model.remove(victim)
             assert t.n_used() == len(model)
             assert t.lookup(list(range(12))).tolist() == [next((m[1] for m in model if m[0] == i), -1) for i in range(12)]
+
+
+def test_prefix_tree_hand_case_and_invariants():
+    """Pin for PrefixTree: a batch counted by hand, then invariants on random batches (a node is never
+    more loaded than its parent; the loads of all nodes of an id add up to segment_loads' figure for
+    that id; eviction removes a node with everything below it and nothing else)."""
+    t = orc.PrefixTree()
+    # A = [1, 2, 3] x 5 tokens, B = [1, 2, 9] x 2, C = [7] x 4, D = [1, 1] x 1
+    batch = t.walk([[1, 2, 3], [1, 2, 9], [7], [1, 1]], [5, 2, 4, 1])
+    # node (1): 5 + 2 + 1 = 8; (1,2): 7; (1,2,3): 5; (7): 4; (1,2,9): 2; (1,1): 1
+    assert t.ranked(batch) == [((1,), 8), ((1, 2), 7), ((1, 2, 3), 5), ((7,), 4), ((1, 2, 9), 2), ((1, 1), 1)]
+    assert t.hot(2) == [((1,), 8), ((1, 2), 7)]
+    # a second batch adds to the same nodes; its own loads start from zero
+    batch2 = t.walk([[7, 8], [1, 2, 3]], [10, 1])
+    assert t.ranked(batch2) == [((7,), 10), ((7, 8), 10), ((1,), 1), ((1, 2), 1), ((1, 2, 3), 1)]
+    assert t.hot(3) == [((7,), 14), ((7, 8), 10), ((1,), 9)]
+    # equal loads: the older node first (here the parent)
+    assert [p for p, _ in t.hot()][:2] == [(7,), (7, 8)]
+    t.evict(2)                                   # (1,2), (1,2,3), (1,2,9) go; (1), (1,1), (7), (7,8) stay
+    assert sorted(t.load) == [(1,), (1, 1), (7,), (7, 8)]
+    rng = np.random.default_rng(12)
+    for trial in range(10):
+        t = orc.PrefixTree()
+        stems = [rng.integers(0, 6, size=int(rng.integers(1, 5))).tolist() for _ in range(3)]
+        for b in range(3):
+            lists = [stems[int(rng.integers(0, 3))][:int(rng.integers(0, 5))] + rng.integers(0, 6, size=int(rng.integers(0, 4))).tolist()
+                     for _ in range(8)]
+            ntok = rng.integers(0, 20, size=8).tolist()
+            batch = t.walk(lists, ntok)
+            for path, l in batch.items():
+                if len(path) > 1:
+                    assert batch[path[:-1]] >= l and t.load[path[:-1]] >= t.load[path]
+            per_id = {}
+            for path, l in batch.items():
+                per_id[path[-1]] = per_id.get(path[-1], 0) + l
+            assert per_id == dict(orc.segment_loads(lists, ntok))
+            r = t.ranked(batch)
+            assert [l for _, l in r] == sorted((l for _, l in r), reverse=True)
+            for i, (path, _) in enumerate(r):                       # a parent always precedes its children
+                if len(path) > 1:
+                    assert path[:-1] in [p for p, _ in r[:i]]
+        victim = int(rng.integers(0, 6))
+        before = dict(t.load)
+        t.evict(victim)
+        assert set(t.load) == {p for p in before if victim not in p}
