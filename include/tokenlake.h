@@ -139,6 +139,28 @@ tl_status tl_pool_release(tl_pool* pool, uint64_t segment_id);
  * is evictable. */
 tl_status tl_pool_evict_lru(tl_pool* pool, uint64_t* evicted_id);
 
+/* The pool's prefix tree (Section 3.1: a global prefix tree indexes the segments; Section 3.2:
+ * `get_prefix_tree` hands it to the scheduler; Section 4.3: a segment is accessed only when its
+ * prefix is, so load concentrates near the root and heavy hitters are found from the root without
+ * walking the whole tree).  The tree lives in the pool across batches: tl_plan_create walks every
+ * request's list from the root, makes the nodes that are missing -- a node is a segment id under a
+ * given parent; the same id under two prefixes is two nodes of one slot -- and adds the request's
+ * new tokens to the load of every node on the way, so a node is never more loaded than its parent.
+ * tl_pool_evict_lru removes the evicted segment's nodes with everything below them.
+ *
+ * tl_pool_hot_segments: up to max_n nodes by decreasing cumulative load (equal loads: the older node
+ * first, so a parent precedes its children), found by a best-first search from the root that looks
+ * only at the children of the nodes it returns.  ids_out: host [max_n]; loads_out (new tokens that
+ * attended to the node), depths_out (0 = first segment of a prefix): host [max_n] or NULL.
+ *
+ * tl_pool_prefix_tree: the tree in level order from the root, at most max_nodes nodes: segment id,
+ * position of the parent in the same output (-1 = child of the root; a parent always comes first)
+ * and cumulative load.  *n_total_out (may be NULL) = nodes in the whole tree. */
+tl_status tl_pool_hot_segments(const tl_pool* pool, int32_t max_n, uint64_t* ids_out, int64_t* loads_out,
+                               int32_t* depths_out, int32_t* n_out);
+tl_status tl_pool_prefix_tree(const tl_pool* pool, int32_t max_nodes, uint64_t* ids_out, int32_t* parents_out,
+                              int64_t* loads_out, int32_t* n_out, int32_t* n_total_out);
+
 /* segment_id -> slot for n ids (host arrays); -1 for an id that is not resident.
  * Never fails on a miss.  Bit-exact integer work. */
 tl_status tl_pool_lookup(const tl_pool* pool, const uint64_t* ids, int32_t n, int32_t* slots_out);
@@ -237,12 +259,14 @@ tl_status tl_plan_export(const tl_plan* plan, int32_t* item_row_base, int32_t* i
                          int32_t* item_tokens, int32_t* item_slot_ptr, int32_t* item_slots,
                          int32_t* merge_ptr, int32_t* merge_rows);
 /* Heavy hitters of the batch (Section 4.3: load concentrates on segments near the root of the
- * prefix tree; they are found without walking the whole tree and are the candidates for
- * replication).  The load of a slot is the number of new tokens whose request lists it (a slot
- * listed twice by a request counts twice).  Writes up to max_n slots in order of decreasing
- * load -- equal loads in order of first appearance when the requests' lists are read in request
- * order, front to back, which puts segments nearer the root first -- with their loads, and the
- * number written to *n_out.  slots_out: host [max_n] int32; loads_out: host [max_n] int64 or NULL. */
+ * prefix tree; they are found from the root without walking the whole tree and are the candidates
+ * for replication).  The plan keeps the part of the pool's prefix tree that its requests walked,
+ * each node with the new tokens of the requests that passed through it; this call returns up to
+ * max_n of those nodes in order of decreasing load -- equal loads in order of first visit (requests
+ * in order, lists front to back), so a parent precedes its children -- by a best-first search from
+ * the root that looks only at the children of what it returns.  A segment that sits at several
+ * tree positions (lists that name it under different prefixes, or twice) appears once per position.
+ * slots_out: host [max_n] int32, the nodes' slots; loads_out: host [max_n] int64 or NULL. */
 tl_status tl_plan_hot_slots(const tl_plan* plan, int32_t max_n, int32_t* slots_out, int64_t* loads_out, int32_t* n_out);
 
 /* Sizes of the two variable-length arrays of tl_plan_export. */

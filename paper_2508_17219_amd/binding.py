@@ -51,6 +51,8 @@ _SIGNATURES = {
     "tl_pool_release": (_I32, [_P, _U64]),
     "tl_pool_evict_lru": (_I32, [_P, C.POINTER(_U64)]),
     "tl_pool_lookup": (_I32, [_P, _P, _I32, _P]),
+    "tl_pool_hot_segments": (_I32, [_P, _I32, _P, _P, _P, C.POINTER(_I32)]),
+    "tl_pool_prefix_tree": (_I32, [_P, _I32, _P, _P, _P, C.POINTER(_I32), C.POINTER(_I32)]),
     "tl_pool_fills": (_I32, [_P, _P, _I32, _P]),
     "tl_pool_used": (_I32, [_P, C.POINTER(_I32)]),
     "tl_pool_gather": (_I32, [_P, _P, _I32, _P, _P, _P]),
@@ -182,6 +184,24 @@ def tl_pool_evict_lru(pool: int) -> int:
     out = _U64(0)
     _check(load_library().tl_pool_evict_lru(pool, C.byref(out)))
     return out.value
+
+
+def tl_pool_hot_segments(pool: int, max_n: int):
+    """(ids, loads, depths) of the prefix tree's most loaded nodes, at most max_n, parents first."""
+    m = max(max_n, 1)
+    ids, loads, depths, n = np.zeros(m, np.uint64), np.zeros(m, np.int64), np.zeros(m, np.int32), _I32(0)
+    _check(load_library().tl_pool_hot_segments(pool, max_n, ids.ctypes.data, loads.ctypes.data, depths.ctypes.data, C.byref(n)))
+    return ids[:n.value], loads[:n.value], depths[:n.value]
+
+
+def tl_pool_prefix_tree(pool: int, max_nodes: int):
+    """(ids, parents, loads, n_total): the pool's prefix tree in level order, at most max_nodes nodes."""
+    m = max(max_nodes, 1)
+    ids, parents, loads = np.zeros(m, np.uint64), np.zeros(m, np.int32), np.zeros(m, np.int64)
+    n, total = _I32(0), _I32(0)
+    _check(load_library().tl_pool_prefix_tree(pool, max_nodes, ids.ctypes.data, parents.ctypes.data, loads.ctypes.data,
+                                              C.byref(n), C.byref(total)))
+    return ids[:n.value], parents[:n.value], loads[:n.value], total.value
 
 
 def tl_pool_lookup(pool: int, ids) -> np.ndarray:

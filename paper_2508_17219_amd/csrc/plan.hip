@@ -2,12 +2,15 @@
 // plane runs; Section 4.3: segments near the root of the prefix tree are hot, so requests
 // that share a run of segments are batched against it).
 //
-// Requests' slot lists are walked as a radix tree: a maximal run of list positions that the
-// same set of requests passes through becomes one work item whose query rows are all new
-// tokens of those requests.  Items with few rows per kv head are cut into split-K chunks.
+// Every request's list is walked down the pool's prefix tree (nodes are made as needed and stay
+// for later batches; each node on the way takes the request's new tokens as load).  A maximal
+// chain of tree nodes that the same set of requests passes through becomes one work item whose
+// query rows are all new tokens of those requests.  Items with few rows per kv head are cut into
+// split-K chunks.
 #include <algorithm>
 #include <cstring>
 #include <new>
+#include <queue>
 #include <unordered_set>
 
 #include "tl_internal.h"
@@ -119,51 +122,85 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
         fused[r] = rows >= kFuseRows || !shares;
       }
     }
+    // ---- walk the prefix tree ---------------------------------------------------------------------
+    // every request with a list, in order, front to back; `grouped` requests are those the planner
+    // may put together (new tokens, not set aside for the one-pass kernel)
+    PrefixTree& tree = pool->tree;
+    tree.begin_batch();
+    std::vector<int32_t> path(n_entries);          // tree node of every list entry
+    auto is_live = [&](int32_t r) { return ntok_of(r) > 0 && len_of(r) > 0 && !fused[r]; };
+    for (int32_t r = 0; r < n_req; ++r) {
+      const bool grouped = is_live(r);
+      int32_t node = 0;
+      for (int32_t i = req_seg_ptr[r]; i < req_seg_ptr[r + 1]; ++i) {
+        node = tree.child(node, seg_ids[i], slots[i]);
+        tree.visit(node, ntok_of(r), grouped, r);
+        path[i] = node;
+      }
+    }
+    // the batch's part of the tree, copied for tl_plan_hot_slots (which must not need the pool)
+    {
+      const std::vector<int32_t>& bn = tree.batch_nodes();
+      const size_t nb = bn.size();
+      p->bt_slot.resize(nb);
+      p->bt_load.resize(nb);
+      p->bt_first_child.resize(nb);
+      p->bt_next_sib.resize(nb);
+      auto idx = [&](int32_t n) { return n < 0 ? -1 : tree.at(n).batch_index; };
+      for (size_t i = 0; i < nb; ++i) {
+        const TreeNode& x = tree.at(bn[i]);
+        p->bt_slot[i] = x.slot;
+        p->bt_load[i] = x.batch_load;
+        p->bt_first_child[i] = idx(x.batch_first_child);
+        p->bt_next_sib[i] = idx(x.batch_next_sib);
+      }
+      for (int32_t c = tree.at(0).batch_first_child; c >= 0; c = tree.at(c).batch_next_sib) p->bt_roots.push_back(idx(c));
+    }
+
+    // ---- work items from tree nodes -----------------------------------------------------------------
     std::vector<RawItem> raw;
     std::vector<int32_t> live;
     for (int32_t r = 0; r < n_req; ++r)
-      if (ntok_of(r) > 0 && len_of(r) > 0 && !fused[r]) live.push_back(r);
+      if (is_live(r)) live.push_back(r);
     if (flags & TL_PLAN_NO_SHARING) {
       for (int32_t r : live) raw.push_back(RawItem{{r}, r, 0, len_of(r)});
     } else {
-      struct Frame { std::vector<int32_t> reqs; int32_t depth; };
-      std::vector<Frame> stack;
-      stack.push_back(Frame{live, 0});
+      // A run starts at a node and goes down while one child carries all of the node's grouped
+      // requests (then nobody has ended and nobody has turned off).  Runs come out parent level
+      // first, siblings in order of their first request, then each sibling's subtree in turn.
+      std::vector<int32_t> item_of(tree.batch_nodes().size(), -1);   // run that starts at a visited node
+      std::vector<int32_t> stack(1, 0), kids, next;
       while (!stack.empty()) {
-        Frame f = std::move(stack.back());
+        const int32_t f = stack.back();
         stack.pop_back();
-        // partition by the slot at this depth, in order of first appearance
-        std::vector<int32_t> keys;
-        std::unordered_map<int32_t, std::vector<int32_t>> parts;
-        for (int32_t r : f.reqs) {
-          if (len_of(r) <= f.depth) continue;
-          int32_t s = slot_at(r, f.depth);
-          auto ins = parts.emplace(s, std::vector<int32_t>());
-          if (ins.second) keys.push_back(s);
-          ins.first->second.push_back(r);
-        }
-        // children pushed in reverse so that items come out in first-appearance order
-        std::vector<Frame> next;
-        for (int32_t s : keys) {
-          std::vector<int32_t>& sub = parts[s];
-          int32_t e = f.depth + 1;
+        kids.clear();
+        for (int32_t c = tree.at(f).batch_first_child; c >= 0; c = tree.at(c).batch_next_sib)
+          if (tree.at(c).batch_cnt > 0) kids.push_back(c);
+        std::sort(kids.begin(), kids.end(),
+                  [&](int32_t a, int32_t b) { return tree.at(a).batch_first_req < tree.at(b).batch_first_req; });
+        next.clear();
+        for (int32_t c : kids) {
+          const int32_t cnt = tree.at(c).batch_cnt;
+          int32_t last = c;
           for (;;) {
-            bool all_continue = true, any_continue = false;
-            for (int32_t r : sub) {
-              if (len_of(r) > e) any_continue = true; else all_continue = false;
-            }
-            if (!any_continue || !all_continue) break;       // somebody ends here: the set changes
-            int32_t s0 = slot_at(sub[0], e);
-            bool same = true;
-            for (int32_t r : sub) if (slot_at(r, e) != s0) { same = false; break; }
-            if (!same) break;
-            ++e;
+            int32_t all = -1;
+            for (int32_t d = tree.at(last).batch_first_child; d >= 0; d = tree.at(d).batch_next_sib)
+              if (tree.at(d).batch_cnt == cnt) { all = d; break; }
+            if (all < 0) break;
+            last = all;
           }
-          raw.push_back(RawItem{sub, sub[0], f.depth, e});
-          next.push_back(Frame{sub, e});
+          item_of[tree.at(c).batch_index] = (int32_t)raw.size();
+          raw.push_back(RawItem{{}, tree.at(c).batch_first_req, tree.at(c).depth, tree.at(last).depth + 1});
+          next.push_back(last);
         }
-        for (auto it = next.rbegin(); it != next.rend(); ++it) stack.push_back(std::move(*it));
+        for (auto it = next.rbegin(); it != next.rend(); ++it) stack.push_back(*it);
       }
+      // who passes through each run's first node, in request order
+      for (int32_t r : live)
+        for (int32_t i = req_seg_ptr[r]; i < req_seg_ptr[r + 1]; ++i) {
+          const int32_t it = item_of[tree.at(path[i]).batch_index];
+          if (it >= 0) raw[it].reqs.push_back(r);
+        }
     }
 
     // The kv tokens of a slot list as tiles of kKvTile rows.  A slot listed several times (lists are
@@ -384,13 +421,6 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
           if (!tok_fused[t]) p->merge_rows[cur[t]++] = self_base + t;
     }
 
-    // kept for tl_plan_hot_slots, which ranks the slots on first request
-    p->list_slots = slots;
-    p->list_ptr.assign(req_seg_ptr, req_seg_ptr + n_req + 1);
-    p->list_ntok.resize(n_req);
-    for (int32_t r = 0; r < n_req; ++r) p->list_ntok[r] = ntok_of(r);
-    p->hot_ready = false;
-
     int64_t uniq_tok = 0;
     {
       std::vector<char> seen(pool->n_slots, 0);
@@ -492,34 +522,25 @@ tl_status tl_plan_get_info(const tl_plan* plan, tl_plan_info* info) {
 
 tl_status tl_plan_hot_slots(const tl_plan* plan, int32_t max_n, int32_t* slots_out, int64_t* loads_out, int32_t* n_out) {
   if (!plan || max_n < 0 || !n_out || (max_n > 0 && !slots_out)) TL_FAIL(TL_EINVAL, "tl_plan_hot_slots: bad argument");
-  if (!plan->hot_ready) {
-    // load of a slot = new tokens of the requests that list it
-    try {
-      std::vector<int64_t> load(plan->pool_n_slots, 0);
-      std::vector<char> seen(plan->pool_n_slots, 0);
-      std::vector<int32_t> order;   // first appearance, requests in order, lists front to back
-      for (int32_t r = 0; r < plan->n_req; ++r)
-        for (int32_t i = plan->list_ptr[r]; i < plan->list_ptr[r + 1]; ++i) {
-          const int32_t s = plan->list_slots[i];
-          if (!seen[s]) {
-            seen[s] = 1;
-            order.push_back(s);
-          }
-          load[s] += plan->list_ntok[r];
-        }
-      std::stable_sort(order.begin(), order.end(), [&](int32_t x, int32_t y) { return load[x] > load[y]; });
-      plan->hot_loads.clear();
-      for (int32_t s : order) plan->hot_loads.push_back(load[s]);
-      plan->hot_slots.swap(order);
-      plan->hot_ready = true;
-    } catch (const std::bad_alloc&) {
-      TL_FAIL(TL_ENOMEM, "tl_plan_hot_slots: host allocation failed");
+  // Best-first search from the root over the nodes this batch walked: a node enters the frontier when
+  // its parent leaves it and is never more loaded than its parent, so nodes leave in order of
+  // decreasing load (equal loads: first visited first) and only the children of what is returned
+  // are ever looked at.
+  int32_t n = 0;
+  try {
+    auto later = [&](int32_t a, int32_t b) { return plan->bt_load[a] != plan->bt_load[b] ? plan->bt_load[a] < plan->bt_load[b] : a > b; };
+    std::priority_queue<int32_t, std::vector<int32_t>, decltype(later)> frontier(later);
+    for (int32_t c : plan->bt_roots) frontier.push(c);
+    while (n < max_n && !frontier.empty()) {
+      const int32_t x = frontier.top();
+      frontier.pop();
+      slots_out[n] = plan->bt_slot[x];
+      if (loads_out) loads_out[n] = plan->bt_load[x];
+      ++n;
+      for (int32_t c = plan->bt_first_child[x]; c >= 0; c = plan->bt_next_sib[c]) frontier.push(c);
     }
-  }
-  const int32_t n = std::min<int32_t>(max_n, (int32_t)plan->hot_slots.size());
-  for (int32_t i = 0; i < n; ++i) {
-    slots_out[i] = plan->hot_slots[i];
-    if (loads_out) loads_out[i] = plan->hot_loads[i];
+  } catch (const std::bad_alloc&) {
+    TL_FAIL(TL_ENOMEM, "tl_plan_hot_slots: host allocation failed");
   }
   *n_out = n;
   return TL_OK;

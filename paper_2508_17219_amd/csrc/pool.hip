@@ -141,6 +141,7 @@ tl_status tl_pool_create(tl_pool** out, int32_t n_slots, int32_t seg_len, int32_
     p->fill.assign(n_slots, 0);
     p->refcnt.assign(n_slots, 0);
     p->stamp.assign(n_slots, 0);
+    p->tree.reset(n_slots);
   } catch (...) {
     delete p;
     TL_FAIL(TL_ENOMEM, "tl_pool_create: host allocation failed");
@@ -367,11 +368,54 @@ tl_status tl_pool_evict_lru(tl_pool* pool, uint64_t* evicted_id) {
   if (best < 0) TL_FAIL(TL_ENOTFOUND, "tl_pool_evict_lru: no segment with zero references");
   if (evicted_id) *evicted_id = pool->id_of[best];
   pool->slot_of.erase(pool->id_of[best]);
+  pool->tree.remove_slot(best);          // a prefix that has lost a segment is no prefix: its nodes go, with what hangs below
   pool->fill[best] = 0;
   pool->n_used--;
   pool->generation++;
   if (best < pool->free_hint) pool->free_hint = best;
   pool->fill_dirty = true;
+  return TL_OK;
+}
+
+tl_status tl_pool_hot_segments(const tl_pool* pool, int32_t max_n, uint64_t* ids_out, int64_t* loads_out, int32_t* depths_out,
+                               int32_t* n_out) {
+  if (!pool || max_n < 0 || !n_out || (max_n > 0 && !ids_out)) TL_FAIL(TL_EINVAL, "tl_pool_hot_segments: bad argument");
+  try {
+    std::vector<int32_t> nodes;
+    pool->tree.hottest(max_n, nodes);
+    for (size_t i = 0; i < nodes.size(); ++i) {
+      const TreeNode& x = pool->tree.at(nodes[i]);
+      ids_out[i] = x.id;
+      if (loads_out) loads_out[i] = x.load;
+      if (depths_out) depths_out[i] = x.depth;
+    }
+    *n_out = (int32_t)nodes.size();
+  } catch (const std::bad_alloc&) {
+    TL_FAIL(TL_ENOMEM, "tl_pool_hot_segments: host allocation failed");
+  }
+  return TL_OK;
+}
+
+tl_status tl_pool_prefix_tree(const tl_pool* pool, int32_t max_nodes, uint64_t* ids_out, int32_t* parents_out, int64_t* loads_out,
+                              int32_t* n_out, int32_t* n_total_out) {
+  if (!pool || max_nodes < 0 || !n_out || (max_nodes > 0 && (!ids_out || !parents_out)))
+    TL_FAIL(TL_EINVAL, "tl_pool_prefix_tree: bad argument");
+  try {
+    std::vector<int32_t> nodes;
+    pool->tree.level_order(max_nodes, nodes);
+    std::unordered_map<int32_t, int32_t> pos;       // node -> position in the output
+    for (size_t i = 0; i < nodes.size(); ++i) {
+      const TreeNode& x = pool->tree.at(nodes[i]);
+      pos.emplace(nodes[i], (int32_t)i);
+      ids_out[i] = x.id;
+      parents_out[i] = x.parent == 0 ? -1 : pos.at(x.parent);      // a parent always comes earlier in level order
+      if (loads_out) loads_out[i] = x.load;
+    }
+    *n_out = (int32_t)nodes.size();
+    if (n_total_out) *n_total_out = pool->tree.size();
+  } catch (const std::bad_alloc&) {
+    TL_FAIL(TL_ENOMEM, "tl_pool_prefix_tree: host allocation failed");
+  }
   return TL_OK;
 }
 

@@ -7,6 +7,7 @@
 #include <unordered_map>
 #include <vector>
 
+#include "prefix_tree.h"
 #include "tokenlake.h"
 
 namespace tl {
@@ -71,6 +72,7 @@ struct tl_pool {
   int32_t free_hint;             // no free slot below this index
   uint64_t generation;           // goes up whenever a slot's content, fill or owner changes (put of a new id,
                                  // append, adopt, evict): a plan is valid for the generation it was built in
+  mutable tl::PrefixTree tree;   // grows as plans walk their requests' lists; loses a segment's nodes on eviction
   // device mirror of fill[]
   mutable int32_t* fill_dev;
   mutable bool fill_dirty;
@@ -87,11 +89,10 @@ struct tl_plan {
                                    // lists first, then those with kLongMergeList or more partials
   int32_t n_merge_short = 0;
   std::vector<int32_t> single_tok; // the new token of every request that has exactly one (not fused): self block = one key
-  // heavy hitters, computed on first request from the resolved lists kept here
-  std::vector<int32_t> list_slots, list_ptr, list_ntok;
-  mutable bool hot_ready;
-  mutable std::vector<int32_t> hot_slots;  // every listed slot, by decreasing load (new tokens that attend to it)
-  mutable std::vector<int64_t> hot_loads;
+  // the part of the pool's prefix tree that this batch walked, nodes in order of first visit (a node's
+  // parent comes before it): what tl_plan_hot_slots searches, from the root side, without the pool
+  std::vector<int32_t> bt_slot, bt_first_child, bt_next_sib, bt_roots;
+  std::vector<int64_t> bt_load;
   std::vector<int32_t> tok;      // token index array referenced by Work::tok_off
   std::vector<int32_t> tile_base;  // Work::full_off
   std::vector<int32_t> part_tile;  // Work::part_off, pairs (first kv row, valid tokens)

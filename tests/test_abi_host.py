@@ -463,20 +463,32 @@ def test_batched_append_validates_every_chain_before_anything_changes():
     B.tl_pool_destroy(pool)
 
 
-def test_hot_slots_match_the_oracles_segment_loads():
-    for b in (wl.multiturn(turn=3), wl.prefill(seed=9, n_req=5, new_tokens=40, lo=300, hi=900, seg_len=128, n_slots=64, n_shared=2),
-              wl.longctx(n_req=2, entries=40, new_tokens=64, n_ids=25, n_slots=32)):
+def test_hot_slots_match_the_oracles_prefix_tree():
+    """tl_plan_hot_slots against the oracle's brute-force prefix tree of the same batch (node = path of
+    ids from the root; loads; parents first among equals).  Where every segment sits at one tree
+    position (multi-turn, prefill) that is also the oracle's per-segment load table; the
+    long-context lists name segments under many prefixes, one node each."""
+    for b, tree_shaped in ((wl.multiturn(turn=3), True),
+                           (wl.prefill(seed=9, n_req=5, new_tokens=40, lo=300, hi=900, seg_len=128, n_slots=64, n_shared=2), True),
+                           (wl.longctx(n_req=2, entries=40, new_tokens=64, n_ids=25, n_slots=32), False)):
         pool = _pool_for(b)
         plan = B.tl_plan_create(pool, b.q_heads, b.req_row_ptr, b.req_seg_ptr, b.seg_ids)
         lists = [b.seg_ids[b.req_seg_ptr[r]:b.req_seg_ptr[r + 1]].tolist() for r in range(b.n_req)]
-        want = orc.segment_loads(lists, np.diff(b.req_row_ptr).tolist())
+        ntok = np.diff(b.req_row_ptr).tolist()
+        t = orc.PrefixTree()
+        want = t.ranked(t.walk(lists, ntok))
         slots, loads = B.tl_plan_hot_slots(plan, 10 ** 6)
-        assert slots.tolist() == B.tl_pool_lookup(pool, [i for i, _ in want]).tolist()
+        assert slots.tolist() == B.tl_pool_lookup(pool, [path[-1] for path, _ in want]).tolist()
         assert loads.tolist() == [l for _, l in want]
+        if tree_shaped:
+            per_seg = orc.segment_loads(lists, ntok)
+            assert slots.tolist() == B.tl_pool_lookup(pool, [i for i, _ in per_seg]).tolist() and loads.tolist() == [l for _, l in per_seg]
         top, _ = B.tl_plan_hot_slots(plan, 3)
         assert top.tolist() == slots[:3].tolist()
+        B.tl_pool_destroy(pool)                                  # the plan keeps its own part of the tree
+        again, _ = B.tl_plan_hot_slots(plan, 5)
+        assert again.tolist() == slots[:5].tolist()
         B.tl_plan_destroy(plan)
-        B.tl_pool_destroy(pool)
     # the multi-turn batch: the 16 segments of the system prompt carry every new token
     b = wl.multiturn(turn=3)
     pool = _pool_for(b)
@@ -485,6 +497,64 @@ def test_hot_slots_match_the_oracles_segment_loads():
     assert loads[:16].tolist() == [64 * 256] * 16 and loads[16] == 256
     assert slots[:16].tolist() == B.tl_pool_lookup(pool, np.arange(16, dtype=np.uint64)).tolist()
     B.tl_plan_destroy(plan)
+    B.tl_pool_destroy(pool)
+
+
+def test_prefix_tree_lives_across_batches_and_loses_evicted_segments():
+    """The pool's tree against the oracle's over a sequence of random batches with evictions in
+    between: cumulative loads, ranking from the root, level-order export, and the removal of an
+    evicted segment's nodes with everything below them; the plans of a batch built from the tree
+    still cover every (token, list entry) pair."""
+    rng = np.random.default_rng(77)
+    n_ids, C = 14, 64
+    pool = B.tl_pool_create(16, C, 1, 128, FAKE_K, FAKE_V)
+    ids = np.arange(n_ids, dtype=np.uint64) + 50
+    B.tl_pool_adopt(pool, ids, np.arange(n_ids), np.full(n_ids, C))
+    resident = set(int(i) for i in ids)
+    t = orc.PrefixTree()
+    stems = [rng.choice(ids, size=3, replace=False).tolist() for _ in range(3)]
+    for step in range(12):
+        lists, ntok = [], []
+        for r in range(int(rng.integers(1, 7))):
+            l = stems[int(rng.integers(0, 3))][:int(rng.integers(0, 4))] + rng.choice(ids, size=int(rng.integers(0, 4))).tolist()
+            lists.append([int(x) for x in l if int(x) in resident])
+            ntok.append(int(rng.choice([0, 1, 5, 70])))
+        row_ptr = np.concatenate([[0], np.cumsum(ntok)]).astype(np.int32)
+        seg_ptr = np.concatenate([[0], np.cumsum([len(l) for l in lists])]).astype(np.int32)
+        flat = np.array([x for l in lists for x in l], np.uint64)
+        plan = B.tl_plan_create(pool, 4, row_ptr, seg_ptr, flat, B.TL_PLAN_SELF_BLOCK)
+        batch = t.walk(lists, ntok)
+        want = t.ranked(batch)
+        slots, loads = B.tl_plan_hot_slots(plan, 1000)
+        assert slots.tolist() == B.tl_pool_lookup(pool, [p[-1] for p, _ in want]).tolist() and loads.tolist() == [l for _, l in want]
+        B.tl_plan_destroy(plan)
+        # cumulative ranking and export
+        hot = t.hot()
+        got_ids, got_loads, got_depths = B.tl_pool_hot_segments(pool, 1000)
+        assert got_ids.tolist() == [p[-1] for p, _ in hot] and got_loads.tolist() == [l for _, l in hot]
+        assert got_depths.tolist() == [len(p) - 1 for p, _ in hot]
+        k = int(rng.integers(0, 5))
+        assert B.tl_pool_hot_segments(pool, k)[0].tolist() == [p[-1] for p, _ in hot[:k]]
+        e_ids, e_par, e_loads, total = B.tl_pool_prefix_tree(pool, 1000)
+        assert total == t.n_nodes() == len(e_ids)
+        paths = []
+        for i in range(len(e_ids)):                               # rebuild every node's path from the export
+            paths.append((paths[e_par[i]] if e_par[i] >= 0 else ()) + (int(e_ids[i]),))
+            assert e_par[i] < i
+        assert sorted(paths) == sorted(t.load) and all(t.load[p] == int(l) for p, l in zip(paths, e_loads))
+        assert [len(p) for p in paths] == sorted(len(p) for p in paths)          # level order
+        assert len(B.tl_pool_prefix_tree(pool, 2)[0]) == min(2, total)
+        if step % 3 == 2 and len(resident) > 4:                   # evict something: its nodes and their subtrees go
+            victim = int(rng.choice(sorted(resident)))
+            for i in sorted(resident):
+                if i != victim:
+                    B.tl_plan_destroy(B.tl_plan_create(pool, 4, [0, 1], [0, 1], np.array([i], np.uint64), 0))   # refresh the others
+                    t.walk([[i]], [1])
+            B.tl_pool_release(pool, victim)
+            assert B.tl_pool_evict_lru(pool) == victim
+            t.evict(victim)
+            resident.discard(victim)
+            assert B.tl_pool_prefix_tree(pool, 1000)[3] == t.n_nodes()
     B.tl_pool_destroy(pool)
 
 
