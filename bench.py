@@ -100,7 +100,7 @@ def run_workload(batch, steps, warmup, torch, B, split_segments=0, fuse=True, ex
         calls = (lambda: B.tl_segment_attn(pool, plan, q, scale, outp, lsep),
                  lambda: B.tl_causal_block(plan, q, kn, vn, scale, outp, lsep),
                  lambda: B.tl_merge(plan, outp, lsep, out, True, lse),
-                 lambda: B.tl_fused_attn(pool, plan, q, kn, vn, scale, out, True, lse))
+                 lambda: B.tl_fused_attn(pool, plan, q, kn, vn, scale, out, True, lse, prior_partial=outp, prior_lse=lsep))
         if marks and which is None: marks[0].record()          # five marks: one before, one after every call
         for i, call in enumerate(calls):
             if marks and which == i: marks[0].record()         # two marks: around call `which` only

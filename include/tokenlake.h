@@ -195,7 +195,7 @@ enum {
                              Default (flag absent): a slot that the list names m times is walked
                              once with weight m (exact: m equal keys contribute m exp(s) to the
                              numerator and the denominator alike)                          */
-  TL_PLAN_FUSE_ROWS = 4   /* requests that gain nothing from sharing a run of slots leave the
+  TL_PLAN_FUSE_ROWS = 4,  /* requests that gain nothing from sharing a run of slots leave the
                              three-step path: one pass of tl_fused_attn over their whole slot
                              list and their own new tokens writes their final output.  These
                              are the requests with more than 16 query rows per kv head (new
@@ -206,6 +206,19 @@ enum {
                              KV instead.  Such rows have a single partial, so nothing is
                              written to out_partial for them and tl_segment_attn /
                              tl_causal_block / tl_merge skip them.  Needs TL_PLAN_SELF_BLOCK. */
+  TL_PLAN_FUSE_TAILS = 16 /* every request with more than 16 query rows per kv head (that
+                             TL_PLAN_FUSE_ROWS, if also given, has not taken whole) is cut where its
+                             list stops being shared: the runs it shares with other requests stay
+                             work items of tl_segment_attn -- a hot segment is read once for all its
+                             requesters' rows (Section 4.3) -- and the rest of its list together with
+                             its own new tokens is one pass of tl_fused_attn, whose epilogue merges
+                             the request's partial rows of those work items in and writes the final
+                             output.  No causal tile, no partial of its own and no tl_merge for such
+                             a request; tl_fused_attn must follow tl_segment_attn on the same stream
+                             and be given the partial buffers.  (In a batch of fewer row-tile
+                             workgroups than the GPU has CUs a private run longer than 2048 tokens is
+                             cut along its KV instead, as without the flag.)  Needs
+                             TL_PLAN_SELF_BLOCK; not with TL_PLAN_NO_SHARING. */
 };
 
 typedef struct tl_plan_info {
@@ -228,6 +241,10 @@ typedef struct tl_plan_info {
   int64_t tile_pairs;      /* (query token, kv token) pairs the row-tile kernels compute: as
                               prefix_pairs over row-tile work, each distinct slot of a work
                               item's list counted once (unless TL_PLAN_WALK_REPEATS)       */
+  int64_t item_pairs;      /* the part of prefix_pairs that tl_segment_attn's work items compute
+                              (the rest belongs to tl_fused_attn's one-pass rows and tails)   */
+  int32_t n_prior_rows;    /* partial rows of work items that tl_fused_attn merges in itself
+                              (TL_PLAN_FUSE_TAILS), counted per (request, work item)           */
 } tl_plan_info;
 
 /* req_row_ptr: host [n_req+1], offsets of each request's new tokens in the batch's Q
@@ -299,10 +316,14 @@ tl_status tl_causal_block(tl_plan* plan, const void* q_dev, const void* k_new_de
  * q_dev, k_new_dev, v_new_dev as in tl_causal_block.  out_dev: device [n_tokens, q_heads, 128],
  * bf16 if out_is_bf16 else fp32; lse_out: device [n_tokens, q_heads] fp32 or NULL.  Only the
  * fused requests' tokens are written; the other tokens of the same arrays are written by
- * tl_merge.  A plan without fused requests: nothing to do, TL_OK. */
+ * tl_merge.  A plan without fused requests: nothing to do, TL_OK.
+ * prior_partial / prior_lse: device, the out_partial / lse arrays that tl_segment_attn has written
+ * for this plan earlier on the same stream; read only under TL_PLAN_FUSE_TAILS (the partial rows of
+ * the shared runs above each one-pass tail, merged in by the epilogue with the rule of tl_merge);
+ * may be NULL when the plan's n_prior_rows is 0, else TL_EINVAL. */
 tl_status tl_fused_attn(const tl_pool* pool, tl_plan* plan, const void* q_dev, const void* k_new_dev,
-                        const void* v_new_dev, float scale, void* out_dev, int32_t out_is_bf16, float* lse_out,
-                        void* stream);
+                        const void* v_new_dev, float scale, const float* prior_partial, const float* prior_lse,
+                        void* out_dev, int32_t out_is_bf16, float* lse_out, void* stream);
 
 /* tl_fused_attn for callers that cannot allocate device memory (code under HIP graph capture set-up
  * rules, tight serving loops, harnesses that forbid hipMalloc): same arguments, same kernels, same
@@ -316,8 +337,9 @@ tl_status tl_fused_attn(const tl_pool* pool, tl_plan* plan, const void* q_dev, c
  * call's contents: calls on one stream are ordered and safe; calls that overlap on one GPU (two
  * streams, two threads) race and must be serialised by the caller. */
 tl_status tl_fused_attn_static(const tl_pool* pool, tl_plan* plan, const void* q_dev, const void* k_new_dev,
-                               const void* v_new_dev, float scale, void* out_dev, int32_t out_is_bf16,
-                               float* lse_out, void* stream);
+                               const void* v_new_dev, float scale, const float* prior_partial,
+                               const float* prior_lse, void* out_dev, int32_t out_is_bf16, float* lse_out,
+                               void* stream);
 
 /* Exact recombination of each token's partials (Section 2.1: partial outputs and normalizers are
  * reduced into the final output; Section 4, first paragraph):

@@ -17,7 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libtokenlake.so")
 
 TL_OK, TL_EINVAL, TL_ENOMEM, TL_EFULL, TL_ENOTFOUND, TL_EHIP = 0, -1, -2, -3, -4, -5
-TL_PLAN_SELF_BLOCK, TL_PLAN_NO_SHARING, TL_PLAN_FUSE_ROWS, TL_PLAN_WALK_REPEATS = 1, 2, 4, 8
+TL_PLAN_SELF_BLOCK, TL_PLAN_NO_SHARING, TL_PLAN_FUSE_ROWS, TL_PLAN_WALK_REPEATS, TL_PLAN_FUSE_TAILS = 1, 2, 4, 8, 16
 
 
 class TokenLakeError(RuntimeError):
@@ -31,7 +31,8 @@ class tl_plan_info(C.Structure):
         "n_req", "n_tokens", "q_heads", "kv_heads", "n_items", "n_partial_rows", "self_row_base",
         "n_tiles", "n_units", "n_causal_tiles", "n_list_entries", "n_merge_entries")] + [
         (n, C.c_int64) for n in ("prefix_pairs", "self_pairs", "unique_kv_tokens")] + [
-        (n, C.c_int32) for n in ("n_fused_tiles", "n_fused_tokens", "n_single_tokens")] + [("tile_pairs", C.c_int64)]
+        (n, C.c_int32) for n in ("n_fused_tiles", "n_fused_tokens", "n_single_tokens")] + [
+        ("tile_pairs", C.c_int64), ("item_pairs", C.c_int64), ("n_prior_rows", C.c_int32)]
 
 
 _lib = None
@@ -65,8 +66,8 @@ _SIGNATURES = {
     "tl_segment_attn": (_I32, [_P, _P, _P, _F32, _P, _P, _P]),
     "tl_causal_block": (_I32, [_P, _P, _P, _P, _F32, _P, _P, _P]),
     "tl_merge": (_I32, [_P, _P, _P, _P, _I32, _P, _P]),
-    "tl_fused_attn": (_I32, [_P, _P, _P, _P, _P, _F32, _P, _I32, _P, _P]),
-    "tl_fused_attn_static": (_I32, [_P, _P, _P, _P, _P, _F32, _P, _I32, _P, _P]),
+    "tl_fused_attn": (_I32, [_P, _P, _P, _P, _P, _F32, _P, _P, _P, _I32, _P, _P]),
+    "tl_fused_attn_static": (_I32, [_P, _P, _P, _P, _P, _F32, _P, _P, _P, _I32, _P, _P]),
     "tl_model_segment_time": (_I32, [_F64, _F64, _F64, _F64, _F64, _PF64]),
     "tl_model_comm_time": (_I32, [_F64, _F64, _F64, _PF64]),
     "tl_model_segment_threshold": (_I32, [_F64, _F64, _F64, _F64, _F64, _F64, _PF64]),
@@ -325,22 +326,27 @@ def tl_causal_block(plan: int, q, k_new, v_new, scale: float, out_partial, lse, 
                                           _stream(stream)))
 
 
-def tl_fused_attn(pool: int, plan: int, q, k_new, v_new, scale: float, out, out_is_bf16: bool, lse_out=None, stream=None):
-    T, _, hq, hkv = _shape_of(plan)
+def tl_fused_attn(pool: int, plan: int, q, k_new, v_new, scale: float, out, out_is_bf16: bool, lse_out=None, stream=None,
+                  prior_partial=None, prior_lse=None):
+    """prior_partial / prior_lse: the partial buffers tl_segment_attn wrote (needed by TL_PLAN_FUSE_TAILS plans)."""
+    T, R, hq, hkv = _shape_of(plan)
     _need(q, "q", T, hq, 128, "bf16"); _need(k_new, "k_new", T, hkv, 128, "bf16"); _need(v_new, "v_new", T, hkv, 128, "bf16")
     _need(out, "out", T, hq, 128, "bf16" if out_is_bf16 else "f32"); _need(lse_out, "lse_out", T, hq, None, "f32")
-    _check(load_library().tl_fused_attn(pool, plan, _dev(q), _dev(k_new), _dev(v_new), scale, _dev(out),
-                                        int(bool(out_is_bf16)), _dev(lse_out), _stream(stream)))
+    _need(prior_partial, "prior_partial", R, hq, 128, "f32"); _need(prior_lse, "prior_lse", R, hq, None, "f32")
+    _check(load_library().tl_fused_attn(pool, plan, _dev(q), _dev(k_new), _dev(v_new), scale, _dev(prior_partial),
+                                        _dev(prior_lse), _dev(out), int(bool(out_is_bf16)), _dev(lse_out), _stream(stream)))
 
 
 def tl_fused_attn_static(pool: int, plan: int, q, k_new, v_new, scale: float, out, out_is_bf16: bool, lse_out=None,
-                         stream=None):
+                         stream=None, prior_partial=None, prior_lse=None):
     """tl_fused_attn without any device allocation (the plan's work lists go to a static device buffer)."""
-    T, _, hq, hkv = _shape_of(plan)
+    T, R, hq, hkv = _shape_of(plan)
     _need(q, "q", T, hq, 128, "bf16"); _need(k_new, "k_new", T, hkv, 128, "bf16"); _need(v_new, "v_new", T, hkv, 128, "bf16")
     _need(out, "out", T, hq, 128, "bf16" if out_is_bf16 else "f32"); _need(lse_out, "lse_out", T, hq, None, "f32")
-    _check(load_library().tl_fused_attn_static(pool, plan, _dev(q), _dev(k_new), _dev(v_new), scale, _dev(out),
-                                               int(bool(out_is_bf16)), _dev(lse_out), _stream(stream)))
+    _need(prior_partial, "prior_partial", R, hq, 128, "f32"); _need(prior_lse, "prior_lse", R, hq, None, "f32")
+    _check(load_library().tl_fused_attn_static(pool, plan, _dev(q), _dev(k_new), _dev(v_new), scale, _dev(prior_partial),
+                                               _dev(prior_lse), _dev(out), int(bool(out_is_bf16)), _dev(lse_out),
+                                               _stream(stream)))
 
 
 def tl_merge(plan: int, out_partial, lse, out, out_is_bf16: bool, lse_out=None, stream=None):

@@ -39,6 +39,9 @@ struct AttnArgs {
   const int32_t* part_tile;  // (first kv row, valid tokens) of each cut-short tile
   const float* tile_lm;      // log2(times the tile's slot is listed), parallel to tile_base
   const float* part_lm;      // the same for the cut-short tiles
+  const int32_t* prior_rows;  // one-pass tails: partial rows to merge in (see Work::prior_off)
+  const float* prior_out;     // [rows, q_heads, 128] partials written by an earlier launch
+  const float* prior_lse;     // [rows, q_heads]
   float* out;             // [rows, q_heads, 128]
   float* lse;             // [rows, q_heads]
   int32_t q_heads, kv_heads, group, seg_len, n_work;   // group = q_heads / kv_heads

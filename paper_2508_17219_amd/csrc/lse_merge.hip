@@ -31,26 +31,30 @@ __global__ __launch_bounds__(256) void lse_merge_kernel(const float* __restrict_
   if (idx < q_heads * 32) {
     const int hd = idx >> 5, c4 = idx & 31;
     // the first kHead entries (every entry, for the short lists this kernel is given) are fetched
-    // together, LSEs first, then the partial rows, so that the loads overlap; a longer list goes on
-    // one entry at a time
+    // together -- row numbers, then LSEs and partial rows at once, neither waiting for the other --
+    // so that one memory latency covers the whole list; a longer list goes on one entry at a time
     constexpr int kHead = 8;
     size_t row[kHead];
     float l[kHead];
-    float M = -INFINITY;
+    float4 v[kHead];
+#pragma unroll
+    for (int u = 0; u < kHead; ++u) row[u] = b + u < e ? (size_t)mrows[b + u] * q_heads + hd : 0;
 #pragma unroll
     for (int u = 0; u < kHead; ++u) {
-      row[u] = b + u < e ? (size_t)mrows[b + u] * q_heads + hd : 0;
-      l[u] = b + u < e ? lse[row[u]] : -INFINITY;
-      M = fmaxf(M, l[u]);
+      l[u] = -INFINITY;
+      v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (b + u < e) {
+        l[u] = lse[row[u]];
+        v[u] = ((const float4*)part)[row[u] * 32 + c4];
+      }
     }
+    float M = -INFINITY;
+#pragma unroll
+    for (int u = 0; u < kHead; ++u) M = fmaxf(M, l[u]);
     for (int jj = b + kHead; jj < e; ++jj) M = fmaxf(M, lse[(size_t)mrows[jj] * q_heads + hd]);
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
     float wsum = 0.f;
     if (M > -INFINITY) {
-      float4 v[kHead];
-#pragma unroll
-      for (int u = 0; u < kHead; ++u)
-        v[u] = b + u < e ? ((const float4*)part)[row[u] * 32 + c4] : make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
       for (int u = 0; u < kHead; ++u) {
         if (b + u < e) {
@@ -209,6 +213,9 @@ void fill_args(AttnArgs& a, const tl_plan* plan, const PlanDev& d, const void* q
   a.scale = scale;
   a.scale_log2e = scale * 1.4426950408889634f;
   a.k2 = a.v2 = nullptr;
+  a.prior_rows = d.prior_rows;
+  a.prior_out = nullptr;
+  a.prior_lse = nullptr;
   a.final_out = nullptr;
   a.final_lse = nullptr;
   a.final_is_bf16 = 0;
@@ -223,10 +230,13 @@ namespace {
 
 // one-pass rows of a plan whose block sits at `base` on the device
 tl_status fused_rows(const tl_pool* pool, const tl_plan* plan, const void* base, const void* q_dev, const void* k_new_dev,
-                     const void* v_new_dev, float scale, void* out_dev, int32_t out_is_bf16, float* lse_out, hipStream_t st) {
+                     const void* v_new_dev, float scale, const float* prior_partial, const float* prior_lse, void* out_dev,
+                     int32_t out_is_bf16, float* lse_out, hipStream_t st) {
   const PlanDev d = plan_dev(plan, base);
   AttnArgs a;
   fill_args(a, plan, d, q_dev, scale, nullptr, nullptr);
+  a.prior_out = prior_partial;
+  a.prior_lse = prior_lse;
   a.k = (const uint16_t*)pool->k_dev;
   a.v = (const uint16_t*)pool->v_dev;
   a.k2 = (const uint16_t*)k_new_dev;
@@ -272,14 +282,16 @@ tl_status static_scratch(void** out) {
 extern "C" {
 
 tl_status tl_fused_attn_static(const tl_pool* pool, tl_plan* plan, const void* q_dev, const void* k_new_dev,
-                               const void* v_new_dev, float scale, void* out_dev, int32_t out_is_bf16, float* lse_out,
-                               void* stream) {
+                               const void* v_new_dev, float scale, const float* prior_partial, const float* prior_lse,
+                               void* out_dev, int32_t out_is_bf16, float* lse_out, void* stream) {
   if (plan && plan->n_tokens == 0) return TL_OK;
   if (!pool || !plan || !q_dev || !k_new_dev || !v_new_dev || !out_dev) TL_FAIL(TL_EINVAL, "tl_fused_attn_static: null argument");
   tl_status rc = plan_is_current(plan, pool, "tl_fused_attn_static");
   if (rc != TL_OK) return rc;
   if (!(scale > 0.f) || !std::isfinite(scale)) TL_FAIL(TL_EINVAL, "tl_fused_attn_static: scale must be positive and finite");
   if (plan->ftiles.empty()) return TL_OK;
+  if (!plan->prior_rows.empty() && (!prior_partial || !prior_lse))
+    TL_FAIL(TL_EINVAL, "tl_fused_attn_static: the plan has one-pass tails: the partials of tl_segment_attn are needed");
   if (plan->blob_host.size() > kStaticScratchBytes)
     TL_FAIL(TL_EINVAL, "tl_fused_attn_static: the plan's work lists take %zu bytes, the static buffer holds %zu",
             plan->blob_host.size(), kStaticScratchBytes);
@@ -290,7 +302,7 @@ tl_status tl_fused_attn_static(const tl_pool* pool, tl_plan* plan, const void* q
   // the buffer keeps the last call's lists: this call's are copied over them, in stream order
   // (nothing in the buffer has to start at zero)
   TL_HIP(hipMemcpyAsync(base, plan->blob_host.data(), plan->blob_host.size(), hipMemcpyHostToDevice, st));
-  return fused_rows(pool, plan, base, q_dev, k_new_dev, v_new_dev, scale, out_dev, out_is_bf16, lse_out, st);
+  return fused_rows(pool, plan, base, q_dev, k_new_dev, v_new_dev, scale, prior_partial, prior_lse, out_dev, out_is_bf16, lse_out, st);
 }
 
 tl_status tl_segment_attn(const tl_pool* pool, tl_plan* plan, const void* q_dev, float scale, float* out_partial,
@@ -350,18 +362,21 @@ tl_status tl_causal_block(tl_plan* plan, const void* q_dev, const void* k_new_de
 }
 
 tl_status tl_fused_attn(const tl_pool* pool, tl_plan* plan, const void* q_dev, const void* k_new_dev,
-                        const void* v_new_dev, float scale, void* out_dev, int32_t out_is_bf16, float* lse_out,
-                        void* stream) {
+                        const void* v_new_dev, float scale, const float* prior_partial, const float* prior_lse,
+                        void* out_dev, int32_t out_is_bf16, float* lse_out, void* stream) {
   if (plan && plan->n_tokens == 0) return TL_OK;   // a batch without new tokens: nothing to do, buffers may be empty
   if (!pool || !plan || !q_dev || !k_new_dev || !v_new_dev || !out_dev) TL_FAIL(TL_EINVAL, "tl_fused_attn: null argument");
   tl_status rc = plan_is_current(plan, pool, "tl_fused_attn");
   if (rc != TL_OK) return rc;
   if (!(scale > 0.f) || !std::isfinite(scale)) TL_FAIL(TL_EINVAL, "tl_fused_attn: scale must be positive and finite");
   if (plan->ftiles.empty()) return TL_OK;
+  if (!plan->prior_rows.empty() && (!prior_partial || !prior_lse))
+    TL_FAIL(TL_EINVAL, "tl_fused_attn: the plan has one-pass tails: the partials of tl_segment_attn are needed");
   hipStream_t st = (hipStream_t)stream;
   rc = plan_device_ready(plan, st);
   if (rc != TL_OK) return rc;
-  return fused_rows(pool, plan, plan->blob_dev, q_dev, k_new_dev, v_new_dev, scale, out_dev, out_is_bf16, lse_out, st);
+  return fused_rows(pool, plan, plan->blob_dev, q_dev, k_new_dev, v_new_dev, scale, prior_partial, prior_lse, out_dev,
+                    out_is_bf16, lse_out, st);
 }
 
 tl_status tl_merge(tl_plan* plan, const float* out_partial, const float* lse, void* out_dev, int32_t out_is_bf16,

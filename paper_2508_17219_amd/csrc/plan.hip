@@ -41,8 +41,10 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
   if (G > 32) TL_FAIL(TL_EINVAL, "tl_plan_create: q_heads/kv_heads must be at most 32");
   if (split_segments < 0) TL_FAIL(TL_EINVAL, "tl_plan_create: negative split_segments");
   if (compute_units > 4096) TL_FAIL(TL_EINVAL, "tl_plan_create: compute_units above 4096");
-  if ((flags & TL_PLAN_FUSE_ROWS) && !(flags & TL_PLAN_SELF_BLOCK))
-    TL_FAIL(TL_EINVAL, "tl_plan_create: TL_PLAN_FUSE_ROWS needs TL_PLAN_SELF_BLOCK");
+  if ((flags & (TL_PLAN_FUSE_ROWS | TL_PLAN_FUSE_TAILS)) && !(flags & TL_PLAN_SELF_BLOCK))
+    TL_FAIL(TL_EINVAL, "tl_plan_create: TL_PLAN_FUSE_ROWS and TL_PLAN_FUSE_TAILS need TL_PLAN_SELF_BLOCK");
+  if ((flags & TL_PLAN_FUSE_TAILS) && (flags & TL_PLAN_NO_SHARING))
+    TL_FAIL(TL_EINVAL, "tl_plan_create: TL_PLAN_FUSE_TAILS has nothing to do under TL_PLAN_NO_SHARING");
   if (req_row_ptr[0] != 0 || req_seg_ptr[0] != 0) TL_FAIL(TL_EINVAL, "tl_plan_create: offsets must start at 0");
   for (int32_t r = 0; r < n_req; ++r)
     if (req_row_ptr[r + 1] < req_row_ptr[r] || req_seg_ptr[r + 1] < req_seg_ptr[r])
@@ -94,6 +96,16 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
     const int64_t n_cu = compute_units < 0 ? kComputeUnits : compute_units;
     const int32_t min_chunk_slots = std::max(1, 2048 / pool->seg_len);
     std::vector<char> fused(n_req, 0);
+    // A one-pass row tile cannot be cut along its KV: when the whole batch is fewer row-tile
+    // workgroups than the GPU has CUs (one long prompt, say), requests whose slot lists are long
+    // enough to be cut (see below) stay on the three-step path
+    bool small_batch = false;
+    {
+      int64_t wgs = 0;
+      for (int32_t r = 0; r < n_req; ++r)
+        if (ntok_of(r) > 0) wgs += (int64_t)((ntok_of(r) + tok_tile - 1) / tok_tile) * pool->kv_heads;
+      small_batch = wgs < n_cu;
+    }
     if (flags & TL_PLAN_FUSE_ROWS) {
       std::vector<int32_t> users(pool->n_slots, 0), last_user(pool->n_slots, -1);
       for (int32_t r = 0; r < n_req; ++r) {
@@ -106,13 +118,6 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
           }
         }
       }
-      // A one-pass row tile cannot be cut along its KV: when the whole batch is fewer row-tile
-      // workgroups than the GPU has CUs (one long prompt, say), requests whose slot lists are long
-      // enough to be cut (see below) stay on the three-step path
-      int64_t wgs = 0;
-      for (int32_t r = 0; r < n_req; ++r)
-        if (ntok_of(r) > 0) wgs += (int64_t)((ntok_of(r) + tok_tile - 1) / tok_tile) * pool->kv_heads;
-      const bool small_batch = wgs < n_cu;
       for (int32_t r = 0; r < n_req; ++r) {
         const int64_t rows = (int64_t)ntok_of(r) * G;
         if (rows <= kUnitRows) continue;
@@ -238,6 +243,36 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
       return kv_tokens;
     };
 
+    // ---- one-pass tails ---------------------------------------------------------------------
+    // TL_PLAN_FUSE_TAILS: a request with more than a token's worth of rows takes the one-pass kernel
+    // for the end of its list that nobody shares (the run whose only request it is; possibly empty)
+    // and its own new tokens.  The shared runs above stay work items, read once for all their
+    // requesters' rows; their partial rows for this request are listed as `priors`, which the
+    // one-pass kernel's epilogue merges in, so the request needs no causal tile and no tl_merge.
+    std::vector<char> tailed(n_req, 0);
+    std::vector<int32_t> tail_begin(n_req, 0), tail_end(n_req, 0);
+    std::vector<std::vector<int32_t>> priors(n_req);     // per request: partial row of its first token in every shared item
+    std::vector<char> is_tail_item(raw.size(), 0);
+    if (flags & TL_PLAN_FUSE_TAILS) {
+      for (int32_t r = 0; r < n_req; ++r) {
+        if (fused[r] || (int64_t)ntok_of(r) * G <= kUnitRows) continue;
+        tailed[r] = 1;
+        tail_begin[r] = tail_end[r] = len_of(r);
+      }
+      for (size_t i = 0; i < raw.size(); ++i) {
+        const RawItem& it = raw[i];
+        if (it.reqs.size() != 1 || !tailed[it.reqs[0]]) continue;
+        const int32_t r = it.reqs[0];
+        if (small_batch && it.end - it.begin > min_chunk_slots) {    // long enough to be cut along its KV instead
+          tailed[r] = 0;
+          continue;
+        }
+        is_tail_item[i] = 1;
+        tail_begin[r] = it.begin;
+        tail_end[r] = it.end;
+      }
+    }
+
     // ---- final items, work lists ----------------------------------------------------------
     // An item goes to split-K units if it has a token's worth of rows, or if it is a run shared by
     // decode-type requests only (each with a token's worth of rows) that together would not fill
@@ -261,7 +296,9 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
       // chunk (at most 32 slots, at least 512 tokens) that still gives three quarters of a unit per
       // CU, halved if the count then lands between one and one and a half rounds.
       std::vector<std::pair<int64_t, int64_t>> runs;     // (list entries, token groups) of every unit item
-      for (const RawItem& it : raw) {
+      for (size_t i = 0; i < raw.size(); ++i) {
+        const RawItem& it = raw[i];
+        if (is_tail_item[i]) continue;
         int64_t n_tok = 0;
         for (int32_t r : it.reqs) n_tok += ntok_of(r);
         if (unit_item(it, n_tok)) runs.emplace_back(it.end - it.begin, (n_tok + tok_unit - 1) / tok_unit);
@@ -285,7 +322,9 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
     int tile_chunks = 1;
     {
       int64_t wgs = 0;
-      for (const RawItem& it : raw) {
+      for (size_t i = 0; i < raw.size(); ++i) {
+        const RawItem& it = raw[i];
+        if (is_tail_item[i]) continue;
         int64_t n_tok = 0;
         for (int32_t r : it.reqs) n_tok += ntok_of(r);
         if (!unit_item(it, n_tok)) wgs += ((n_tok + tok_tile - 1) / tok_tile) * pool->kv_heads;
@@ -297,7 +336,10 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
     p->item_slot_ptr.push_back(0);
     int64_t prefix_pairs = 0, tile_pairs = 0;
     int32_t n_fused_tokens = 0;
-    for (const RawItem& it : raw) {
+    int64_t item_pairs = 0;
+    for (size_t ri = 0; ri < raw.size(); ++ri) {
+      const RawItem& it = raw[ri];
+      if (is_tail_item[ri]) continue;
       int32_t n_tok = 0;
       for (int32_t r : it.reqs) n_tok += ntok_of(r);
       const bool few_rows = unit_item(it, n_tok);
@@ -315,13 +357,21 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
           int32_t s = slot_at(it.src_req, pos);
           p->item_slots.push_back(s);
           prefix_pairs += (int64_t)n_tok * pool->fill[s];
+          item_pairs += (int64_t)n_tok * pool->fill[s];
+        }
+        {
+          int32_t first = row_cursor;             // partial row of each tailed requester's first token in this item
+          for (int32_t r : it.reqs) {
+            if (tailed[r]) priors[r].push_back(first);
+            first += ntok_of(r);
+          }
         }
         p->item_row_base.push_back(row_cursor);
         p->item_tok_ptr.push_back((int32_t)p->item_tokens.size());
         p->item_slot_ptr.push_back((int32_t)p->item_slots.size());
         if (few_rows) {
           for (int32_t t0 = 0; t0 < n_tok; t0 += tok_unit)
-            p->units.push_back(Work{tok_base + t0, std::min(tok_unit, n_tok - t0), row_cursor + t0, slot_base, c1 - c0, 0, 0, 0, 0});
+            p->units.push_back(Work{tok_base + t0, std::min(tok_unit, n_tok - t0), row_cursor + t0, slot_base, c1 - c0, 0, 0, 0, 0, 0, 0});
         } else {
           // the item's kv tokens as tiles of kKvTile rows (shared by all its row tiles)
           const int32_t full_off = (int32_t)p->tile_base.size();
@@ -333,7 +383,7 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
           // tokens are simply taken tok_tile at a time in item order (Q rows are gathered).
           for (int32_t t0 = 0; t0 < n_tok; t0 += tok_tile)
             p->tiles.push_back(Work{tok_base + t0, std::min(tok_tile, n_tok - t0), row_cursor + t0, slot_base, c1 - c0,
-                                    full_off, n_full, part_off, n_part});
+                                    full_off, n_full, part_off, n_part, 0, 0});
         }
         row_cursor += n_tok;
       }
@@ -353,15 +403,22 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
         const int64_t lq = b - a;
         self_pairs += lq * (lq + 1) / 2;
         int32_t full_off = 0, n_full = 0, part_off = 0, n_part = 0;
-        if (fused[r]) {
-          // the request's whole slot list as tiles of kKvTile rows
+        int32_t prior_off = 0, n_prior = 0;
+        if (fused[r] || tailed[r]) {
+          // the request's whole slot list (one-pass rows) or the private end of it (one-pass tail) as
+          // tiles of kKvTile rows
+          const int32_t p0 = fused[r] ? 0 : tail_begin[r], p1 = fused[r] ? len_of(r) : tail_end[r];
           full_off = (int32_t)p->tile_base.size();
           part_off = (int32_t)p->part_tile.size() / 2;
-          for (int32_t pos = 0; pos < len_of(r); ++pos) prefix_pairs += lq * pool->fill[slot_at(r, pos)];
-          tile_pairs += lq * emit_tiles([&](int32_t pos) { return slot_at(r, pos); }, len_of(r));
+          for (int32_t pos = p0; pos < p1; ++pos) prefix_pairs += lq * pool->fill[slot_at(r, pos)];
+          tile_pairs += lq * emit_tiles([&](int32_t pos) { return slot_at(r, p0 + pos); }, p1 - p0);
           n_full = (int32_t)p->tile_base.size() - full_off;
           n_part = (int32_t)p->part_tile.size() / 2 - part_off;
           n_fused_tokens += (int32_t)lq;
+          prior_off = (int32_t)p->prior_rows.size();
+          n_prior = (int32_t)priors[r].size();
+          p->prior_rows.insert(p->prior_rows.end(), priors[r].begin(), priors[r].end());
+          fused[r] = 1;                   // from here on the two kinds are the same thing
         }
         if (!fused[r] && lq == 1) {      // a single new token sees itself only: no row tile for it
           p->single_tok.push_back(a);
@@ -370,9 +427,9 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
         for (int32_t t0 = a; t0 < b; t0 += tok_tile) {
           const int32_t n = std::min(tok_tile, b - t0);
           if (fused[r])
-            p->ftiles.push_back(Work{ident_base + t0, n, t0, a, t0 + n - a, full_off, n_full, part_off, n_part});
+            p->ftiles.push_back(Work{ident_base + t0, n, t0, a, t0 + n - a, full_off, n_full, part_off, n_part, prior_off, n_prior});
           else
-            p->ctiles.push_back(Work{ident_base + t0, n, self_base + t0, a, t0 + n - a, 0, 0, 0, 0});
+            p->ctiles.push_back(Work{ident_base + t0, n, self_base + t0, a, t0 + n - a, 0, 0, 0, 0, 0, 0});
         }
       }
       row_cursor += T;
@@ -391,13 +448,16 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
                      [](const Work& x, const Work& y) { return x.n_full + x.n_part > y.n_full + y.n_part; });
 
     // ---- merge lists --------------------------------------------------------------------------
-    p->merge_ptr.assign(T + 1, 0);
-    for (int32_t i = 0; i < n_items; ++i)
-      for (int32_t j = p->item_tok_ptr[i]; j < p->item_tok_ptr[i + 1]; ++j) p->merge_ptr[p->item_tokens[j] + 1]++;
+    // (tokens of one-pass requests are in no merge list: a one-pass tail's partial rows in the shared
+    // items are read by the one-pass kernel itself)
     std::vector<char> tok_fused(T, 0);
     for (int32_t r = 0; r < n_req; ++r)
       if (fused[r])
         for (int32_t t = req_row_ptr[r]; t < req_row_ptr[r + 1]; ++t) tok_fused[t] = 1;
+    p->merge_ptr.assign(T + 1, 0);
+    for (int32_t i = 0; i < n_items; ++i)
+      for (int32_t j = p->item_tok_ptr[i]; j < p->item_tok_ptr[i + 1]; ++j)
+        if (!tok_fused[p->item_tokens[j]]) p->merge_ptr[p->item_tokens[j] + 1]++;
     for (int32_t t = 0; t < T; ++t)
       if (!tok_fused[t]) p->merge_tok.push_back(t);
     if (self_base >= 0)
@@ -415,7 +475,7 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
       std::vector<int32_t> cur(p->merge_ptr.begin(), p->merge_ptr.end() - 1);
       for (int32_t i = 0; i < n_items; ++i)
         for (int32_t j = p->item_tok_ptr[i]; j < p->item_tok_ptr[i + 1]; ++j)
-          p->merge_rows[cur[p->item_tokens[j]]++] = p->item_row_base[i] + (j - p->item_tok_ptr[i]);
+          if (!tok_fused[p->item_tokens[j]]) p->merge_rows[cur[p->item_tokens[j]]++] = p->item_row_base[i] + (j - p->item_tok_ptr[i]);
       if (self_base >= 0)
         for (int32_t t = 0; t < T; ++t)
           if (!tok_fused[t]) p->merge_rows[cur[t]++] = self_base + t;
@@ -452,6 +512,8 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
     inf.n_fused_tokens = n_fused_tokens;
     inf.n_single_tokens = (int32_t)p->single_tok.size();
     inf.tile_pairs = tile_pairs;
+    inf.item_pairs = item_pairs;
+    inf.n_prior_rows = (int32_t)p->prior_rows.size();
 
     // ---- one block with everything the kernels read ---------------------------------------------
     {
@@ -476,6 +538,7 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
       o.single_tok = reserve(sizeof(int32_t) * p->single_tok.size());
       o.tile_lm = reserve(sizeof(float) * p->tile_lm.size());
       o.part_lm = reserve(sizeof(float) * p->part_lm.size());
+      o.prior_rows = reserve(sizeof(int32_t) * p->prior_rows.size());
       p->blob_host.assign(total + 256, 0);
       auto fill = [&](size_t at, const void* src, size_t bytes) {
         if (bytes) memcpy(p->blob_host.data() + at, src, bytes);
@@ -494,6 +557,7 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
       fill(o.single_tok, p->single_tok.data(), sizeof(int32_t) * p->single_tok.size());
       fill(o.tile_lm, p->tile_lm.data(), sizeof(float) * p->tile_lm.size());
       fill(o.part_lm, p->part_lm.data(), sizeof(float) * p->part_lm.size());
+      fill(o.prior_rows, p->prior_rows.data(), sizeof(int32_t) * p->prior_rows.size());
     }
   } catch (const std::bad_alloc&) {
     rc = TL_ENOMEM;

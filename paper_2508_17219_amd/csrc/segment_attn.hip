@@ -641,9 +641,44 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
     const float l_tot = xor32_sum(l_run[rg]);
     const float lr_tot = l_tot + xor32_sum(lr_run[rg]);
     if (row_ok[rg]) {
-      const float inv = lr_tot > 0.f ? 1.f / lr_tot : 0.f;
+      float inv = lr_tot > 0.f ? 1.f / lr_tot : 0.f;
       const int head = g * G + head_j[rg];
-      const float lse_val = l_tot > 0.f ? m_ref[rg] * a.scale + __logf(l_tot) : -INFINITY;
+      float lse_val = l_tot > 0.f ? m_ref[rg] * a.scale + __logf(l_tot) : -INFINITY;
+      if (MODE == 2 && wk.n_prior > 0) {
+        // One-pass tail: the row's partials in the work items above it (shared runs, computed by an
+        // earlier launch) are merged in with the rule of the merge kernel,
+        //   M = max LSE_j, w_j = exp(LSE_j - M), O = sum w_j O_j / sum w_j, LSE = M + ln sum w_j,
+        // taken one partial at a time: (M, W, acc) <- (max(M, L), W e^(M-M') + e^(L-M'), acc e^(M-M') + O_j e^(L-M')).
+        // The accumulators are brought to their normalised values first.
+#pragma unroll
+        for (int d = 0; d < 4; ++d)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) o[rg][d][r] *= inv;
+        float M = lse_val, W = lse_val > -INFINITY ? 1.f : 0.f;
+        const int tok_in_req = wk.out_row - wk.kv_off + tok_local[rg];
+        for (int j = 0; j < wk.n_prior; ++j) {
+          const size_t prow = (size_t)(a.prior_rows[wk.prior_off + j] + tok_in_req) * a.q_heads + head;
+          const float L = a.prior_lse[prow];
+          if (!(L > -INFINITY)) continue;              // a partial without keys has weight 0
+          const float Mn = fmaxf(M, L);
+          const float ea = M > -INFINITY ? __expf(M - Mn) : 0.f, eb = __expf(L - Mn);
+          const float* pp = a.prior_out + prow * kHeadDim;
+#pragma unroll
+          for (int d = 0; d < 4; ++d)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+              const float4 x = *(const float4*)&pp[32 * d + 8 * q4 + 4 * h];
+              o[rg][d][4 * q4 + 0] = o[rg][d][4 * q4 + 0] * ea + x.x * eb;
+              o[rg][d][4 * q4 + 1] = o[rg][d][4 * q4 + 1] * ea + x.y * eb;
+              o[rg][d][4 * q4 + 2] = o[rg][d][4 * q4 + 2] * ea + x.z * eb;
+              o[rg][d][4 * q4 + 3] = o[rg][d][4 * q4 + 3] * ea + x.w * eb;
+            }
+          W = W * ea + eb;
+          M = Mn;
+        }
+        inv = W > 0.f ? 1.f / W : 0.f;
+        lse_val = W > 0.f ? M + __logf(W) : -INFINITY;
+      }
       if (MODE == 2) {
         // final output of the token, in the caller's layout and type
         const size_t orow = (size_t)token[rg] * a.q_heads + head;

@@ -49,8 +49,13 @@ constexpr int kComputeUnits = 256;   // MI355X (tl_plan_create's default; the pl
 //               part_tile[] (first kv row, valid tokens) for the tiles cut short by a fill.
 //  causal work: kv_off = first new token of the request, kv_len = new tokens visible to the
 //               last row of the tile; tokens of the tile are consecutive.
+//  one-pass rows: both of the above (tile lists of the request's pool part, new tokens as causal
+//               work; out_row = the tile's first token) and prior_off/n_prior: entries of the plan's
+//               prior_rows[], each the partial row that the request's FIRST new token has in a work
+//               item above it (row of this tile's first token = entry + out_row - kv_off), which the
+//               epilogue merges into the result.
 struct Work {
-  int32_t tok_off, n_tok, out_row, kv_off, kv_len, full_off, n_full, part_off, n_part;
+  int32_t tok_off, n_tok, out_row, kv_off, kv_len, full_off, n_full, part_off, n_part, prior_off, n_prior;
 };
 
 int get_option_vread();
@@ -98,6 +103,7 @@ struct tl_plan {
   std::vector<int32_t> part_tile;  // Work::part_off, pairs (first kv row, valid tokens)
   bool any_repeat = false;              // some work item's list names a slot more than once
   std::vector<float> tile_lm, part_lm;  // log2 of how often the tile's slot is listed (parallel to tile_base / part_tile pairs)
+  std::vector<int32_t> prior_rows;      // Work::prior_off
   uint64_t pool_generation;      // the pool's generation when the plan was built
   int32_t pool_n_slots;
   // Everything the kernels read, laid out once at creation as one block of host memory (each array
@@ -105,7 +111,7 @@ struct tl_plan {
   std::vector<char> blob_host;
   struct {
     size_t tiles, units, ctiles, ftiles, tok, slots, merge_ptr, merge_rows, tile_base, part_tile, merge_tok, single_tok,
-        tile_lm, part_lm;
+        tile_lm, part_lm, prior_rows;
   } off;
   void* blob_dev;                // hipMalloc'd copy of blob_host, or null
 };
@@ -117,6 +123,7 @@ struct PlanDev {
   const Work *tiles, *units, *ctiles, *ftiles;
   const int32_t *tok, *slots, *merge_ptr, *merge_rows, *tile_base, *part_tile, *merge_tok, *single_tok;
   const float *tile_lm, *part_lm;
+  const int32_t* prior_rows;
 };
 inline PlanDev plan_dev(const tl_plan* p, const void* base) {
   const char* b = (const char*)base;
@@ -135,6 +142,7 @@ inline PlanDev plan_dev(const tl_plan* p, const void* base) {
   d.single_tok = (const int32_t*)(b + p->off.single_tok);
   d.tile_lm = (const float*)(b + p->off.tile_lm);
   d.part_lm = (const float*)(b + p->off.part_lm);
+  d.prior_rows = (const int32_t*)(b + p->off.prior_rows);
   return d;
 }
 

@@ -65,7 +65,8 @@ int main() {
       row_ptr.push_back(row_ptr.back() + tok_choices[pick(0, 6)]);
     }
     const int flag_sets[] = {0, TL_PLAN_SELF_BLOCK, TL_PLAN_SELF_BLOCK | TL_PLAN_NO_SHARING,
-                             TL_PLAN_SELF_BLOCK | TL_PLAN_FUSE_ROWS, TL_PLAN_SELF_BLOCK | TL_PLAN_FUSE_ROWS | TL_PLAN_NO_SHARING};
+                             TL_PLAN_SELF_BLOCK | TL_PLAN_FUSE_ROWS, TL_PLAN_SELF_BLOCK | TL_PLAN_FUSE_ROWS | TL_PLAN_NO_SHARING,
+                             TL_PLAN_SELF_BLOCK | TL_PLAN_FUSE_TAILS, TL_PLAN_SELF_BLOCK | TL_PLAN_FUSE_TAILS | TL_PLAN_FUSE_ROWS};
     for (int flags : flag_sets)
       for (int cus : {0, 8, 256})
         for (int dedupe : {0, 1}) {

@@ -155,7 +155,7 @@ def test_a_plan_goes_stale_when_the_pool_changes():
         # fake, never dereferenced pointers; a current plan would get as far as the device, so only
         # the stale answer is asked for here
         rc = lib.tl_segment_attn(pool, plan, FAKE_K, 0.1, FAKE_K, FAKE_V, None)
-        rc2 = lib.tl_fused_attn(pool, plan, FAKE_K, FAKE_K, FAKE_V, 0.1, FAKE_K, 0, None, None)
+        rc2 = lib.tl_fused_attn(pool, plan, FAKE_K, FAKE_K, FAKE_V, 0.1, None, None, FAKE_K, 0, None, None)
         assert rc == rc2 or rc2 == B.TL_OK
         return rc == B.TL_EINVAL and b"pool has changed" in lib.tl_last_error()
 
@@ -174,9 +174,12 @@ def test_a_plan_goes_stale_when_the_pool_changes():
     B.tl_plan_destroy(plan)
 
 
-def _check_plan_covers(b, plan, flags, fused_req=()):
+def _check_plan_covers(b, plan, flags, fused_req=(), tail_req=()):
+    """fused_req: requests taken whole by the one-pass kernel (in no work item); tail_req: requests whose
+    shared runs are work items and whose private end is a one-pass tail (TL_PLAN_FUSE_TAILS): the
+    work items cover a leading part of their lists, and none of their partial rows is in a merge list."""
     info = B.tl_plan_get_info(plan)
-    fused_tok = set(t for r in fused_req for t in range(b.req_row_ptr[r], b.req_row_ptr[r + 1]))
+    fused_tok = set(t for r in tuple(fused_req) + tuple(tail_req) for t in range(b.req_row_ptr[r], b.req_row_ptr[r + 1]))
     ex = B.tl_plan_export(plan)
     slots = B.tl_pool_lookup(plan_pool[0], b.seg_ids)
     T = b.n_tokens
@@ -193,10 +196,25 @@ def _check_plan_covers(b, plan, flags, fused_req=()):
             row = int(ex["item_row_base"][i]) + jpos
             assert row not in rows_seen
             rows_seen.add(row)
+    n_prior = 0
     for r in range(b.n_req):
-        want = sorted(int(s) for s in slots[b.req_seg_ptr[r]:b.req_seg_ptr[r + 1]])
+        mine = [int(s) for s in slots[b.req_seg_ptr[r]:b.req_seg_ptr[r + 1]]]
         for t in range(b.req_row_ptr[r], b.req_row_ptr[r + 1]):
-            assert sorted(got[t]) == ([] if r in fused_req else want), (r, t)
+            if r in tail_req:              # the shared, leading part of the list, whatever its length
+                assert sorted(got[t]) == sorted(mine[:len(got[t])]), (r, t)
+            else:
+                assert sorted(got[t]) == ([] if r in fused_req else sorted(mine)), (r, t)
+    tail_item_rows = set()
+    for i in range(info.n_items):
+        toks = ex["item_tokens"][ex["item_tok_ptr"][i]:ex["item_tok_ptr"][i + 1]]
+        seen_req = set()
+        for jpos, t in enumerate(toks):
+            r = int(np.searchsorted(b.req_row_ptr, int(t), side="right") - 1)
+            if r in tail_req:
+                tail_item_rows.add(int(ex["item_row_base"][i]) + jpos)
+                seen_req.add(r)
+        n_prior += len(seen_req)
+    assert info.n_prior_rows == n_prior
     n_item_rows = len(rows_seen)
     assert rows_seen == set(range(n_item_rows))
     self_rows = T if flags & B.TL_PLAN_SELF_BLOCK else 0
@@ -204,8 +222,9 @@ def _check_plan_covers(b, plan, flags, fused_req=()):
     assert info.self_row_base == (n_item_rows if flags & B.TL_PLAN_SELF_BLOCK else -1)   # also for a batch with no tokens
     # merge lists: every partial row exactly once, under its own token
     mp, mr = ex["merge_ptr"], ex["merge_rows"]
-    assert mp[0] == 0 and mp[-1] == len(mr) == info.n_merge_entries == info.n_partial_rows - len(fused_tok)
-    assert sorted(mr.tolist()) == [x for x in range(info.n_partial_rows) if x - info.self_row_base not in fused_tok]
+    assert mp[0] == 0 and mp[-1] == len(mr) == info.n_merge_entries == info.n_partial_rows - len(fused_tok) - len(tail_item_rows)
+    assert sorted(mr.tolist()) == [x for x in range(info.n_partial_rows)
+                                   if x - info.self_row_base not in fused_tok and x not in tail_item_rows]
     row_tok = {}
     for i in range(info.n_items):
         toks = ex["item_tokens"][ex["item_tok_ptr"][i]:ex["item_tok_ptr"][i + 1]]
@@ -294,6 +313,44 @@ def test_small_batch_of_row_tiles_is_cut_along_its_kv():
                             0, 0)                                                        # switched off: one item
     assert B.tl_plan_get_info(plan).n_items == 1
     B.tl_plan_destroy(plan)
+    B.tl_pool_destroy(plan_pool[0])
+
+
+def test_one_pass_tails_keep_shared_runs_as_work_items():
+    """TL_PLAN_FUSE_TAILS: the shared system prompt stays one work item read once for every session's
+    rows; each session's private history and its new tokens are one-pass rows that merge the session's
+    partial rows of that item in; nothing is left for tl_causal_block or tl_merge."""
+    b = wl.multiturn(turn=3)
+    plan_pool[0] = _pool_for(b)
+    flags = B.TL_PLAN_SELF_BLOCK | B.TL_PLAN_FUSE_TAILS
+    plan = B.tl_plan_create(plan_pool[0], b.q_heads, b.req_row_ptr, b.req_seg_ptr, b.seg_ids, flags)
+    info = _check_plan_covers(b, plan, flags, tail_req=tuple(range(64)))
+    assert info.n_items == 1 and info.n_tiles == 64 * 256 // 64 and info.n_fused_tokens == b.n_tokens
+    assert info.n_prior_rows == 64 and info.n_causal_tiles == 0 and info.n_merge_entries == 0
+    assert info.item_pairs == 64 * 256 * 16 * 256 and info.prefix_pairs == 64 * 256 * (16 + 12) * 256
+    B.tl_plan_destroy(plan)
+    # with TL_PLAN_FUSE_ROWS as well, requests of 512 rows or more are taken whole and leave no work item
+    plan = B.tl_plan_create(plan_pool[0], b.q_heads, b.req_row_ptr, b.req_seg_ptr, b.seg_ids, flags | B.TL_PLAN_FUSE_ROWS)
+    info = _check_plan_covers(b, plan, flags | B.TL_PLAN_FUSE_ROWS, fused_req=tuple(range(64)))
+    assert info.n_items == 0 and info.n_prior_rows == 0
+    B.tl_plan_destroy(plan)
+    B.tl_pool_destroy(plan_pool[0])
+    # short chunks (40 tokens x 4 heads = 160 rows): FUSE_ROWS leaves them on the three steps, FUSE_TAILS takes the tails;
+    # a decode token in the same batch keeps its split-K units and its merge list
+    b = wl.multiturn(turn=2, n_sessions=6, new_tokens=40, seg_len=64, n_slots=512)
+    lens = [40, 40, 1, 40, 0, 40]
+    b.req_row_ptr = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    plan_pool[0] = _pool_for(b)
+    both = B.TL_PLAN_SELF_BLOCK | B.TL_PLAN_FUSE_ROWS | B.TL_PLAN_FUSE_TAILS
+    plan = B.tl_plan_create(plan_pool[0], b.q_heads, b.req_row_ptr, b.req_seg_ptr, b.seg_ids, both)
+    info = _check_plan_covers(b, plan, both, tail_req=(0, 1, 3, 5))
+    assert info.n_fused_tokens == 160 and info.n_single_tokens == 1 and info.n_units > 0 and info.n_causal_tiles == 0
+    B.tl_plan_destroy(plan)
+    with pytest.raises(B.TokenLakeError):
+        B.tl_plan_create(plan_pool[0], b.q_heads, b.req_row_ptr, b.req_seg_ptr, b.seg_ids, B.TL_PLAN_FUSE_TAILS)     # needs the self block
+    with pytest.raises(B.TokenLakeError):
+        B.tl_plan_create(plan_pool[0], b.q_heads, b.req_row_ptr, b.req_seg_ptr, b.seg_ids,
+                         B.TL_PLAN_SELF_BLOCK | B.TL_PLAN_FUSE_TAILS | B.TL_PLAN_NO_SHARING)
     B.tl_pool_destroy(plan_pool[0])
 
 
@@ -589,8 +646,11 @@ def test_random_batches_every_pair_once_under_every_plan_mode():
         plan_pool[0] = _pool_for(b)
         tok_tile = 256 // g
         for flags in (0, B.TL_PLAN_SELF_BLOCK, B.TL_PLAN_SELF_BLOCK | B.TL_PLAN_NO_SHARING,
-                      B.TL_PLAN_SELF_BLOCK | B.TL_PLAN_FUSE_ROWS):
+                      B.TL_PLAN_SELF_BLOCK | B.TL_PLAN_FUSE_ROWS, B.TL_PLAN_SELF_BLOCK | B.TL_PLAN_FUSE_TAILS,
+                      B.TL_PLAN_SELF_BLOCK | B.TL_PLAN_FUSE_ROWS | B.TL_PLAN_FUSE_TAILS):
             for cus in (0, 8, 256):
+                if (flags & B.TL_PLAN_FUSE_TAILS) and cus:
+                    continue                       # (with a CU count a long private run may be cut instead: not predicted here)
                 plan = B.tl_plan_create(plan_pool[0], b.q_heads, b.req_row_ptr, b.req_seg_ptr, b.seg_ids, flags,
                                         int(rng.choice([0, 1, 3])), cus)
                 fused = ()
@@ -608,7 +668,10 @@ def test_random_batches_every_pair_once_under_every_plan_mode():
                                   if ntok[r] * g > 16
                                   and not (wgs < cus and len(lists[r]) > max(1, 2048 // seg_len))
                                   and (ntok[r] * g >= 512 or not any(users[i] > 1 for i in lists[r])))
-                _check_plan_covers(b, plan, flags, fused_req=fused)
+                tails = ()
+                if flags & B.TL_PLAN_FUSE_TAILS:   # every other request with more than a token's worth of rows
+                    tails = tuple(r for r in range(n_req) if ntok[r] * g > 16 and r not in fused)
+                _check_plan_covers(b, plan, flags, fused_req=fused, tail_req=tails)
                 B.tl_plan_destroy(plan)
         B.tl_pool_destroy(plan_pool[0])
 

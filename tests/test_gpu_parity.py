@@ -583,6 +583,65 @@ def test_fused_rows_small_shapes_every_row():
             run.close()
 
 
+def test_one_pass_tails_merge_the_shared_runs_partials_every_row():
+    """TL_PLAN_FUSE_TAILS: shared runs are work items (read once for all their requesters' rows), each
+    request's private end and its new tokens are one-pass rows whose epilogue merges the request's
+    partial rows of those items in.  Every row against the oracle: nested sharing (a run shared by
+    all, a further run shared by two), a request whose whole list is shared (empty tail), one with no
+    prefix, a decode token and a zero-token request in the same batch, ragged fills, fp32 and bf16."""
+    _say("one-pass tails")
+    S, F, T = B.TL_PLAN_SELF_BLOCK, B.TL_PLAN_FUSE_ROWS, B.TL_PLAN_FUSE_TAILS
+    A, Bq, C_, D = 1, 2, 3, 4
+    lists = [[A, Bq, C_, 10, 11], [A, Bq, D, 12], [A, Bq, C_, 13, 14, 15], [A, Bq, C_], [A, Bq, C_], [], [A, 16], [A, Bq, 17]]
+    ntok = [70, 130, 90, 33, 64, 40, 1, 0]
+    ids = sorted(set(x for l in lists for x in l))
+    rng = np.random.default_rng(3)
+    fills = {i: (64 if i in (A, Bq) else int(rng.integers(1, 65))) for i in ids}
+    b = wl.Batch(name="tails", seed=88, q_heads=8, kv_heads=2, seg_len=64, n_slots=32,
+                 req_row_ptr=np.concatenate([[0], np.cumsum(ntok)]).astype(np.int32),
+                 req_seg_ptr=np.concatenate([[0], np.cumsum([len(l) for l in lists])]).astype(np.int32),
+                 seg_ids=np.array([x for l in lists for x in l], dtype=np.uint64), pool_ids=np.array(ids, dtype=np.uint64),
+                 pool_slots=rng.permutation(32)[:len(ids)].astype(np.int32),
+                 pool_fills=np.array([fills[i] for i in ids], dtype=np.int32))
+    for flags in (S | T, S | F | T):
+        for out_bf16 in (False, True):
+            run = H.run_gpu(b, flags=flags, out_bf16=out_bf16, compute_units=0, split_segments=1)
+            i = run.info
+            assert i.n_prior_rows >= 8 and i.n_causal_tiles == 0 and i.n_single_tokens == 1 and i.n_units > 0
+            assert i.n_fused_tokens == sum(ntok) - 1
+            if not out_bf16:
+                _check_all_requests(run)
+            else:
+                want = H.run_gpu(b, flags=flags, compute_units=0, split_segments=1)
+                assert torch.equal(run.out, want.out.to(torch.bfloat16)) and torch.equal(run.lse, want.lse)
+                want.close()
+            run.close()
+    # the same batch through the plain three steps gives the same result to rounding
+    a3 = H.run_gpu(b, flags=S, compute_units=0)
+    at = H.run_gpu(b, flags=S | T, compute_units=0)
+    assert (a3.out - at.out).abs().max().item() <= 2e-3 and (a3.lse - at.lse).abs().max().item() <= 1e-4
+    a3.close(); at.close()
+    # peaked and offset values, and scores far from the first block's range, through the tails
+    for kw in [dict(k_gain=4.0, v_offset_mod=7), dict(k_boost=(2, 1 << 30, 32.0), v_offset_mod=7)]:
+        pb = wl.prefill(seed=23, n_req=3, new_tokens=100, lo=700, hi=1100, seg_len=128, n_slots=48, n_shared=2, **kw)
+        run = H.run_gpu(pb, flags=S | T, compute_units=0)
+        assert run.info.n_prior_rows == 3 and run.info.n_fused_tokens == 300
+        _check_all_requests(run)
+        run.close()
+
+
+def test_full_multiturn_config_with_one_pass_tails():
+    """Turn 7 of the multi-turn workload as the benchmark spec words it: the shared prompt's 16 segments are
+    read once against all 16384 query tokens (one work item), each session's history and new tokens
+    go through the one-pass kernel, which merges the session's partial rows in."""
+    _say("full multi-turn, one-pass tails")
+    b = wl.multiturn(turn=7)
+    run = H.run_gpu(b, flags=B.TL_PLAN_SELF_BLOCK | B.TL_PLAN_FUSE_TAILS)
+    assert run.info.n_items == 1 and run.info.n_prior_rows == 64 and run.info.n_merge_entries == 0
+    _check_every_request(run, rows_per_req=2, seed=9, full_heads={0, 63})
+    run.close()
+
+
 def test_only_short_segments_no_full_tile_anywhere():
     """Every segment holds fewer than 64 tokens, so no pool tile is full: the pipelined path never
     runs on the pool (only on the new tokens of the one-pass rows), the masked path does all of it."""
@@ -1108,7 +1167,8 @@ def test_random_batches_against_the_oracle():
                      pool_ids=np.array(ids, dtype=np.uint64),
                      pool_slots=rng.permutation(32)[:len(ids)].astype(np.int32),
                      pool_fills=np.array([fills[i] for i in ids], dtype=np.int32))
-        for kw in (dict(), dict(fuse=True), dict(flags=B.TL_PLAN_SELF_BLOCK | B.TL_PLAN_NO_SHARING, split_segments=1)):
+        for kw in (dict(), dict(fuse=True), dict(flags=B.TL_PLAN_SELF_BLOCK | B.TL_PLAN_NO_SHARING, split_segments=1),
+                   dict(flags=B.TL_PLAN_SELF_BLOCK | B.TL_PLAN_FUSE_TAILS, compute_units=0)):
             run = H.run_gpu(b, **kw)
             _check_all_requests(run)
             run.close()

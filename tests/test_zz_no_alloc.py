@@ -57,7 +57,7 @@ def test_static_buffer_variant_refuses_lists_beyond_its_buffer():
     plan = B.tl_plan_create(pool, 8, row_ptr, seg_ptr, np.tile(ids, n_req), B.TL_PLAN_SELF_BLOCK | B.TL_PLAN_FUSE_ROWS)
     assert B.tl_plan_get_info(plan).n_fused_tokens == n_req * 64
     lib = B.load_library()
-    rc = lib.tl_fused_attn_static(pool, plan, FAKE_K, FAKE_K, FAKE_V, 0.1, FAKE_K, 0, None, None)
+    rc = lib.tl_fused_attn_static(pool, plan, FAKE_K, FAKE_K, FAKE_V, 0.1, None, None, FAKE_K, 0, None, None)
     assert rc == B.TL_EINVAL and b"static buffer holds" in lib.tl_last_error()
     B.tl_plan_destroy(plan)
     B.tl_pool_destroy(pool)

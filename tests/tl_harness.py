@@ -83,8 +83,8 @@ def run_gpu(batch: wl.Batch, flags=None, split_segments: int = 0, out_bf16: bool
     if flags & B.TL_PLAN_SELF_BLOCK:
         B.tl_causal_block(plan, q, kn, vn, batch.scale, outp, lsep)
     B.tl_merge(plan, outp, lsep, out, out_bf16, lse)
-    if flags & B.TL_PLAN_FUSE_ROWS:
-        B.tl_fused_attn(pool, plan, q, kn, vn, batch.scale, out, out_bf16, lse)
+    if flags & (B.TL_PLAN_FUSE_ROWS | B.TL_PLAN_FUSE_TAILS):
+        B.tl_fused_attn(pool, plan, q, kn, vn, batch.scale, out, out_bf16, lse, prior_partial=outp, prior_lse=lsep)
     torch.cuda.synchronize()
     return DeviceRun(batch, pool, plan, info, q, kn, vn, pk, pv, outp, lsep, out, lse)
 
