@@ -92,7 +92,7 @@ def run_workload(batch, steps, warmup, torch, B, split_segments=0, fuse=True, ex
     # In the timed region only the dominant call is bracketed by HIP events (every event is a marker
     # in the stream and costs the GPU a few microseconds); the other calls are timed in a short loop
     # of their own afterwards.
-    all_fused = info.n_fused_tokens == info.n_tokens and info.n_tokens > 0
+    all_fused = info.n_fused_tokens == info.n_tokens and info.n_tokens > 0 and info.n_items == 0
     dom = 3 if all_fused else 0           # index of the dominant call: tl_fused_attn or tl_segment_attn
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(steps)]
 
@@ -303,22 +303,34 @@ def algorithmic_work(batch, info):
 
 
 def three_step_report(b, r, w):
-    """Per-kernel times and roofline fractions of a plan without one-pass rows: tl_segment_attn
-    (row tiles over the pool work items), tl_causal_block (row tiles over the new tokens), tl_merge."""
+    """Per-kernel times and roofline fractions of a plan that keeps shared runs as work items:
+    tl_segment_attn (row tiles over the pool work items), then either tl_causal_block + tl_merge
+    (plain three steps) or tl_fused_attn over each request's private end and new tokens, merging the
+    work items' partials in (TL_PLAN_FUSE_TAILS)."""
     info = r["info"]
     hq, d = b.q_heads, b.head_dim
-    merge_bytes = info["n_merge_entries"] * hq * (d + 1) * 4.0 + info["n_tokens"] * hq * (2.0 * d + 4.0)
-    seg = w["flops_prefix"] / (r["segment_attn_ms"] * 1e-3) / 1e12
-    cau = w["flops_self"] / (r["causal_block_ms"] * 1e-3) / 1e12
-    mer = merge_bytes / (r["merge_ms"] * 1e-3) / 1e9
-    return {"ms_per_step": r["ms_per_step"], "merged_tok_s": b.n_tokens / (r["ms_per_step"] * 1e-3),
-            "work_items": info["n_items"], "row_tiles": info["n_tiles"], "causal_tiles": info["n_causal_tiles"],
-            "segment_attn": {"ms": r["segment_attn_ms"], "bound": "mfma", "achieved": seg, "unit": "TFLOP/s",
-                             "frac": seg / PEAK_BF16_TFLOPS},
-            "causal_block": {"ms": r["causal_block_ms"], "bound": "mfma", "achieved": cau, "unit": "TFLOP/s",
-                             "frac": cau / PEAK_BF16_TFLOPS},
-            "merge": {"ms": r["merge_ms"], "bound": "hbm", "achieved": mer, "unit": "GB/s", "frac": mer / PEAK_HBM_GBS,
-                      "algorithmic_bytes": merge_bytes}}
+    item_flops = 4.0 * hq * d * info["item_pairs"]
+    seg = item_flops / (r["segment_attn_ms"] * 1e-3) / 1e12
+    out = {"ms_per_step": r["ms_per_step"], "merged_tok_s": b.n_tokens / (r["ms_per_step"] * 1e-3),
+           "work_items": info["n_items"], "row_tiles": info["n_tiles"], "causal_tiles": info["n_causal_tiles"],
+           "one_pass_tiles": info["n_fused_tiles"], "prior_rows_merged_in_kernel": info["n_prior_rows"],
+           "segment_attn": {"ms": r["segment_attn_ms"], "bound": "mfma", "achieved": seg, "unit": "TFLOP/s",
+                            "frac": seg / PEAK_BF16_TFLOPS}}
+    if info["n_causal_tiles"] > 0:
+        cau = w["flops_self"] / (r["causal_block_ms"] * 1e-3) / 1e12
+        out["causal_block"] = {"ms": r["causal_block_ms"], "bound": "mfma", "achieved": cau, "unit": "TFLOP/s",
+                               "frac": cau / PEAK_BF16_TFLOPS}
+    if info["n_merge_entries"] > 0:
+        merge_bytes = info["n_merge_entries"] * hq * (d + 1) * 4.0 + info["n_tokens"] * hq * (2.0 * d + 4.0)
+        mer = merge_bytes / (r["merge_ms"] * 1e-3) / 1e9
+        out["merge"] = {"ms": r["merge_ms"], "bound": "hbm", "achieved": mer, "unit": "GB/s", "frac": mer / PEAK_HBM_GBS,
+                        "algorithmic_bytes": merge_bytes}
+    if info["n_fused_tiles"] > 0:
+        fl = w["flops_prefix"] - item_flops + w["flops_self"]
+        fu = fl / (r["fused_attn_ms"] * 1e-3) / 1e12
+        out["fused_attn"] = {"ms": r["fused_attn_ms"], "bound": "mfma", "achieved": fu, "unit": "TFLOP/s",
+                             "frac": fu / PEAK_BF16_TFLOPS}
+    return out
 
 
 def cpu_baseline(batch, budget_s=15.0):
@@ -381,6 +393,9 @@ def main():
     ap.add_argument("--no-sharing", action="store_true", help="plan with TL_PLAN_NO_SHARING (one item chain per request)")
     ap.add_argument("--three-step", action="store_true",
                     help="plan without TL_PLAN_FUSE_ROWS: every request goes through partials and the merge")
+    ap.add_argument("--tails", action="store_true",
+                    help="plan with TL_PLAN_FUSE_TAILS alone: shared runs as work items read once, private ends and new "
+                         "tokens in one pass that merges the shared runs' partials in")
     ap.add_argument("--no-decode", action="store_true", help="skip the appended decode measurement")
     ap.add_argument("--no-extra", action="store_true",
                     help="skip the appended short measurements (three-step plan, other named workloads, MFMA-only rate)")
@@ -448,8 +463,9 @@ def main():
     batch = maker()
     if args.workload == "decode" and decode_kw:
         batch.name = "decode[%s]" % ", ".join("%s=%d" % kv for kv in sorted(decode_kw.items()))
-    res = run_workload(batch, args.steps, args.warmup, torch, B, args.split_segments, fuse=not args.three_step,
-                       extra_flags=B.TL_PLAN_NO_SHARING if args.no_sharing else 0, graph=args.graph)
+    res = run_workload(batch, args.steps, args.warmup, torch, B, args.split_segments, fuse=not (args.three_step or args.tails),
+                       extra_flags=(B.TL_PLAN_NO_SHARING if args.no_sharing else 0) | (B.TL_PLAN_FUSE_TAILS if args.tails else 0),
+                       graph=args.graph)
     work = algorithmic_work(batch, res["info"])
     tok_s = batch.n_tokens / (res["ms_per_step"] * 1e-3)
 
@@ -462,7 +478,7 @@ def main():
                     "unit": "GB/s", "frac": ach / PEAK_HBM_GBS,
                     "traffic": measured_traffic("splitk_unit_attn_kernel", b.name),
                     "algorithmic_bytes": by, "avg_kernel_ms": r["segment_attn_ms"]}
-        if r["info"]["n_fused_tokens"] == r["info"]["n_tokens"]:
+        if r["info"]["n_fused_tokens"] == r["info"]["n_tokens"] and r["info"]["n_items"] == 0:
             # every request takes the one-pass kernel: pool tiles and causal block in one launch
             fl = w["flops_prefix"] + w["flops_self"]
             ach = fl / (r["fused_attn_ms"] * 1e-3) / 1e12
@@ -474,12 +490,12 @@ def main():
                     "executed_flops": w["flops_tiles"] + w["flops_self"],
                     "executed_tflops": (w["flops_tiles"] + w["flops_self"]) / (r["fused_attn_ms"] * 1e-3) / 1e12,
                     "avg_kernel_ms": r["fused_attn_ms"]}
-        ach = w["flops_prefix"] / seg_s / 1e12
+        item_flops = 4.0 * b.q_heads * b.head_dim * r["info"]["item_pairs"]      # the work items' share of the prefix flops
+        ach = item_flops / seg_s / 1e12
         return {"kernel": "row_tile_attn_kernel", "bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS,
                 "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS,
                 "traffic": measured_traffic("row_tile_attn_kernel", b.name),
-                "algorithmic_flops": w["flops_prefix"], "executed_flops": w["flops_tiles"],
-                "executed_tflops": w["flops_tiles"] / seg_s / 1e12, "avg_kernel_ms": r["segment_attn_ms"]}
+                "algorithmic_flops": item_flops, "avg_kernel_ms": r["segment_attn_ms"]}
 
     line = {
         "metric": "merged tok/s (one layer: attention over the segment pool + causal self block, partials merged)",
@@ -513,16 +529,27 @@ def main():
         side_steps = max(5, min(args.steps, 20))
         r3 = run_workload(batch, side_steps, 3, torch, B, args.split_segments, fuse=False)
         line["three_step"] = three_step_report(batch, r3, algorithmic_work(batch, r3["info"]))
+        # hot segments read once for all their requesters' rows, private ends and new tokens in one pass
+        # that merges the shared runs' partials in (TL_PLAN_FUSE_TAILS): this workload and multi-turn turn 7
+        line["shared_runs_once"] = []
+        for sb in (batch, wl.multiturn(turn=7)):
+            rt = run_workload(sb, side_steps, 3, torch, B, args.split_segments, fuse=False, extra_flags=B.TL_PLAN_FUSE_TAILS)
+            rep_ = three_step_report(sb, rt, algorithmic_work(sb, rt["info"]))
+            rep_["workload"] = sb.name
+            line["shared_runs_once"].append(rep_)
         # the other named workloads, short runs, default plan
         line["configs"] = []
         for mk in (wl.tiny, wl.longctx, lambda: wl.multiturn(turn=0), lambda: wl.multiturn(turn=7)):
             ob = mk()
             orr = run_workload(ob, side_steps, 3, torch, B, args.split_segments, fuse=True)
             orl = roofline_for(ob, orr, algorithmic_work(ob, orr["info"]))
+            # `achieved` counts flops per list entry (what the method asks for); `frac` is what the matrix
+            # unit was given (a slot that a list names m times is walked once, weighted) over the peak
+            ex_t = orl.get("executed_tflops", orl["achieved"])
             line["configs"].append({"workload": ob.name, "new_tokens": ob.n_tokens, "ms_per_step": orr["ms_per_step"],
                                     "merged_tok_s": ob.n_tokens / (orr["ms_per_step"] * 1e-3), "kernel": orl["kernel"],
-                                    "achieved": orl["achieved"], "unit": orl["unit"], "frac": orl["frac"],
-                                    "steps": side_steps})
+                                    "achieved": orl["achieved"], "executed": ex_t, "unit": orl["unit"],
+                                    "frac": ex_t / orl["peak"], "steps": side_steps})
     if args.workload != "decode" and not args.no_decode:
         db = wl.decode()
         dres = run_workload(db, max(3, args.steps // 4), 1, torch, B, args.split_segments, fuse=not args.three_step)

@@ -34,7 +34,8 @@ struct AttnArgs {
   const int32_t* fill;    // per-slot valid tokens (pool work)
   const Work* work;
   const int32_t* tok;     // token index lists
-  const int32_t* slots;   // slot lists (pool work)
+  const int32_t* slots;   // slot lists of the split-K units
+  const float* slot_lm;   // log2(times the unit's run lists the slot), parallel to slots; null = all once
   const int32_t* tile_base;  // first kv row of each full 64-token tile (pool row tiles)
   const int32_t* part_tile;  // (first kv row, valid tokens) of each cut-short tile
   const float* tile_lm;      // log2(times the tile's slot is listed), parallel to tile_base

@@ -88,8 +88,10 @@ __global__ __launch_bounds__(kThreads) void splitk_unit_attn_kernel(const AttnAr
   };
 
   // tile cursor over the unit's slots (uniform across the workgroup)
+  // (a slot that the unit's run lists m times is walked once; its keys weigh m: lm = log2 m is
+  // added to the exponent of the tile's probabilities)
   int li = 0, kk = 0;
-  auto next_tile = [&](int& base, int& valid) -> bool {
+  auto next_tile = [&](int& base, int& valid, float& lm) -> bool {
     while (li < wk.kv_len) {
       const int slot = a.slots[wk.kv_off + li];
       const int f = a.fill[slot];
@@ -97,6 +99,7 @@ __global__ __launch_bounds__(kThreads) void splitk_unit_attn_kernel(const AttnAr
       if (off < f) {
         base = slot * a.seg_len + off;
         valid = min(kTok, f - off);
+        lm = a.slot_lm ? a.slot_lm[wk.kv_off + li] : 0.f;
         kk++;
         if (kk * kTok >= f) { li++; kk = 0; }
         return true;
@@ -108,13 +111,15 @@ __global__ __launch_bounds__(kThreads) void splitk_unit_attn_kernel(const AttnAr
   };
 
   int base = 0, valid = 0;
-  bool have = next_tile(base, valid);
+  float lm = 0.f;
+  bool have = next_tile(base, valid, lm);
   if (have) gload(base, valid);
 
   while (have) {
     lstore();
     int nbase = 0, nvalid = 0;
-    const bool have_next = next_tile(nbase, nvalid);
+    float nlm = 0.f;
+    const bool have_next = next_tile(nbase, nvalid, nlm);
     if (have_next) gload(nbase, nvalid);
     TL_UNIT_SYNC();
 
@@ -142,7 +147,7 @@ __global__ __launch_bounds__(kThreads) void splitk_unit_attn_kernel(const AttnAr
       const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
       const float alpha = fast_exp2((m_run - m_use) * c);
       m_run = m_new;
-      const float mc = m_use * c;
+      const float mc = m_use * c - lm;
       float lsum = 0.f;
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
@@ -182,6 +187,7 @@ __global__ __launch_bounds__(kThreads) void splitk_unit_attn_kernel(const AttnAr
     have = have_next;
     base = nbase;
     valid = nvalid;
+    lm = nlm;
   }
 
   float l_tot = l_run + __shfl_xor(l_run, 16);

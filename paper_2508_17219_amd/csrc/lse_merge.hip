@@ -201,6 +201,7 @@ void fill_args(AttnArgs& a, const tl_plan* plan, const PlanDev& d, const void* q
   a.q = (const uint16_t*)q;
   a.tok = d.tok;
   a.slots = d.slots;
+  a.slot_lm = plan->any_unit_repeat ? d.unit_lm : nullptr;
   a.tile_base = d.tile_base;
   a.part_tile = d.part_tile;
   a.tile_lm = plan->any_repeat ? d.tile_lm : nullptr;   // null: every tile has multiplicity 1

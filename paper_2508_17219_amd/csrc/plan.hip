@@ -343,7 +343,27 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
       int32_t n_tok = 0;
       for (int32_t r : it.reqs) n_tok += ntok_of(r);
       const bool few_rows = unit_item(it, n_tok);
-      const int32_t run = it.end - it.begin;
+      // The run's slots, each with the number of times the run lists it.  Split-K units walk a slot
+      // that is listed m times once, with weight m, like the row tiles (reading 8 of the paper's
+      // silence on repeated segments: a list is a multiset); row-tile items dedupe in emit_tiles,
+      // so for them every list position stays an entry of its own here.
+      std::vector<std::pair<int32_t, int32_t>> run_slots;
+      {
+        const int32_t n_pos = it.end - it.begin;
+        if (few_rows && dedupe) {
+          for (int32_t pos = it.begin; pos < it.end; ++pos) mult_of[slot_at(it.src_req, pos)]++;
+          for (int32_t pos = it.begin; pos < it.end; ++pos) {
+            const int32_t sl = slot_at(it.src_req, pos);
+            if (mult_of[sl] == 0) continue;
+            run_slots.emplace_back(sl, mult_of[sl]);
+            mult_of[sl] = 0;
+          }
+        } else {
+          run_slots.reserve(n_pos);
+          for (int32_t pos = it.begin; pos < it.end; ++pos) run_slots.emplace_back(slot_at(it.src_req, pos), 1);
+        }
+      }
+      const int32_t run = (int32_t)run_slots.size();
       const int32_t step = few_rows ? split
                            : tile_chunks > 1 ? std::max(min_chunk_slots, (run + tile_chunks - 1) / tile_chunks)
                                              : run;
@@ -353,11 +373,17 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
         for (int32_t r : it.reqs)
           for (int32_t t = req_row_ptr[r]; t < req_row_ptr[r + 1]; ++t) p->item_tokens.push_back(t);
         const int32_t slot_base = (int32_t)p->item_slots.size();
-        for (int32_t pos = it.begin + c0; pos < it.begin + c1; ++pos) {
-          int32_t s = slot_at(it.src_req, pos);
-          p->item_slots.push_back(s);
-          prefix_pairs += (int64_t)n_tok * pool->fill[s];
-          item_pairs += (int64_t)n_tok * pool->fill[s];
+        const int32_t unit_base = (int32_t)p->unit_slots.size();
+        for (int32_t u = c0; u < c1; ++u) {
+          const int32_t sl = run_slots[u].first, m = run_slots[u].second;
+          for (int32_t k = 0; k < m; ++k) p->item_slots.push_back(sl);       // the item's list keeps every occurrence
+          prefix_pairs += (int64_t)m * n_tok * pool->fill[sl];
+          item_pairs += (int64_t)m * n_tok * pool->fill[sl];
+          if (few_rows) {
+            p->unit_slots.push_back(sl);
+            p->unit_lm.push_back(log2f((float)m));
+            if (m > 1) p->any_unit_repeat = true;
+          }
         }
         {
           int32_t first = row_cursor;             // partial row of each tailed requester's first token in this item
@@ -371,18 +397,19 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
         p->item_slot_ptr.push_back((int32_t)p->item_slots.size());
         if (few_rows) {
           for (int32_t t0 = 0; t0 < n_tok; t0 += tok_unit)
-            p->units.push_back(Work{tok_base + t0, std::min(tok_unit, n_tok - t0), row_cursor + t0, slot_base, c1 - c0, 0, 0, 0, 0, 0, 0});
+            p->units.push_back(Work{tok_base + t0, std::min(tok_unit, n_tok - t0), row_cursor + t0, unit_base, c1 - c0, 0, 0, 0, 0, 0, 0});
         } else {
           // the item's kv tokens as tiles of kKvTile rows (shared by all its row tiles)
           const int32_t full_off = (int32_t)p->tile_base.size();
           const int32_t part_off = (int32_t)p->part_tile.size() / 2;
-          tile_pairs += (int64_t)n_tok * emit_tiles([&](int32_t pos) { return p->item_slots[slot_base + pos]; }, c1 - c0);
+          tile_pairs += (int64_t)n_tok * emit_tiles([&](int32_t pos) { return p->item_slots[slot_base + pos]; },
+                                                    (int32_t)p->item_slots.size() - slot_base);
           const int32_t n_full = (int32_t)p->tile_base.size() - full_off;
           const int32_t n_part = (int32_t)p->part_tile.size() / 2 - part_off;
           // row tiles never straddle two requests' token ranges unless ranges are short:
           // tokens are simply taken tok_tile at a time in item order (Q rows are gathered).
           for (int32_t t0 = 0; t0 < n_tok; t0 += tok_tile)
-            p->tiles.push_back(Work{tok_base + t0, std::min(tok_tile, n_tok - t0), row_cursor + t0, slot_base, c1 - c0,
+            p->tiles.push_back(Work{tok_base + t0, std::min(tok_tile, n_tok - t0), row_cursor + t0, slot_base, (int32_t)p->item_slots.size() - slot_base,
                                     full_off, n_full, part_off, n_part, 0, 0});
         }
         row_cursor += n_tok;
@@ -529,7 +556,8 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
       o.ctiles = reserve(sizeof(Work) * p->ctiles.size());
       o.ftiles = reserve(sizeof(Work) * p->ftiles.size());
       o.tok = reserve(sizeof(int32_t) * p->tok.size());
-      o.slots = reserve(sizeof(int32_t) * p->item_slots.size());
+      o.slots = reserve(sizeof(int32_t) * p->unit_slots.size());
+      o.unit_lm = reserve(sizeof(float) * p->unit_lm.size());
       o.merge_ptr = reserve(sizeof(int32_t) * p->merge_ptr.size());
       o.merge_rows = reserve(sizeof(int32_t) * p->merge_rows.size());
       o.tile_base = reserve(sizeof(int32_t) * p->tile_base.size());
@@ -548,7 +576,8 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
       fill(o.ctiles, p->ctiles.data(), sizeof(Work) * p->ctiles.size());
       fill(o.ftiles, p->ftiles.data(), sizeof(Work) * p->ftiles.size());
       fill(o.tok, p->tok.data(), sizeof(int32_t) * p->tok.size());
-      fill(o.slots, p->item_slots.data(), sizeof(int32_t) * p->item_slots.size());
+      fill(o.slots, p->unit_slots.data(), sizeof(int32_t) * p->unit_slots.size());
+      fill(o.unit_lm, p->unit_lm.data(), sizeof(float) * p->unit_lm.size());
       fill(o.merge_ptr, p->merge_ptr.data(), sizeof(int32_t) * p->merge_ptr.size());
       fill(o.merge_rows, p->merge_rows.data(), sizeof(int32_t) * p->merge_rows.size());
       fill(o.tile_base, p->tile_base.data(), sizeof(int32_t) * p->tile_base.size());

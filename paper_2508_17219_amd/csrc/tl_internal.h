@@ -43,8 +43,8 @@ constexpr int kComputeUnits = 256;   // MI355X (tl_plan_create's default; the pl
 
 // One unit of kernel work.  Its query tokens are tok[tok_off .. tok_off+n_tok) (batch token
 // indices), its partial rows out_row .. out_row+n_tok-1.
-//  pool work:   kv_off/kv_len index the plan's slot-list array; for row tiles the item's kv
-//               tokens are also listed as tiles of 64: full_off/n_full index tile_base[]
+//  pool work:   split-K units: kv_off/kv_len index the plan's unit slot list (with unit_lm[]);
+//               row tiles: the item's kv tokens are listed as tiles of 64: full_off/n_full index tile_base[]
 //               (first kv row of each completely filled tile), part_off/n_part index
 //               part_tile[] (first kv row, valid tokens) for the tiles cut short by a fill.
 //  causal work: kv_off = first new token of the request, kv_len = new tokens visible to the
@@ -104,6 +104,9 @@ struct tl_plan {
   bool any_repeat = false;              // some work item's list names a slot more than once
   std::vector<float> tile_lm, part_lm;  // log2 of how often the tile's slot is listed (parallel to tile_base / part_tile pairs)
   std::vector<int32_t> prior_rows;      // Work::prior_off
+  std::vector<int32_t> unit_slots;      // split-K units: Work::kv_off/kv_len, each distinct slot of a chunk once ...
+  std::vector<float> unit_lm;           // ... with log2 of the number of times the run lists it
+  bool any_unit_repeat = false;
   uint64_t pool_generation;      // the pool's generation when the plan was built
   int32_t pool_n_slots;
   // Everything the kernels read, laid out once at creation as one block of host memory (each array
@@ -111,7 +114,7 @@ struct tl_plan {
   std::vector<char> blob_host;
   struct {
     size_t tiles, units, ctiles, ftiles, tok, slots, merge_ptr, merge_rows, tile_base, part_tile, merge_tok, single_tok,
-        tile_lm, part_lm, prior_rows;
+        tile_lm, part_lm, prior_rows, unit_lm;
   } off;
   void* blob_dev;                // hipMalloc'd copy of blob_host, or null
 };
@@ -124,6 +127,7 @@ struct PlanDev {
   const int32_t *tok, *slots, *merge_ptr, *merge_rows, *tile_base, *part_tile, *merge_tok, *single_tok;
   const float *tile_lm, *part_lm;
   const int32_t* prior_rows;
+  const float* unit_lm;
 };
 inline PlanDev plan_dev(const tl_plan* p, const void* base) {
   const char* b = (const char*)base;
@@ -143,6 +147,7 @@ inline PlanDev plan_dev(const tl_plan* p, const void* base) {
   d.tile_lm = (const float*)(b + p->off.tile_lm);
   d.part_lm = (const float*)(b + p->off.part_lm);
   d.prior_rows = (const int32_t*)(b + p->off.prior_rows);
+  d.unit_lm = (const float*)(b + p->off.unit_lm);
   return d;
 }
 

@@ -515,6 +515,29 @@ def test_repeated_segments_walked_once_with_their_multiplicity():
         runs[0].close(); runs[1].close()
 
 
+def test_repeated_segments_in_split_k_units_are_walked_once():
+    """Decode tokens over lists that name segments several times: a split-K unit walks each distinct
+    slot of its run once, with the multiplicity as weight (the run is deduplicated before it is cut
+    into chunks); with TL_PLAN_WALK_REPEATS every occurrence is walked.  Both against the oracle,
+    which concatenates the list as it stands, and against each other; ragged fills."""
+    _say("repeated segments, split-K units")
+    b = wl.longctx(seed=78, n_req=6, entries=50, new_tokens=1, seg_len=128, n_ids=9, n_slots=16, hq=16, hkv=2)
+    fills = b.pool_fills.copy()
+    fills[::2] = 45
+    b.pool_fills = fills
+    for split in (0, 2):
+        runs = {}
+        for dedupe in (1, 0):
+            flags = B.TL_PLAN_SELF_BLOCK | (0 if dedupe else B.TL_PLAN_WALK_REPEATS)
+            runs[dedupe] = H.run_gpu(b, flags=flags, split_segments=split)
+            assert runs[dedupe].info.n_units > 0 and runs[dedupe].info.n_tiles == 0
+            _check_all_requests(runs[dedupe])
+        assert runs[1].info.n_units < runs[0].info.n_units or split == 0       # 9 distinct slots instead of 50 entries
+        assert runs[1].info.prefix_pairs == runs[0].info.prefix_pairs
+        assert (runs[1].out - runs[0].out).abs().max().item() <= 8e-3 and (runs[1].lse - runs[0].lse).abs().max().item() <= 1e-4
+        runs[0].close(); runs[1].close()
+
+
 @pytest.mark.parametrize("turn", range(8))
 def test_full_multiturn_config_every_session(turn):
     """Every session of every turn, three-step plan (the shared prompt as one work item read once
