@@ -21,54 +21,44 @@ namespace {
 //   M = max_j LSE_j;  w_j = exp(LSE_j - M);  O = sum w_j O_j / sum w_j;  LSE = M + ln sum w_j
 template <bool OUT_BF16>
 __global__ __launch_bounds__(256) void lse_merge_kernel(const float* __restrict__ part, const float* __restrict__ lse,
-                                                        const int32_t* __restrict__ mptr,
-                                                        const int32_t* __restrict__ mrows,
-                                                        const int32_t* __restrict__ mtok, void* __restrict__ out,
+                                                        const int32_t* __restrict__ mfix, void* __restrict__ out,
                                                         float* __restrict__ lse_out, int q_heads) {
-  const int t = mtok[blockIdx.x];
-  const int b = mptr[t], e = mptr[t + 1];
+  // the token's record: {token, partial rows..., -1 ...}; the same for every lane, one load
+  int32_t rec[kMergeFixInts];
+#pragma unroll
+  for (int u = 0; u < kMergeFixInts; ++u) rec[u] = mfix[(size_t)blockIdx.x * kMergeFixInts + u];
+  const int t = rec[0];
   const int idx = blockIdx.y * blockDim.x + threadIdx.x;
   if (idx < q_heads * 32) {
     const int hd = idx >> 5, c4 = idx & 31;
-    // the first kHead entries (every entry, for the short lists this kernel is given) are fetched
-    // together -- row numbers, then LSEs and partial rows at once, neither waiting for the other --
-    // so that one memory latency covers the whole list; a longer list goes on one entry at a time
-    constexpr int kHead = 8;
-    size_t row[kHead];
-    float l[kHead];
-    float4 v[kHead];
+    // LSEs and partial rows of the whole list are fetched at once, neither waiting for the other:
+    // one memory latency after the record's
+    constexpr int kList = kMergeFixInts - 1;
+    float l[kList];
+    float4 v[kList];
 #pragma unroll
-    for (int u = 0; u < kHead; ++u) row[u] = b + u < e ? (size_t)mrows[b + u] * q_heads + hd : 0;
-#pragma unroll
-    for (int u = 0; u < kHead; ++u) {
+    for (int u = 0; u < kList; ++u) {
       l[u] = -INFINITY;
       v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (b + u < e) {
-        l[u] = lse[row[u]];
-        v[u] = ((const float4*)part)[row[u] * 32 + c4];
+      if (rec[1 + u] >= 0) {
+        const size_t row = (size_t)rec[1 + u] * q_heads + hd;
+        l[u] = lse[row];
+        v[u] = ((const float4*)part)[row * 32 + c4];
       }
     }
     float M = -INFINITY;
 #pragma unroll
-    for (int u = 0; u < kHead; ++u) M = fmaxf(M, l[u]);
-    for (int jj = b + kHead; jj < e; ++jj) M = fmaxf(M, lse[(size_t)mrows[jj] * q_heads + hd]);
+    for (int u = 0; u < kList; ++u) M = fmaxf(M, l[u]);
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
     float wsum = 0.f;
     if (M > -INFINITY) {
 #pragma unroll
-      for (int u = 0; u < kHead; ++u) {
-        if (b + u < e) {
+      for (int u = 0; u < kList; ++u) {
+        if (rec[1 + u] >= 0) {
           const float w = expf(l[u] - M);
           acc.x += w * v[u].x; acc.y += w * v[u].y; acc.z += w * v[u].z; acc.w += w * v[u].w;
           wsum += w;
         }
-      }
-      for (int jj = b + kHead; jj < e; ++jj) {
-        const size_t r = (size_t)mrows[jj] * q_heads + hd;
-        const float w = expf(lse[r] - M);
-        const float4 x = ((const float4*)part)[r * 32 + c4];
-        acc.x += w * x.x; acc.y += w * x.y; acc.z += w * x.z; acc.w += w * x.w;
-        wsum += w;
       }
       const float inv = 1.f / wsum;
       acc.x *= inv; acc.y *= inv; acc.z *= inv; acc.w *= inv;
@@ -393,11 +383,11 @@ tl_status tl_merge(tl_plan* plan, const float* out_partial, const float* lse, vo
   if (n_short > 0) {
     const dim3 grid((unsigned)n_short, (unsigned)((plan->q_heads * 32 + 255) / 256)), block(256);
     if (out_is_bf16)
-      hipLaunchKernelGGL(lse_merge_kernel<true>, grid, block, 0, st, out_partial, lse, d.merge_ptr, d.merge_rows,
-                         d.merge_tok, out_dev, lse_out, plan->q_heads);
+      hipLaunchKernelGGL(lse_merge_kernel<true>, grid, block, 0, st, out_partial, lse, d.merge_fix, out_dev, lse_out,
+                         plan->q_heads);
     else
-      hipLaunchKernelGGL(lse_merge_kernel<false>, grid, block, 0, st, out_partial, lse, d.merge_ptr, d.merge_rows,
-                         d.merge_tok, out_dev, lse_out, plan->q_heads);
+      hipLaunchKernelGGL(lse_merge_kernel<false>, grid, block, 0, st, out_partial, lse, d.merge_fix, out_dev, lse_out,
+                         plan->q_heads);
   }
   if (n_long > 0) {
     // long merge lists (split-K): the sliced kernel, one workgroup per (token, head)

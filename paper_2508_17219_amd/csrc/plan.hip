@@ -507,6 +507,16 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
         for (int32_t t = 0; t < T; ++t)
           if (!tok_fused[t]) p->merge_rows[cur[t]++] = self_base + t;
     }
+    // the short lists once more as fixed records, so that the merge kernel gets a token's whole list with
+    // one load instead of three dependent ones
+    static_assert(kLongMergeList <= kMergeFixInts, "a short list and its token fit one record");
+    p->merge_fix.assign((size_t)p->n_merge_short * kMergeFixInts, -1);
+    for (int32_t i = 0; i < p->n_merge_short; ++i) {
+      const int32_t t = p->merge_tok[i];
+      int32_t* rec = &p->merge_fix[(size_t)i * kMergeFixInts];
+      rec[0] = t;
+      for (int32_t j = p->merge_ptr[t]; j < p->merge_ptr[t + 1]; ++j) rec[1 + j - p->merge_ptr[t]] = p->merge_rows[j];
+    }
 
     int64_t uniq_tok = 0;
     {
@@ -567,6 +577,7 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
       o.tile_lm = reserve(sizeof(float) * p->tile_lm.size());
       o.part_lm = reserve(sizeof(float) * p->part_lm.size());
       o.prior_rows = reserve(sizeof(int32_t) * p->prior_rows.size());
+      o.merge_fix = reserve(sizeof(int32_t) * p->merge_fix.size());
       p->blob_host.assign(total + 256, 0);
       auto fill = [&](size_t at, const void* src, size_t bytes) {
         if (bytes) memcpy(p->blob_host.data() + at, src, bytes);
@@ -587,6 +598,7 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
       fill(o.tile_lm, p->tile_lm.data(), sizeof(float) * p->tile_lm.size());
       fill(o.part_lm, p->part_lm.data(), sizeof(float) * p->part_lm.size());
       fill(o.prior_rows, p->prior_rows.data(), sizeof(int32_t) * p->prior_rows.size());
+      fill(o.merge_fix, p->merge_fix.data(), sizeof(int32_t) * p->merge_fix.size());
     }
   } catch (const std::bad_alloc&) {
     rc = TL_ENOMEM;

@@ -31,6 +31,7 @@ void set_error(const char* fmt, ...) __attribute__((format(printf, 1, 2)));
 
 constexpr int kHeadDim = 128;
 constexpr int kKvTile = 64;      // kv tokens per LDS tile of the row-tile kernel
+constexpr int kMergeFixInts = 8;   // ints of a short merge list's fixed record: the token, then up to 7 partial rows
 constexpr int kLongMergeList = 8;  // partials per token from which the merge deals the list to slices
 constexpr int kRowTile = 256;    // query rows (token x head-in-group) per workgroup
 constexpr int kUnitRows = 16;    // max rows per kv head of a split-K unit
@@ -90,6 +91,7 @@ struct tl_plan {
   std::vector<int32_t> item_row_base, item_tok_ptr, item_tokens, item_slot_ptr, item_slots;
   std::vector<int32_t> merge_ptr, merge_rows;
   std::vector<tl::Work> tiles, units, ctiles, ftiles;   // ftiles: fused rows (pool tiles + causal block in one pass)
+  std::vector<int32_t> merge_fix;  // the short lists again, one fixed record of 8 ints per token: {token, rows..., -1 padding}
   std::vector<int32_t> merge_tok;  // tokens that tl_merge writes (all but the fused ones): n_merge_short with short
                                    // lists first, then those with kLongMergeList or more partials
   int32_t n_merge_short = 0;
@@ -114,7 +116,7 @@ struct tl_plan {
   std::vector<char> blob_host;
   struct {
     size_t tiles, units, ctiles, ftiles, tok, slots, merge_ptr, merge_rows, tile_base, part_tile, merge_tok, single_tok,
-        tile_lm, part_lm, prior_rows, unit_lm;
+        tile_lm, part_lm, prior_rows, unit_lm, merge_fix;
   } off;
   void* blob_dev;                // hipMalloc'd copy of blob_host, or null
 };
@@ -128,6 +130,7 @@ struct PlanDev {
   const float *tile_lm, *part_lm;
   const int32_t* prior_rows;
   const float* unit_lm;
+  const int32_t* merge_fix;
 };
 inline PlanDev plan_dev(const tl_plan* p, const void* base) {
   const char* b = (const char*)base;
@@ -148,6 +151,7 @@ inline PlanDev plan_dev(const tl_plan* p, const void* base) {
   d.part_lm = (const float*)(b + p->off.part_lm);
   d.prior_rows = (const int32_t*)(b + p->off.prior_rows);
   d.unit_lm = (const float*)(b + p->off.unit_lm);
+  d.merge_fix = (const int32_t*)(b + p->off.merge_fix);
   return d;
 }
 
