@@ -39,13 +39,15 @@
 // sum of the unrounded fp32 values.  The kernel keeps the fp32 sum l and, beside it, a
 // correction d ~= sum(rounded) - sum(unrounded); O is divided by l + d, LSE = m + ln l.
 //  * careful path: d is exact (v_dot2c_f32_bf16 sums each packed pair as the matrix unit sees it);
-//  * fast path: a second exact sum would cost 7 % of the kernel's time (the dot instructions share
-//    the matrix pipeline), so each lane tracks the largest probability it has formed (one v_max3
-//    per pair, 2 %) and d takes that value's rounding error: with a fixed exponent reference the
-//    largest probability is a rounded number like any other (with a running maximum it would be
-//    exactly 1), and its rounding is what the error of a peaked row consists of.  What remains is
-//    the error of the other terms, sum_j w_j e_j (v_j - O) with |e_j| <= 2^-8: the same bound as a
-//    kernel that keeps a running maximum.
+//  * fast path: a second exact sum of every tile would cost 7 % of the kernel's time (the dot
+//    instructions share the matrix pipeline), so a tile gets its exact d only if it raised some
+//    lane's row sum by more than a sixteenth (one compare per tile; both blocks' packed
+//    probabilities are still in registers then).  That is every tile at the start of a phase and
+//    hardly any later on, unless a row is peaked: with a fixed exponent reference a dominant
+//    probability is a rounded number like any other (with a running maximum it would be exactly
+//    1), and its rounding is what the error of a peaked row consists of.  What remains is the
+//    error of terms from tiles that added little, sum_j w_j e_j (v_j - O) with |e_j| <= 2^-8 over
+//    those terms: no more than in a kernel that keeps a running maximum.
 #include <type_traits>
 
 #include "attn_common.h"
@@ -69,6 +71,7 @@ constexpr size_t kLdsBytes = (size_t)kBufs * (kKTile + kVTile) * sizeof(uint16_t
 constexpr float kRescaleLog2 = 8.0f;             // careful path: raise the maximum when exceeded by 2^8
 constexpr float kFastPathLimit = 1.152921504606846976e18f;  // 2^60
 constexpr int kDmaPerWave = 16 / kWaves;                  // direct-load instructions per wave per K (or V) tile
+constexpr float kExactCorrectionGrowth = 1.0625f;   // fast path: growth of a lane's row sum over one tile from which the tile's correction is exact
 constexpr int kDepth = 3;            // LDS operands in flight ahead of the MFMA that uses them (ring of kDepth + 1)
 
 // Lanes l and l^32 exchange x: returns {own, partner} in some order.  The swap instruction
@@ -420,9 +423,9 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
     dma_wait();
     __syncthreads();
 
-    float pm[kRG];                      // largest probability this lane has formed in this phase
+    float l_prev[kRG];                  // the lane's row sum before the current tile
 #pragma unroll
-    for (int rg = 0; rg < kRG; ++rg) pm[rg] = 0.f;
+    for (int rg = 0; rg < kRG; ++rg) l_prev[rg] = l_run[rg];
     f32x16 s0[kRG], s1[kRG];            // scores of block 0 / block 1 of a tile (then their probabilities)
     u32x4 p0[kRG][2], p1[kRG][2];       // packed probabilities (bf16 pairs)
     qk_block(lds_k, 0, s0);
@@ -525,16 +528,36 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
           u32x4 (&pp)[2] = step == 0 ? p0[rg] : p1[rg];
           if (r >= 1) l_run[rg] += s[r - 1];
           if (r >= 2 && (r & 1) == 0) set_pair(pp[(r - 2) >> 3], ((r - 2) & 7) >> 1, s[r - 2], s[r - 1]);
-          // the lane's largest probability, two elements per v_max3, in the slices without a convert
-          if (r == 1) pm[rg] = fmaxf(pm[rg], s[0]);
-          if (r >= 3 && (r & 1) == 1) pm[rg] = __builtin_fmaxf(__builtin_fmaxf(pm[rg], s[r - 2]), s[r - 1]);
-          if (r == 15) pm[rg] = fmaxf(pm[rg], s[15]);
           if (r == 15) {
             l_run[rg] += s[15];
             set_pair(pp[1], 3, s[14], s[15]);
           }
           __builtin_amdgcn_sched_barrier(0);
         }
+      }
+      // A tile that raised some lane's row sum by more than a sixteenth gets its exact correction: the sum
+      // of its 32 probabilities per lane as rounded (both blocks' packed values are still in registers)
+      // minus what they added to the row sum.  Rare after the first few tiles of a phase.
+      {
+        bool big = false;
+#pragma unroll
+        for (int rg = 0; rg < kRG; ++rg) big = big || l_run[rg] > kExactCorrectionGrowth * l_prev[rg];
+        if (__builtin_amdgcn_ballot_w64(big) != 0) {
+#pragma unroll
+          for (int rg = 0; rg < kRG; ++rg) {
+            float lr = 0.f;
+#pragma unroll
+            for (int sp = 0; sp < 2; ++sp)
+#pragma unroll
+              for (int i = 0; i < 4; ++i) {
+                lr = add_bf16_pair(lr, p0[rg][sp][i]);
+                lr = add_bf16_pair(lr, p1[rg][sp][i]);
+              }
+            lr_run[rg] += lr - (l_run[rg] - l_prev[rg]);
+          }
+        }
+#pragma unroll
+        for (int rg = 0; rg < kRG; ++rg) l_prev[rg] = l_run[rg];
       }
       // this wave's share of K(t+2) / V(t+1) has landed; after the barrier everybody's has, and
       // everybody is done reading K(t) block 1 and V(t-1), the buffers the next loads overwrite
@@ -568,14 +591,6 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2 / kR
       pv_block(lds_v + ((n_full - 1) % kBufs) * kVTile, 1, pl);
     }
 
-    // what rounding did to the lane's largest probability goes into the correction of the row sum
-#pragma unroll
-    for (int rg = 0; rg < kRG; ++rg) {
-      typedef float f32x2_t __attribute__((ext_vector_type(2)));
-      typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
-      const unsigned w = __builtin_bit_cast(unsigned, __builtin_convertvector(f32x2_t{pm[rg], 0.f}, bf16x2_t));
-      lr_run[rg] += __uint_as_float(w << 16) - pm[rg];
-    }
     // did the fixed reference hold?  (row sums are sums of positive terms: one huge term shows)
     bool bad = false;
 #pragma unroll
