@@ -170,8 +170,9 @@ tl_status tl_pool_fills(const tl_pool* pool, const int32_t* slots, int32_t n, in
 tl_status tl_pool_used(const tl_pool* pool, int32_t* n_used);
 
 /* Copy the listed slots, whole (seg_len tokens each), to contiguous device buffers
- * k_out_dev/v_out_dev [n, seg_len, kv_heads, head_dim].  slots: host [n].  For
- * verification of slot addressing; bit-exact. */
+ * k_out_dev/v_out_dev [n, seg_len, kv_heads, head_dim].  slots: host [n] (read before the call
+ * returns).  Enqueued on `stream` (512 slots per launch); allocates nothing and does not wait.
+ * For verification of slot addressing; bit-exact. */
 tl_status tl_pool_gather(tl_pool* pool, const int32_t* slots, int32_t n, void* k_out_dev, void* v_out_dev,
                          void* stream);
 

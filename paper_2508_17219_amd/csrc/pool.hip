@@ -23,12 +23,19 @@ void set_error(const char* fmt, ...) {
 
 int get_option_vread() { return g_opt_vread; }
 
-// out[(i, :)] = pool[(slots[i], :)], slot_elems16 uint4 per slot; one block column per slot.
-__global__ void gather_slots_kernel(uint4* __restrict__ out, const uint4* __restrict__ pool,
-                                    const int32_t* __restrict__ slots, size_t slot16) {
-  const int32_t s = slots[blockIdx.y];
+// Slot numbers of one gather launch: they travel in the kernel arguments (no device buffer to
+// allocate, fill and free).
+constexpr int kGatherPerLaunch = 512;
+struct GatherSlots {
+  int32_t slot[kGatherPerLaunch];
+};
+
+// out[(first + i, :)] = pool[(slots.slot[i], :)], slot16 uint4 per slot; one block column per slot.
+__global__ void gather_slots_kernel(uint4* __restrict__ out, const uint4* __restrict__ pool, const GatherSlots slots,
+                                    int first, size_t slot16) {
+  const int32_t s = slots.slot[blockIdx.y];
   const uint4* src = pool + (size_t)s * slot16;
-  uint4* dst = out + (size_t)blockIdx.y * slot16;
+  uint4* dst = out + (size_t)(first + blockIdx.y) * slot16;
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < slot16; i += (size_t)gridDim.x * blockDim.x)
     dst[i] = src[i];
 }
@@ -446,22 +453,19 @@ tl_status tl_pool_used(const tl_pool* pool, int32_t* n_used) {
 tl_status tl_pool_gather(tl_pool* pool, const int32_t* slots, int32_t n, void* k_out_dev, void* v_out_dev, void* stream) {
   if (!pool || n < 0 || (n > 0 && (!slots || !k_out_dev || !v_out_dev))) TL_FAIL(TL_EINVAL, "tl_pool_gather: bad argument");
   if (n == 0) return TL_OK;
-  if (n > 65535) TL_FAIL(TL_EINVAL, "tl_pool_gather: at most 65535 slots per call");
   for (int32_t i = 0; i < n; ++i)
     if (slots[i] < 0 || slots[i] >= pool->n_slots) TL_FAIL(TL_EINVAL, "tl_pool_gather: slot %d out of range", slots[i]);
   hipStream_t st = (hipStream_t)stream;
-  int32_t* d_slots = nullptr;
-  TL_HIP(hipMalloc((void**)&d_slots, sizeof(int32_t) * (size_t)n));
-  hipError_t e = hipMemcpyAsync(d_slots, slots, sizeof(int32_t) * (size_t)n, hipMemcpyHostToDevice, st);
-  if (e == hipSuccess) {
-    const size_t slot16 = (size_t)pool->seg_len * pool->kv_heads * pool->head_dim * 2 / 16;
-    dim3 grid((unsigned)(slot16 / 256 > 64 ? 64 : (slot16 + 255) / 256), (unsigned)n);
-    hipLaunchKernelGGL(gather_slots_kernel, grid, dim3(256), 0, st, (uint4*)k_out_dev, (const uint4*)pool->k_dev, d_slots, slot16);
-    hipLaunchKernelGGL(gather_slots_kernel, grid, dim3(256), 0, st, (uint4*)v_out_dev, (const uint4*)pool->v_dev, d_slots, slot16);
-    e = hipGetLastError();
-    if (e == hipSuccess) e = hipStreamSynchronize(st);   // d_slots is freed below
+  const size_t slot16 = (size_t)pool->seg_len * pool->kv_heads * pool->head_dim * 2 / 16;
+  for (int32_t first = 0; first < n; first += kGatherPerLaunch) {
+    const int32_t m = n - first < kGatherPerLaunch ? n - first : kGatherPerLaunch;
+    GatherSlots gs;
+    for (int32_t i = 0; i < kGatherPerLaunch; ++i) gs.slot[i] = i < m ? slots[first + i] : 0;
+    const dim3 grid((unsigned)(slot16 / 256 > 64 ? 64 : (slot16 + 255) / 256), (unsigned)m);
+    hipLaunchKernelGGL(gather_slots_kernel, grid, dim3(256), 0, st, (uint4*)k_out_dev, (const uint4*)pool->k_dev, gs, first, slot16);
+    hipLaunchKernelGGL(gather_slots_kernel, grid, dim3(256), 0, st, (uint4*)v_out_dev, (const uint4*)pool->v_dev, gs, first, slot16);
   }
-  (void)hipFree(d_slots);
+  const hipError_t e = hipGetLastError();
   if (e != hipSuccess) TL_FAIL(TL_EHIP, "tl_pool_gather: %s", hipGetErrorString(e));
   return TL_OK;
 }
