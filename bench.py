@@ -173,12 +173,15 @@ def _probe():
         lib = C.CDLL(_build.PROBE_LIB)
         lib.tlprobe_mfma.restype = C.c_int32
         lib.tlprobe_mfma.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.POINTER(C.c_double), C.c_void_p]
+        lib.tlprobe_mfma_kind.restype = C.c_int32
+        lib.tlprobe_mfma_kind.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.POINTER(C.c_double), C.c_void_p]
         _probe_lib = lib
     return _probe_lib
 
 
-def mfma_sustained(torch, random_operands, iters=2000, reps=3):
-    """TFLOP/s of the matrix unit alone (no memory, LDS or vector work), best of `reps` launches."""
+def mfma_sustained(torch, random_operands, iters=2000, reps=3, kind=None, idle_every=0, times=None):
+    """TFLOP/s of the matrix unit alone (no memory, LDS or vector work), best of `reps` launches.
+    kind/idle_every select one of the probe's operand and throttling variants instead."""
     import ctypes as C
     lib = _probe()
     scratch = torch.zeros(16, dtype=torch.float32, device="cuda")
@@ -188,11 +191,16 @@ def mfma_sustained(torch, random_operands, iters=2000, reps=3):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         fl = C.c_double(0.0)
         e0.record()
-        rc = lib.tlprobe_mfma(int(bool(random_operands)), iters, scratch.data_ptr(), C.byref(fl), st)
+        if kind is None:
+            rc = lib.tlprobe_mfma(int(bool(random_operands)), iters, scratch.data_ptr(), C.byref(fl), st)
+        else:
+            rc = lib.tlprobe_mfma_kind(kind, idle_every, iters, scratch.data_ptr(), C.byref(fl), st)
         e1.record()
         torch.cuda.synchronize()
         if rc != 0:
             raise RuntimeError("tlprobe_mfma failed (%d)" % rc)
+        if times is not None:
+            times.append(e0.elapsed_time(e1))
         best = max(best, fl.value / (e0.elapsed_time(e1) * 1e-3) / 1e12)
     return best
 
@@ -204,8 +212,21 @@ def probe_mfma(torch, iters=8000, reps=5):
     for name, rnd in (("constant_operands", False), ("changing_random_operands", True)):
         best = mfma_sustained(torch, rnd, iters, reps)
         out[name] = {"TFLOP/s": best, "frac_of_peak": best / PEAK_BF16_TFLOPS}
+    # what the power of the matrix unit depends on: the values inside an instruction or the change between instructions
+    kinds = {}
+    for name, kind in (("random_operands_that_never_change", 0), ("plus_minus_one_random_signs", 1),
+                       ("random_mantissas_one_exponent_positive", 2), ("A_changing_B_one", 3), ("A_one_B_changing", 4),
+                       ("both_changing", 5)):
+        kinds[name] = round(mfma_sustained(torch, True, 3000, 3, kind=kind), 1)
+    # the same instructions on the same operands made to take more cycles (the wave idles after every n-th MFMA)
+    throttled = []
+    for idle in (32, 16, 8, 4, 2):
+        ts = []
+        mfma_sustained(torch, True, 3000, 4, kind=5, idle_every=idle, times=ts)
+        throttled.append({"idle_after_every": idle, "ms": round(min(ts[1:]), 4)})
     print(json.dumps({"probe": "mfma_f32_32x32x16_bf16 only, 1024 workgroups x 8 waves, %d x 32 instructions per wave, "
-                               "best of %d launches" % (iters, reps), "peak_TFLOP/s": PEAK_BF16_TFLOPS, **out}))
+                               "best of %d launches" % (iters, reps), "peak_TFLOP/s": PEAK_BF16_TFLOPS, **out,
+                      "operand_kinds_TFLOP/s": kinds, "throttled_one_wave_per_simd": throttled}))
 
 
 def run_session_loop(steps, warmup, torch, B, wl, per_chain_append=False):
