@@ -175,6 +175,8 @@ def _probe():
         lib.tlprobe_mfma.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.POINTER(C.c_double), C.c_void_p]
         lib.tlprobe_mfma_kind.restype = C.c_int32
         lib.tlprobe_mfma_kind.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.POINTER(C.c_double), C.c_void_p]
+        lib.tlprobe_issue.restype = C.c_int32
+        lib.tlprobe_issue.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_double)]
         _probe_lib = lib
     return _probe_lib
 
@@ -227,6 +229,27 @@ def probe_mfma(torch, iters=8000, reps=5):
     print(json.dumps({"probe": "mfma_f32_32x32x16_bf16 only, 1024 workgroups x 8 waves, %d x 32 instructions per wave, "
                                "best of %d launches" % (iters, reps), "peak_TFLOP/s": PEAK_BF16_TFLOPS, **out,
                       "operand_kinds_TFLOP/s": kinds, "throttled_one_wave_per_simd": throttled}))
+
+
+def probe_issue(torch, iters=20000):
+    """Issue cycles of an MFMA and of the softmax's vector instructions on one SIMD, alone and together, with one
+    and two waves per SIMD (cycle counter per wave; a group = a quarter of a loop iteration)."""
+    import ctypes as C
+    lib = _probe()
+    torch.zeros(1, device="cuda")
+    rows = []
+    for name, mode, waves in (("8 v_fma_f32", 0, 1), ("8 v_add_f32", 1, 1), ("8 v_exp_f32", 2, 1), ("8 v_cvt_pk_bf16_f32", 3, 1),
+                              ("8 v_max3_f32", 4, 1), ("8 v_perm_b32", 5, 1), ("1 MFMA 32x32x16 bf16", 10, 1), ("1 MFMA", 10, 2),
+                              ("1 MFMA + one element's fma, exp, add, half a convert", 11, 1), ("the same", 11, 2),
+                              ("1 MFMA + two elements' softmax", 12, 1), ("the same", 12, 2),
+                              ("waves 0-3: 1 MFMA; waves 4-7: 8 v_fma_f32", 20, 2)):
+        a, b = C.c_double(0.0), C.c_double(0.0)
+        rc = lib.tlprobe_issue(mode, waves, iters, C.byref(a), C.byref(b))
+        if rc != 0:
+            raise RuntimeError("tlprobe_issue failed (%d)" % rc)
+        rows.append({"per_group": name, "waves_per_simd": waves, "cycles_waves_0_3": round(a.value, 1),
+                     "cycles_waves_4_7": round(b.value, 1) if waves == 2 else None})
+    print(json.dumps({"probe": "issue cycles per group on one SIMD (256 workgroups, one per CU; loop overhead included)", "rows": rows}))
 
 
 def run_session_loop(steps, warmup, torch, B, wl, per_chain_append=False):
@@ -428,6 +451,8 @@ def main():
                     help="also time the step replayed from a HIP graph (reported as graph_ms_per_step)")
     ap.add_argument("--probe-mfma", action="store_true",
                     help="only run the MFMA-only probe kernel (constant and changing operands) and exit")
+    ap.add_argument("--probe-issue", action="store_true",
+                    help="only run the issue-cycle microbenchmark (MFMA and softmax vector instructions on one SIMD) and exit")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a 1 GiB device copy (to scale rocprofv3 FETCH_SIZE/WRITE_SIZE) and exit")
     args = ap.parse_args()
@@ -444,6 +469,9 @@ def main():
     from paper_2508_17219_amd import build as _build
     _build.ensure_built(verbose=False)       # builds only if no library is there
     B.load_library()
+    if args.probe_issue:
+        probe_issue(torch)
+        return
     if args.probe_mfma:
         probe_mfma(torch)
         return

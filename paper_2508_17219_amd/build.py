@@ -50,7 +50,7 @@ def build(verbose: bool = True, extra_flags=()) -> str:
 
 
 def build_probe(verbose: bool = True) -> str:
-    return _hipcc([os.path.join(HERE, "probe", "mfma_probe.hip")], PROBE_LIB, verbose)
+    return _hipcc([os.path.join(HERE, "probe", "mfma_probe.hip"), os.path.join(HERE, "probe", "issue_probe.hip")], PROBE_LIB, verbose)
 
 
 def ensure_built(verbose: bool = True) -> str:
