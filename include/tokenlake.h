@@ -146,7 +146,10 @@ tl_status tl_pool_evict_lru(tl_pool* pool, uint64_t* evicted_id);
  * request's list from the root, makes the nodes that are missing -- a node is a segment id under a
  * given parent; the same id under two prefixes is two nodes of one slot -- and adds the request's
  * new tokens to the load of every node on the way, so a node is never more loaded than its parent.
- * tl_pool_evict_lru removes the evicted segment's nodes with everything below them.
+ * tl_pool_evict_lru removes the evicted segment's nodes with everything below them.  Lists that
+ * follow no tree (the same segments in ever new orders) make new nodes with every batch: when the
+ * tree has grown beyond 16 nodes per slot of the pool, the next tl_plan_create clears it and the
+ * cumulative loads start over.
  *
  * tl_pool_hot_segments: up to max_n nodes by decreasing cumulative load (equal loads: the older node
  * first, so a parent precedes its children), found by a best-first search from the root that looks

@@ -131,6 +131,9 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
     // every request with a list, in order, front to back; `grouped` requests are those the planner
     // may put together (new tokens, not set aside for the one-pass kernel)
     PrefixTree& tree = pool->tree;
+    // Lists that follow no tree (the same segments in ever new orders) would add nodes batch after batch:
+    // beyond kTreeNodesPerSlot nodes per slot the tree, a record of loads, starts over.
+    if ((int64_t)tree.size() > (int64_t)kTreeNodesPerSlot * pool->n_slots) tree.reset(pool->n_slots);
     tree.begin_batch();
     std::vector<int32_t> path(n_entries);          // tree node of every list entry
     auto is_live = [&](int32_t r) { return ntok_of(r) > 0 && len_of(r) > 0 && !fused[r]; };

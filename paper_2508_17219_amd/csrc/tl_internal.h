@@ -31,6 +31,7 @@ void set_error(const char* fmt, ...) __attribute__((format(printf, 1, 2)));
 
 constexpr int kHeadDim = 128;
 constexpr int kKvTile = 64;      // kv tokens per LDS tile of the row-tile kernel
+constexpr int kTreeNodesPerSlot = 16;   // the pool's prefix tree is cleared when it outgrows this many nodes per slot
 constexpr int kMergeFixInts = 8;   // ints of a short merge list's fixed record: the token, then up to 7 partial rows
 constexpr int kLongMergeList = 8;  // partials per token from which the merge deals the list to slices
 constexpr int kRowTile = 256;    // query rows (token x head-in-group) per workgroup

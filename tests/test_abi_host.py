@@ -703,3 +703,28 @@ def test_binding_checks_tensor_sizes_and_types_against_the_plan():
         B.tl_fused_attn(pool, plan, q, kn, kn, b.scale, out[:T - 1], False, None)
     B.tl_plan_destroy(plan)
     B.tl_pool_destroy(pool)
+
+
+def test_prefix_tree_starts_over_when_lists_follow_no_tree():
+    """Lists that name the same few segments in ever new orders make new tree nodes with every batch; the
+    pool clears its tree when it has outgrown 16 nodes per slot, so its size stays bounded, and plans keep
+    covering every pair."""
+    rng = np.random.default_rng(5)
+    n_slots, C = 8, 64
+    pool = B.tl_pool_create(n_slots, C, 1, 128, FAKE_K, FAKE_V)
+    ids = np.arange(n_slots, dtype=np.uint64) + 10
+    B.tl_pool_adopt(pool, ids, np.arange(n_slots), np.full(n_slots, C))
+    biggest = 0
+    for step in range(60):
+        lists = [rng.permutation(ids)[:6].tolist() for _ in range(4)]
+        row_ptr = np.arange(5, dtype=np.int32) * 3
+        seg_ptr = np.arange(5, dtype=np.int32) * 6
+        plan = B.tl_plan_create(pool, 4, row_ptr, seg_ptr, np.array([x for l in lists for x in l], np.uint64), B.TL_PLAN_SELF_BLOCK)
+        total = B.tl_pool_prefix_tree(pool, 1)[3]
+        assert total <= 16 * n_slots + 24, (step, total)      # at most one batch's nodes over the limit
+        biggest = max(biggest, total)
+        slots, loads = B.tl_plan_hot_slots(plan, 100)
+        assert len(slots) > 0 and loads[0] <= 12
+        B.tl_plan_destroy(plan)
+    assert biggest > 16 * n_slots - 24                         # the limit was reached, i.e. the tree did start over
+    B.tl_pool_destroy(pool)
