@@ -415,6 +415,11 @@ tl_status tl_plan_create(tl_plan** out, const tl_pool* pool, int32_t q_heads, in
             p->tiles.push_back(Work{tok_base + t0, std::min(tok_tile, n_tok - t0), row_cursor + t0, slot_base, (int32_t)p->item_slots.size() - slot_base,
                                     full_off, n_full, part_off, n_part, 0, 0});
         }
+        if ((int64_t)row_cursor + n_tok + T > INT32_MAX) {      // partial rows are numbered in 32 bits
+          set_error("tl_plan_create: more than 2^31 partial rows");
+          delete p;
+          return TL_EINVAL;
+        }
         row_cursor += n_tok;
       }
     }
