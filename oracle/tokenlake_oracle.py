@@ -300,6 +300,35 @@ class PrefixTree:
         return len(self.load)
 
 
+FNV64_OFFSET = 0xCBF29CE484222325
+FNV64_PRIME = 0x100000001B3
+
+
+def fnv1a64(data: bytes, start: int = FNV64_OFFSET) -> int:
+    """64-bit FNV-1a of a byte string (the published algorithm: xor the byte in, multiply by the prime,
+    modulo 2^64), from the given starting value."""
+    h = start
+    for b in data:
+        h = ((h ^ b) * FNV64_PRIME) & 0xFFFFFFFFFFFFFFFF
+    return h
+
+
+def content_segment_ids(tokens, seg_len: int, salt: int = 0):
+    """Segment ids derived from what the segments hold (paper Section 3.1: the global prefix tree is keyed
+    by the token sequence, so that requests name the same cached segment exactly as far as their prompts
+    agree).  Segment k of a sequence covers tokens [k seg_len, min(n, (k+1) seg_len)); its id is the FNV-1a
+    hash of ALL tokens up to its end (each token as four little-endian bytes), started from the offset basis
+    xor `salt` (one salt per model / layer group).  Written as that definition: every id from scratch."""
+    toks = [int(t) for t in tokens]
+    n = len(toks)
+    ids = []
+    for k in range((n + seg_len - 1) // seg_len):
+        end = min(n, (k + 1) * seg_len)
+        data = b"".join((t & 0xFFFFFFFF).to_bytes(4, "little") for t in toks[:end])
+        ids.append(fnv1a64(data, FNV64_OFFSET ^ (salt & 0xFFFFFFFFFFFFFFFF)))
+    return ids
+
+
 def append_rows(pool_k_bits, pool_v_bits, table: SlotTable, tail_id, new_ids, k_rows_bits, v_rows_bits):
     """Store new token rows [n, kv_heads, head_dim] (bf16 bit patterns) at the end of a chain
     of segments: `table.append` decides where each row goes, the rows are copied there.

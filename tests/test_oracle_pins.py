@@ -558,3 +558,33 @@ def test_prefix_tree_hand_case_and_invariants():
         before = dict(t.load)
         t.evict(victim)
         assert set(t.load) == {p for p in before if victim not in p}
+
+
+def test_content_segment_ids_follow_the_published_hash_and_the_prefix_rule():
+    """Pins of the content-derived ids (Section 3.1, tree keyed by tokens): the byte hash against the
+    published FNV-1a test vectors; two sequences get equal ids exactly for the whole segments of their common
+    prefix; an id depends on every earlier token; a partly filled last segment has an id of its own."""
+    assert orc.fnv1a64(b"") == 0xCBF29CE484222325
+    assert orc.fnv1a64(b"a") == 0xAF63DC4C8601EC8C
+    assert orc.fnv1a64(b"foobar") == 0x85944171F73967E8
+    # tokens are hashed as 4 little-endian bytes each: one token 0x61 is the bytes "a\0\0\0"
+    assert orc.content_segment_ids([0x61], 4) == [orc.fnv1a64(b"a\x00\x00\x00")]
+    assert orc.content_segment_ids([0x6F6F66, 0x726162], 2) == [orc.fnv1a64(b"foo\x00bar\x00")]
+    rng = np.random.default_rng(8)
+    for case in range(20):
+        C = int(rng.choice([1, 2, 3, 8]))
+        a = rng.integers(0, 50000, size=int(rng.integers(0, 40))).tolist()
+        lcp = int(rng.integers(0, len(a) + 1))
+        b = a[:lcp] + rng.integers(50000, 60000, size=int(rng.integers(1, 20))).tolist()     # differs from a at position lcp
+        ia, ib = orc.content_segment_ids(a, C), orc.content_segment_ids(b, C)
+        assert len(ia) == (len(a) + C - 1) // C and len(ib) == (len(b) + C - 1) // C
+        same = lcp // C                                    # whole segments inside the common prefix
+        assert ia[:same] == ib[:same]
+        assert all(x != y for x, y in zip(ia[same:], ib[same:]))          # (a 64-bit collision is not expected here)
+        assert len(set(ia)) == len(ia)
+        if a:
+            c = [a[0] ^ 1] + a[1:]
+            assert all(x != y for x, y in zip(ia, orc.content_segment_ids(c, C)))
+            assert orc.content_segment_ids(a, C, salt=7) != ia
+    # a partly filled tail: the id of [1, 2, 3] in segments of 2 is (hash of 1 2), (hash of 1 2 3)
+    assert orc.content_segment_ids([1, 2, 3], 2)[1] == orc.content_segment_ids([1, 2, 3], 3)[0]
