@@ -381,6 +381,19 @@ tl_status tl_model_cache_load(double d, const int64_t* prefix_len, const int64_t
                               int32_t n_gpus, double mem_bw, double flops, double t_ideal, double* traffic_out,
                               double* flops_out, double* load_out);
 
+/* ------------------------------------------------------------------------------------
+ * Segment ids from token content (Section 3.1: the global prefix tree is keyed by the token
+ * sequence, so requests name the same cached segment exactly as far as their prompts agree).
+ * Segment k of a sequence covers tokens [k seg_len, min(n_tokens, (k+1) seg_len)); its id is the
+ * 64-bit FNV-1a hash of all tokens up to its end, each token as four little-endian bytes,
+ * started from the offset basis xor `salt`.  Two sequences get equal ids for the whole segments
+ * of their common prefix and (but for hash collisions) different ids from there on; a partly
+ * filled last segment has an id of its own.  tokens: host [n_tokens]; ids_out: host
+ * [ceil(n_tokens / seg_len)].  Host arithmetic, bit-exact.  TL_EINVAL for seg_len <= 0,
+ * negative n_tokens or a null array that is needed.
+ * ------------------------------------------------------------------------------------ */
+tl_status tl_segment_ids(const int32_t* tokens, int64_t n_tokens, int32_t seg_len, uint64_t salt, uint64_t* ids_out);
+
 #ifdef __cplusplus
 }
 #endif

@@ -72,6 +72,7 @@ _SIGNATURES = {
     "tl_model_comm_time": (_I32, [_F64, _F64, _F64, _PF64]),
     "tl_model_segment_threshold": (_I32, [_F64, _F64, _F64, _F64, _F64, _F64, _PF64]),
     "tl_model_cache_load": (_I32, [_F64, _P, _P, _I32, _I32, _F64, _F64, _F64, _PF64, _PF64, _PF64]),
+    "tl_segment_ids": (_I32, [_P, C.c_int64, _I32, C.c_uint64, _P]),
 }
 EXPORTED = tuple(_SIGNATURES)
 
@@ -390,3 +391,13 @@ def tl_model_cache_load(d: float, prefix_len, input_len, n_gpus: int, mem_bw: fl
     _check(load_library().tl_model_cache_load(d, pl.ctypes.data if len(pl) else None, il.ctypes.data if len(il) else None,
                                               len(pl), n_gpus, mem_bw, flops, t_ideal, C.byref(m), C.byref(f), C.byref(load)))
     return m.value, f.value, load.value
+
+
+def tl_segment_ids(tokens, seg_len: int, salt: int = 0) -> np.ndarray:
+    """Content-derived ids of the segments of a token sequence (uint64, one per started segment)."""
+    t = _host(tokens, np.int32)
+    n_ids = (len(t) + seg_len - 1) // seg_len if seg_len > 0 else 0
+    ids = np.zeros(n_ids, np.uint64)
+    _check(load_library().tl_segment_ids(t.ctypes.data if len(t) else None, len(t), seg_len, salt & 0xFFFFFFFFFFFFFFFF,
+                                         ids.ctypes.data if n_ids else None))
+    return ids

@@ -75,4 +75,18 @@ tl_status tl_model_cache_load(double d, const int64_t* prefix_len, const int64_t
   return TL_OK;
 }
 
+// Content-derived segment ids: one pass over the tokens, the hash state carried from segment to segment
+// (FNV-1a is sequential, so the running value at a segment's end is the hash of everything before it).
+tl_status tl_segment_ids(const int32_t* tokens, int64_t n_tokens, int32_t seg_len, uint64_t salt, uint64_t* ids_out) {
+  if (seg_len <= 0 || n_tokens < 0) TL_FAIL(TL_EINVAL, "tl_segment_ids: seg_len must be positive, n_tokens non-negative");
+  if (n_tokens > 0 && (!tokens || !ids_out)) TL_FAIL(TL_EINVAL, "tl_segment_ids: null argument");
+  uint64_t h = 0xCBF29CE484222325ull ^ salt;
+  for (int64_t i = 0; i < n_tokens; ++i) {
+    const uint32_t t = (uint32_t)tokens[i];
+    for (int b = 0; b < 4; ++b) h = (h ^ ((t >> (8 * b)) & 0xFFu)) * 0x100000001B3ull;
+    if ((i + 1) % seg_len == 0 || i + 1 == n_tokens) ids_out[i / seg_len] = h;
+  }
+  return TL_OK;
+}
+
 }  // extern "C"

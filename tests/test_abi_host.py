@@ -728,3 +728,40 @@ def test_prefix_tree_starts_over_when_lists_follow_no_tree():
         B.tl_plan_destroy(plan)
     assert biggest > 16 * n_slots - 24                         # the limit was reached, i.e. the tree did start over
     B.tl_pool_destroy(pool)
+
+
+def test_segment_ids_from_tokens_equal_the_oracles_and_feed_the_planner():
+    """tl_segment_ids against the oracle's from-scratch definition, bit for bit, on random sequences
+    (negative token values, empty sequences, partly filled tails, salts); then two prompts that agree in
+    their first 2.5 segments get ids that share two slots in the pool and one shared run in the plan."""
+    rng = np.random.default_rng(31)
+    for case in range(40):
+        C_ = int(rng.choice([1, 2, 5, 16, 64]))
+        toks = rng.integers(-2**31, 2**31, size=int(rng.integers(0, 300)), dtype=np.int64).astype(np.int32)
+        salt = int(rng.integers(0, 2**63)) if case % 2 else 0
+        got = B.tl_segment_ids(toks, C_, salt)
+        assert got.dtype == np.uint64 and got.tolist() == orc.content_segment_ids(toks.tolist(), C_, salt)
+    with pytest.raises(B.TokenLakeError):
+        B.tl_segment_ids([1, 2, 3], 0)
+    C_ = 64
+    a = rng.integers(0, 32000, size=4 * C_).tolist()
+    b = a[:2 * C_ + C_ // 2] + rng.integers(0, 32000, size=2 * C_).tolist()
+    ia, ib = B.tl_segment_ids(a, C_), B.tl_segment_ids(b, C_)
+    assert ia[:2].tolist() == ib[:2].tolist() and ia[2] != ib[2]
+    pool = B.tl_pool_create(16, C_, 1, 128, FAKE_K, FAKE_V)
+    ids = np.unique(np.concatenate([ia, ib]))
+    assert len(ids) == len(ia) + len(ib) - 2                       # one copy of the two shared segments
+    last_fill = (len(b) - 1) % C_ + 1
+    fills = np.array([last_fill if i == ib[-1] else C_ for i in ids], np.int32)
+    B.tl_pool_adopt(pool, ids, np.arange(len(ids)), fills)
+    lists = [ia.tolist(), ib.tolist()]
+    plan = B.tl_plan_create(pool, 4, [0, 20, 40], [0, len(ia), len(ia) + len(ib)], np.array(lists[0] + lists[1], np.uint64),
+                            B.TL_PLAN_SELF_BLOCK)
+    ex = B.tl_plan_export(plan)
+    items = [(ex["item_slots"][ex["item_slot_ptr"][i]:ex["item_slot_ptr"][i + 1]].tolist(),
+              sorted(set(ex["item_tokens"][ex["item_tok_ptr"][i]:ex["item_tok_ptr"][i + 1]].tolist())))
+             for i in range(len(ex["item_row_base"]))]
+    shared = [it for it in items if len(it[1]) == 40]
+    assert len(shared) == 1 and shared[0][0] == B.tl_pool_lookup(pool, ia[:2]).tolist()     # the common two segments, read once for both
+    B.tl_plan_destroy(plan)
+    B.tl_pool_destroy(pool)
