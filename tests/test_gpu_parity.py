@@ -1197,6 +1197,44 @@ def test_random_batches_against_the_oracle():
             run.close()
 
 
+def test_random_batches_with_peaked_scores_and_offset_values():
+    """The same kind of random batches with what makes rounding show: keys scaled by 4 or 8 (a few keys
+    dominate a row), per-segment V offsets of up to +-3 (|O| up to 7), segments of 256 tokens that are
+    mostly full (the row-tile kernel's pipelined path), lists of up to 12 segments; every plan mode,
+    every row against the oracle."""
+    _say("random batches, peaked and offset")
+    rng = np.random.default_rng(4242)
+    for case in range(10):
+        seg_len = int(rng.choice([64, 128, 256]))
+        hkv = int(rng.choice([1, 2]))
+        g = int(rng.choice([1, 3, 4, 7, 8]))
+        n_req = int(rng.integers(2, 6))
+        n_ids = int(rng.integers(6, 24))
+        stem = rng.permutation(n_ids)[:int(rng.integers(1, 5))].tolist()
+        lists, ntok = [], []
+        for r in range(n_req):
+            own = rng.integers(0, n_ids, size=int(rng.integers(0, 9))).tolist()
+            lists.append(([] if rng.random() < 0.2 else stem[:int(rng.integers(0, len(stem) + 1))]) + own)
+            ntok.append(int(rng.choice([0, 1, 5, 40, 150, 530 // g + 1, 700 // g])))
+        if sum(ntok) == 0:
+            ntok[0] = 7
+        ids = sorted(set(x for l in lists for x in l)) or [0]
+        fills = {i: (seg_len if rng.random() < 0.8 else int(rng.integers(1, seg_len + 1))) for i in ids}
+        b = wl.Batch(name="peaked%d" % case, seed=700 + case, q_heads=hkv * g, kv_heads=hkv, seg_len=seg_len, n_slots=32,
+                     req_row_ptr=np.concatenate([[0], np.cumsum(ntok)]).astype(np.int32),
+                     req_seg_ptr=np.concatenate([[0], np.cumsum([len(l) for l in lists])]).astype(np.int32),
+                     seg_ids=np.array([x for l in lists for x in l], dtype=np.uint64),
+                     pool_ids=np.array(ids, dtype=np.uint64),
+                     pool_slots=rng.permutation(32)[:len(ids)].astype(np.int32),
+                     pool_fills=np.array([fills[i] for i in ids], dtype=np.int32),
+                     k_gain=float(rng.choice([4.0, 8.0])), v_offset_mod=int(rng.choice([3, 7])))
+        for kw in (dict(), dict(fuse=True), dict(flags=B.TL_PLAN_SELF_BLOCK | B.TL_PLAN_NO_SHARING, split_segments=1),
+                   dict(flags=B.TL_PLAN_SELF_BLOCK | B.TL_PLAN_FUSE_TAILS, compute_units=0)):
+            run = H.run_gpu(b, **kw)
+            _check_all_requests(run)
+            run.close()
+
+
 # ---- the step as a HIP graph ----------------------------------------------------------------------
 @pytest.mark.parametrize("fuse", [False, True])
 def test_step_replays_from_a_hip_graph(fuse):
